@@ -1,0 +1,139 @@
+/*
+ * specvocab.h -- C ABI of the SpecVocab draft-step library for AMD MI355X (gfx950).
+ *
+ * The library computes the draft model's output distribution over a per-step speculative
+ * vocabulary (arxiv 2602.13836, Section 3): it scores the whole vocabulary with a low-rank
+ * selector and keeps the k best tokens (Section 3.3, Steps 1-2), computes the exact logits of
+ * those k tokens only by reading their rows of the output embedding once (Section 3.3, Step 3,
+ * and "Custom kernel" in Section 3.5), and turns them into the subset softmax and the top-kd
+ * draft tokens.  A full-vocabulary projection (Section 3.1) is exported as the baseline.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ * Memory.   Every pointer named "device" is GPU memory of the current HIP device, owned by the
+ *           caller for the whole call and until the stream has finished the enqueued work.  The
+ *           library allocates nothing, frees nothing and keeps no pointer after returning.
+ * Layout.   Matrices are row-major.  ld* arguments are row strides in ELEMENTS.  h, U, W_down and
+ *           W_vocab of one call share one storage type `dt`: SV_F32 (IEEE float32) or SV_BF16
+ *           (bfloat16).  Logits, scores and probabilities are float32; token ids are int32.
+ * Alignment.Base pointers of h, U, W_down, W_vocab and the workspace are 16-byte aligned; a row
+ *           of h / U / W_down / W_vocab is a whole number of 16-byte units (d, d_prime multiples
+ *           of 8 for bf16, of 4 for float32) and so are the row strides.
+ * Stream.   `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *           enqueue work: they do not synchronise, do not read device memory on the host, and can
+ *           be captured into a HIP graph.  Outputs are valid once the stream reaches that point.
+ * Workspace.`ws` is device scratch of at least specvocab_workspace_bytes(...) bytes for the same
+ *           shape (may be NULL when that is 0).  Its contents need not be initialised and are
+ *           undefined afterwards.  Calls that share a workspace must be ordered on one stream.
+ * Errors.   Every entry point returns an sv_status.  Arguments are validated on the host before
+ *           anything is enqueued; on any status other than SV_OK nothing has been launched.
+ *           Index CONTENTS (range, uniqueness) are the caller's contract and are not checked.
+ * Precision.Products of the stored values are accumulated in float32 (order unspecified).
+ *           With SV_BF16 storage the intermediate h' of the selector is rounded to bfloat16
+ *           (round-to-nearest-even) before the second projection; with SV_F32 it stays float32.
+ * Ties.     Wherever "largest" decides, equal values are ordered by smaller token id first.
+ */
+#ifndef SPECVOCAB_H
+#define SPECVOCAB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPECVOCAB_VERSION 100 /* major*10000 + minor*100 + patch */
+
+typedef enum {
+    SV_OK = 0,
+    SV_ERR_NULL = 1,        /* a required pointer is NULL */
+    SV_ERR_SHAPE = 2,       /* a size is out of range or sizes disagree (k > V, kd > k, ld < d ...) */
+    SV_ERR_DTYPE = 3,       /* unknown sv_dtype / sv_idx_mode / sv_op value */
+    SV_ERR_ALIGN = 4,       /* pointer or stride not 16-byte aligned */
+    SV_ERR_WORKSPACE = 5,   /* workspace missing or too small */
+    SV_ERR_UNSUPPORTED = 6, /* legal in principle, not handled by this build (see each function) */
+    SV_ERR_HIP = 8          /* a HIP runtime call (kernel launch, device query) failed */
+} sv_status;
+
+typedef enum { SV_F32 = 0, SV_BF16 = 1 } sv_dtype;
+
+/* SV_IDX_PER_ROW: idx is [rows x k], row r of h uses idx[r, :].
+ * SV_IDX_PER_STEP: idx is [k], one set shared by every row of the step. */
+typedef enum { SV_IDX_PER_ROW = 0, SV_IDX_PER_STEP = 1 } sv_idx_mode;
+
+typedef enum {
+    SV_OP_SELECT = 0,
+    SV_OP_SUBSET_LOGITS = 1,
+    SV_OP_DRAFT_TOPK = 2,
+    SV_OP_DENSE_LOGITS = 3
+} sv_op;
+
+/* Largest kd the draft top-kd accepts. */
+#define SPECVOCAB_MAX_KD 64
+
+/* SPECVOCAB_VERSION of the loaded library. */
+int specvocab_version(void);
+
+/* Static, NUL-terminated description of an sv_status value. */
+const char* specvocab_status_string(int status);
+
+/* Bytes of device workspace the given operation needs for the given shape, written to
+ * *bytes_out (host pointer).  Arguments an operation does not have are ignored (pass 0).
+ * 0 is a valid answer.  Returns SV_ERR_SHAPE / SV_ERR_DTYPE on sizes the operation rejects. */
+int specvocab_workspace_bytes(int op, int64_t rows, int64_t d, int64_t V, int64_t k,
+                              int64_t d_prime, int64_t kd, int dt, int idx_mode,
+                              size_t* bytes_out);
+
+/* Section 3.3, Steps 1 and 2: the candidate vocabulary of every row.
+ *     h'[r, :] = W_down h[r, :]          W_down  device [d_prime x d], row stride d
+ *     s[r, :]  = W_vocab h'[r, :]        W_vocab device [V x d_prime], row stride d_prime
+ *     idx_out[r, :] = token ids of the k largest s[r, :], in ascending id order
+ * h: device [rows x d], row stride ldh.  idx_out: device [rows x k] int32.
+ * scores_out: device [rows x k] float32 receiving s[r, idx_out[r, j]], or NULL.
+ * Requires 1 <= k <= V < 2^31, 1 <= d_prime, rows >= 1. */
+int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh,
+                     const void* W_down, int64_t d_prime,
+                     const void* W_vocab, int64_t V,
+                     int dt, int64_t k,
+                     int32_t* idx_out, float* scores_out,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/* Section 3.3, Step 3 (the fused indexed LM head of Section 3.5, "Custom kernel"):
+ *     logits_out[r, j] = < U[idx(r, j), :], h[r, :] >
+ * without materialising U[idx, :]; each needed row of U is read from memory once per use.
+ * h: device [rows x d] stride ldh.  U: device [V x d] stride ldu.
+ * idx: device int32, [rows x k] (SV_IDX_PER_ROW) or [k] (SV_IDX_PER_STEP), any order; every
+ * entry must lie in [0, V) (caller's contract, unchecked).  Duplicates just repeat the value.
+ * logits_out: device [rows x k] float32. */
+int specvocab_subset_logits(const void* h, int64_t rows, int64_t d, int64_t ldh,
+                            const void* U, int64_t V, int64_t ldu, int dt,
+                            const int32_t* idx, int64_t k, int idx_mode,
+                            float* logits_out,
+                            void* ws, size_t ws_bytes, void* stream);
+
+/* Subset softmax (Section 3.3, q_K = softmax(z')) and the top-kd draft tokens of every row
+ * (inference hyper-parameter "Top-k", 10 in the paper's appendix):
+ *     q[r, j]      = exp(logits[r, j] - max_j) / sum_l exp(logits[r, l] - max_j)
+ *     tok_out[r,t] = idx(r, j_t), prob_out[r, t] = q[r, j_t], where j_0, j_1, ... order the row by
+ *                    descending logit, equal logits by ascending token id
+ * logits: device [rows x k] float32 (finite).  idx: as in specvocab_subset_logits; token ids of
+ * one row must be unique.  tok_out: device [rows x kd] int32.  prob_out: device [rows x kd]
+ * float32.  probs_full_out: device [rows x k] float32 receiving q, or NULL.
+ * Requires 1 <= kd <= min(k, SPECVOCAB_MAX_KD), else SV_ERR_SHAPE / SV_ERR_UNSUPPORTED. */
+int specvocab_draft_topk(const float* logits, const int32_t* idx, int idx_mode,
+                         int64_t rows, int64_t k, int64_t kd,
+                         int32_t* tok_out, float* prob_out, float* probs_full_out,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/* Section 3.1, the full-vocabulary baseline:  logits_out[r, v] = < U[v, :], h[r, :] >.
+ * logits_out: device [rows x V] float32. */
+int specvocab_dense_logits(const void* h, int64_t rows, int64_t d, int64_t ldh,
+                           const void* U, int64_t V, int64_t ldu, int dt,
+                           float* logits_out,
+                           void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECVOCAB_H */

@@ -1,0 +1,273 @@
+// C ABI of the SpecVocab draft-step library: host-side argument validation, workspace carving
+// and launch planning.  Nothing here touches device memory on the host, allocates, or
+// synchronises; every check happens before the first kernel is enqueued.
+#include "../../include/specvocab.h"
+
+#include "sv_device.h"
+#include "sv_launch.h"
+
+namespace sv {
+
+hipError_t device_info(DeviceInfo* out) {
+    static DeviceInfo cached[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!cached[dev].valid) {
+        int cus = 0;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        cached[dev].cus = cus > 0 ? cus : 256;
+        cached[dev].valid = 1;
+    }
+    *out = cached[dev];
+    return hipSuccess;
+}
+
+}  // namespace sv
+
+namespace {
+
+constexpr int64_t kMaxRows = 65535;            // rows ride on gridDim.y
+constexpr int64_t kMaxVocab = 2147483647LL;
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round256(size_t n) { return (n + 255u) & ~static_cast<size_t>(255u); }
+inline int esize_of(int dt) { return dt == SV_BF16 ? 2 : 4; }
+inline bool dtype_ok(int dt) { return dt == SV_F32 || dt == SV_BF16; }
+inline bool mode_ok(int m) { return m == SV_IDX_PER_ROW || m == SV_IDX_PER_STEP; }
+
+// a row of `n` elements must be a whole number of 16-byte units, and so must its stride
+inline int check_row(int64_t n, int64_t ld, int dt) {
+    if (n < 1 || ld < n) return SV_ERR_SHAPE;
+    const int per16 = 16 / esize_of(dt);
+    if (n % per16 != 0) return SV_ERR_UNSUPPORTED;
+    if (ld % per16 != 0) return SV_ERR_ALIGN;
+    return SV_OK;
+}
+
+struct SelectWs {
+    size_t hp_off, s_off, radix_off, total;
+};
+SelectWs select_ws(int64_t rows, int64_t V, int64_t d_prime, int dt) {
+    SelectWs w;
+    w.hp_off = 0;
+    w.s_off = round256((size_t)rows * (size_t)d_prime * (size_t)esize_of(dt));
+    w.radix_off = w.s_off + round256((size_t)rows * (size_t)V * sizeof(float));
+    w.total = w.radix_off + round256(sv::radix_scratch_words(rows, V) * sizeof(uint32_t));
+    return w;
+}
+
+int check_select_shape(int64_t rows, int64_t d, int64_t V, int64_t k, int64_t d_prime, int dt) {
+    if (!dtype_ok(dt)) return SV_ERR_DTYPE;
+    if (rows < 1 || rows > kMaxRows || V < 1 || V > kMaxVocab || k < 1 || k > V) return SV_ERR_SHAPE;
+    int st = check_row(d, d, dt);
+    if (st != SV_OK) return st;
+    st = check_row(d_prime, d_prime, dt);
+    if (st != SV_OK) return st;
+    if (d > (1 << 24) || d_prime > (1 << 24)) return SV_ERR_UNSUPPORTED;
+    return SV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int specvocab_version(void) { return SPECVOCAB_VERSION; }
+
+const char* specvocab_status_string(int status) {
+    switch (status) {
+        case SV_OK: return "ok";
+        case SV_ERR_NULL: return "a required pointer is NULL";
+        case SV_ERR_SHAPE: return "a size is out of range or sizes disagree";
+        case SV_ERR_DTYPE: return "unknown dtype, index mode or operation";
+        case SV_ERR_ALIGN: return "pointer or row stride is not 16-byte aligned";
+        case SV_ERR_WORKSPACE: return "workspace missing or too small";
+        case SV_ERR_UNSUPPORTED: return "shape not supported by this build";
+        case SV_ERR_HIP: return "a HIP runtime call failed";
+        default: return "unknown status";
+    }
+}
+
+int specvocab_workspace_bytes(int op, int64_t rows, int64_t d, int64_t V, int64_t k, int64_t d_prime,
+                              int64_t kd, int dt, int idx_mode, size_t* bytes_out) {
+    (void)kd;
+    (void)idx_mode;
+    if (!bytes_out) return SV_ERR_NULL;
+    *bytes_out = 0;
+    switch (op) {
+        case SV_OP_SELECT: {
+            const int st = check_select_shape(rows, d, V, k, d_prime, dt);
+            if (st != SV_OK) return st;
+            *bytes_out = select_ws(rows, V, d_prime, dt).total;
+            return SV_OK;
+        }
+        case SV_OP_SUBSET_LOGITS:
+        case SV_OP_DRAFT_TOPK:
+        case SV_OP_DENSE_LOGITS:
+            return SV_OK;
+        default:
+            return SV_ERR_DTYPE;
+    }
+}
+
+int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* W_down,
+                     int64_t d_prime, const void* W_vocab, int64_t V, int dt, int64_t k,
+                     int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream) {
+    if (!h || !W_down || !W_vocab || !idx_out) return SV_ERR_NULL;
+    int st = check_select_shape(rows, d, V, k, d_prime, dt);
+    if (st != SV_OK) return st;
+    st = check_row(d, ldh, dt);
+    if (st != SV_OK) return st;
+    if (!aligned16(h) || !aligned16(W_down) || !aligned16(W_vocab) || !aligned16(ws)) return SV_ERR_ALIGN;
+    const SelectWs w = select_ws(rows, V, d_prime, dt);
+    if (!ws || ws_bytes < w.total) return SV_ERR_WORKSPACE;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int es = esize_of(dt);
+    char* base = static_cast<char*>(ws);
+    char* hp = base + w.hp_off;
+    float* scores = reinterpret_cast<float*>(base + w.s_off);
+    uint32_t* radix = reinterpret_cast<uint32_t*>(base + w.radix_off);
+
+    // Step 1a: h' = W_down h, stored in the storage dtype (bf16: rounded to nearest even)
+    sv::GemvArgs g{};
+    g.x = static_cast<const char*>(h);
+    g.x_row_bytes = ldh * es;
+    g.M = static_cast<const char*>(W_down);
+    g.m_row_bytes = d * es;
+    g.idx = nullptr;
+    g.idx_row_stride = 0;
+    g.n_items = d_prime;
+    g.chunks = (int)(d * es / 16);
+    g.rows = (int)rows;
+    g.out_f32 = dt == SV_BF16 ? nullptr : reinterpret_cast<float*>(hp);
+    g.out_bf16 = dt == SV_BF16 ? reinterpret_cast<uint16_t*>(hp) : nullptr;
+    g.out_row_stride = d_prime;
+    if (sv::launch_gemv(dt, g, s) != hipSuccess) return SV_ERR_HIP;
+
+    // Step 1b: s = W_vocab h'
+    const int vchunks = (int)(d_prime * es / 16);
+    if (sv::scores_supported(vchunks)) {
+        sv::ScoresArgs sa{};
+        sa.hp = hp;
+        sa.Wv = static_cast<const char*>(W_vocab);
+        sa.V = V;
+        sa.chunks = vchunks;
+        sa.rows = (int)rows;
+        sa.s = scores;
+        if (sv::launch_scores(dt, sa, s) != hipSuccess) return SV_ERR_HIP;
+    } else {
+        sv::GemvArgs g2{};
+        g2.x = hp;
+        g2.x_row_bytes = d_prime * es;
+        g2.M = static_cast<const char*>(W_vocab);
+        g2.m_row_bytes = d_prime * es;
+        g2.n_items = V;
+        g2.chunks = vchunks;
+        g2.rows = (int)rows;
+        g2.out_f32 = scores;
+        g2.out_row_stride = V;
+        if (sv::launch_gemv(dt, g2, s) != hipSuccess) return SV_ERR_HIP;
+    }
+
+    // Step 2: exact top-k, ascending ids
+    sv::RadixArgs ra{};
+    ra.s = scores;
+    ra.V = V;
+    ra.rows = (int)rows;
+    ra.k = k;
+    ra.idx_out = idx_out;
+    ra.scores_out = scores_out;
+    ra.scratch = radix;
+    if (sv::launch_radix_select(ra, s) != hipSuccess) return SV_ERR_HIP;
+    return SV_OK;
+}
+
+int specvocab_subset_logits(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* U, int64_t V,
+                            int64_t ldu, int dt, const int32_t* idx, int64_t k, int idx_mode,
+                            float* logits_out, void* ws, size_t ws_bytes, void* stream) {
+    (void)ws;
+    (void)ws_bytes;
+    if (!h || !U || !idx || !logits_out) return SV_ERR_NULL;
+    if (!dtype_ok(dt) || !mode_ok(idx_mode)) return SV_ERR_DTYPE;
+    if (rows < 1 || rows > kMaxRows || V < 1 || V > kMaxVocab || k < 1) return SV_ERR_SHAPE;
+    int st = check_row(d, ldh, dt);
+    if (st != SV_OK) return st;
+    st = check_row(d, ldu, dt);
+    if (st != SV_OK) return st;
+    if (!aligned16(h) || !aligned16(U)) return SV_ERR_ALIGN;
+
+    const int es = esize_of(dt);
+    sv::GemvArgs g{};
+    g.x = static_cast<const char*>(h);
+    g.x_row_bytes = ldh * es;
+    g.M = static_cast<const char*>(U);
+    g.m_row_bytes = ldu * es;
+    g.idx = idx;
+    g.idx_row_stride = idx_mode == SV_IDX_PER_ROW ? k : 0;
+    g.n_items = k;
+    g.chunks = (int)(d * es / 16);
+    g.rows = (int)rows;
+    g.out_f32 = logits_out;
+    g.out_row_stride = k;
+    if (sv::launch_gemv(dt, g, static_cast<hipStream_t>(stream)) != hipSuccess) return SV_ERR_HIP;
+    return SV_OK;
+}
+
+int specvocab_draft_topk(const float* logits, const int32_t* idx, int idx_mode, int64_t rows, int64_t k,
+                         int64_t kd, int32_t* tok_out, float* prob_out, float* probs_full_out, void* ws,
+                         size_t ws_bytes, void* stream) {
+    (void)ws;
+    (void)ws_bytes;
+    if (!logits || !idx || !tok_out || !prob_out) return SV_ERR_NULL;
+    if (!mode_ok(idx_mode)) return SV_ERR_DTYPE;
+    if (rows < 1 || k < 1 || k > kMaxVocab || kd < 1 || kd > k) return SV_ERR_SHAPE;
+    if (kd > SPECVOCAB_MAX_KD) return SV_ERR_UNSUPPORTED;
+    if (rows > kMaxVocab) return SV_ERR_SHAPE;
+
+    sv::TopkArgs t{};
+    t.logits = logits;
+    t.idx = idx;
+    t.idx_row_stride = idx_mode == SV_IDX_PER_ROW ? k : 0;
+    t.rows = (int)rows;
+    t.k = k;
+    t.kd = (int)kd;
+    t.tok_out = tok_out;
+    t.prob_out = prob_out;
+    t.probs_full_out = probs_full_out;
+    if (sv::launch_softmax_topk(t, static_cast<hipStream_t>(stream)) != hipSuccess) return SV_ERR_HIP;
+    return SV_OK;
+}
+
+int specvocab_dense_logits(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* U, int64_t V,
+                           int64_t ldu, int dt, float* logits_out, void* ws, size_t ws_bytes, void* stream) {
+    (void)ws;
+    (void)ws_bytes;
+    if (!h || !U || !logits_out) return SV_ERR_NULL;
+    if (!dtype_ok(dt)) return SV_ERR_DTYPE;
+    if (rows < 1 || rows > kMaxRows || V < 1 || V > kMaxVocab) return SV_ERR_SHAPE;
+    int st = check_row(d, ldh, dt);
+    if (st != SV_OK) return st;
+    st = check_row(d, ldu, dt);
+    if (st != SV_OK) return st;
+    if (!aligned16(h) || !aligned16(U)) return SV_ERR_ALIGN;
+
+    const int es = esize_of(dt);
+    sv::GemvArgs g{};
+    g.x = static_cast<const char*>(h);
+    g.x_row_bytes = ldh * es;
+    g.M = static_cast<const char*>(U);
+    g.m_row_bytes = ldu * es;
+    g.idx = nullptr;
+    g.n_items = V;
+    g.chunks = (int)(d * es / 16);
+    g.rows = (int)rows;
+    g.out_f32 = logits_out;
+    g.out_row_stride = V;
+    if (sv::launch_gemv(dt, g, static_cast<hipStream_t>(stream)) != hipSuccess) return SV_ERR_HIP;
+    return SV_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,135 @@
+// Row-gather matrix-vector kernels (Section 3.3 Step 3 and, with no index list, Section 3.1).
+//
+// One wavefront owns one (or RPI) whole rows of the matrix at a time: the 64 lanes read the row
+// as consecutive 16-byte units (one global_load_dwordx4 per 1 KiB), so every byte of a gathered
+// row is fetched exactly once and in full cache lines.  The hidden-state row is held in
+// registers in the same lane layout for the whole life of the wave.  Products are accumulated
+// per lane in float32 and reduced across the wave with DPP row operations.
+#include "sv_device.h"
+#include "sv_launch.h"
+
+namespace sv {
+
+namespace {
+
+template <int DT, int NL, int RPI, bool OUT_BF16>
+__global__ __launch_bounds__(256) void gemv_rows_kernel(const GemvArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t r = blockIdx.y;
+    const int C = a.chunks;
+
+    const u32x4* xp = reinterpret_cast<const u32x4*>(a.x + r * a.x_row_bytes);
+    u32x4 xreg[NL];
+#pragma unroll
+    for (int c = 0; c < NL; ++c) {
+        const int ch = c * 64 + lane;
+        xreg[c] = ch < C ? xp[ch] : zero16();
+    }
+    const int32_t* idx = a.idx ? a.idx + r * a.idx_row_stride : nullptr;
+    const int64_t n = a.n_items;
+    const int64_t step = (int64_t)gridDim.x * 4 * RPI;
+
+    for (int64_t it = ((int64_t)blockIdx.x * 4 + wave) * RPI; it < n; it += step) {
+        const u32x4* mp[RPI];
+#pragma unroll
+        for (int q = 0; q < RPI; ++q) {
+            int64_t item = it + q;
+            if (item > n - 1) item = n - 1;           // tail: recompute the last item, never stored
+            const int64_t row = idx ? (int64_t)idx[item] : item;
+            mp[q] = reinterpret_cast<const u32x4*>(a.M + row * a.m_row_bytes);
+        }
+        u32x4 w[RPI][NL];
+#pragma unroll
+        for (int q = 0; q < RPI; ++q)
+#pragma unroll
+            for (int c = 0; c < NL; ++c) {
+                const int ch = c * 64 + lane;
+                w[q][c] = ch < C ? load16<true>(mp[q] + ch) : zero16();
+            }
+        float acc[RPI];
+#pragma unroll
+        for (int q = 0; q < RPI; ++q) {
+            acc[q] = 0.0f;
+#pragma unroll
+            for (int c = 0; c < NL; ++c) acc[q] = dot16<DT>(w[q][c], xreg[c], acc[q]);
+            acc[q] = wave_sum(acc[q]);
+        }
+        if (lane == 0) {
+#pragma unroll
+            for (int q = 0; q < RPI; ++q) {
+                if (it + q < n) {
+                    if constexpr (OUT_BF16) a.out_bf16[r * a.out_row_stride + it + q] = f32_to_bf16_rne(acc[q]);
+                    else a.out_f32[r * a.out_row_stride + it + q] = acc[q];
+                }
+            }
+        }
+    }
+}
+
+// any row length: the row is walked in 1 KiB pieces, x is re-read (from L2) for every item
+template <int DT, bool OUT_BF16>
+__global__ __launch_bounds__(256) void gemv_long_rows_kernel(const GemvArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t r = blockIdx.y;
+    const int C = a.chunks;
+    const u32x4* xp = reinterpret_cast<const u32x4*>(a.x + r * a.x_row_bytes);
+    const int32_t* idx = a.idx ? a.idx + r * a.idx_row_stride : nullptr;
+    const int64_t n = a.n_items;
+    const int64_t step = (int64_t)gridDim.x * 4;
+    for (int64_t it = (int64_t)blockIdx.x * 4 + wave; it < n; it += step) {
+        const int64_t row = idx ? (int64_t)idx[it] : it;
+        const u32x4* mp = reinterpret_cast<const u32x4*>(a.M + row * a.m_row_bytes);
+        float acc = 0.0f;
+        for (int ch = lane; ch < C; ch += 64) acc = dot16<DT>(load16<true>(mp + ch), xp[ch], acc);
+        acc = wave_sum(acc);
+        if (lane == 0) {
+            if constexpr (OUT_BF16) a.out_bf16[r * a.out_row_stride + it] = f32_to_bf16_rne(acc);
+            else a.out_f32[r * a.out_row_stride + it] = acc;
+        }
+    }
+}
+
+template <int DT, int NL, int RPI>
+hipError_t launch_rows(const GemvArgs& a, int cus, hipStream_t stream) {
+    const int64_t waves = (a.n_items + RPI - 1) / RPI;
+    int64_t bx = (waves + 3) / 4;
+    const int64_t cap = ((int64_t)cus * 8 + a.rows - 1) / a.rows;
+    if (bx > cap) bx = cap;
+    if (bx < 1) bx = 1;
+    dim3 grid((unsigned)bx, (unsigned)a.rows, 1), block(256, 1, 1);
+    if (a.out_bf16) hipLaunchKernelGGL((gemv_rows_kernel<DT, NL, RPI, true>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((gemv_rows_kernel<DT, NL, RPI, false>), grid, block, 0, stream, a);
+    return hipGetLastError();
+}
+
+template <int DT>
+hipError_t launch_dt(const GemvArgs& a, int cus, hipStream_t stream) {
+    const int nl = (a.chunks + 63) / 64;
+    if (nl <= 1) return launch_rows<DT, 1, 4>(a, cus, stream);
+    if (nl <= 2) return launch_rows<DT, 2, 4>(a, cus, stream);
+    if (nl <= 4) return launch_rows<DT, 4, 2>(a, cus, stream);
+    if (nl <= 8) return launch_rows<DT, 8, 2>(a, cus, stream);
+    if (nl <= 16) return launch_rows<DT, 16, 1>(a, cus, stream);
+    int64_t bx = (a.n_items + 3) / 4;
+    const int64_t cap = ((int64_t)cus * 8 + a.rows - 1) / a.rows;
+    if (bx > cap) bx = cap;
+    if (bx < 1) bx = 1;
+    dim3 grid((unsigned)bx, (unsigned)a.rows, 1), block(256, 1, 1);
+    if (a.out_bf16) hipLaunchKernelGGL((gemv_long_rows_kernel<DT, true>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((gemv_long_rows_kernel<DT, false>), grid, block, 0, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_gemv(int dt, const GemvArgs& a, hipStream_t stream) {
+    DeviceInfo di;
+    hipError_t e = device_info(&di);
+    if (e != hipSuccess) return e;
+    if (dt == DT_BF16) return launch_dt<DT_BF16>(a, di.cus, stream);
+    return launch_dt<DT_F32>(a, di.cus, stream);
+}
+
+}  // namespace sv

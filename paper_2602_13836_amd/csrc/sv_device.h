@@ -1,0 +1,135 @@
+// Device-side helpers shared by the gfx950 kernels: storage formats, 16-byte dot products,
+// DPP wave reductions and the order-preserving float key used by every top-k.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sv {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+
+constexpr int kWave = 64;
+
+template <int DT> struct Elem;
+template <> struct Elem<DT_F32> { static constexpr int size = 4; static constexpr int per16 = 4; };
+template <> struct Elem<DT_BF16> { static constexpr int size = 2; static constexpr int per16 = 8; };
+
+__device__ __forceinline__ u32x4 zero16() { return u32x4{0u, 0u, 0u, 0u}; }
+
+// streaming 16-byte load: the gathered rows are read once per step and need not stay in L2
+template <bool NT>
+__device__ __forceinline__ u32x4 load16(const u32x4* p) {
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+// acc + <w, x> over the 16 bytes held in w and x (8 bf16 pairs or 4 float32 pairs), fp32 accumulate
+template <int DT>
+__device__ __forceinline__ float dot16(const u32x4 w, const u32x4 x, float acc) {
+    if constexpr (DT == DT_BF16) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w[i]),
+                                                  __builtin_bit_cast(bf16x2_t, x[i]), acc, false);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc = fmaf(__uint_as_float(w[i]), __uint_as_float(x[i]), acc);
+    }
+    return acc;
+}
+
+// float32 -> bfloat16 bits, round-to-nearest-even (finite inputs)
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
+    uint32_t u = __float_as_uint(x);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// ---- DPP lane exchange ------------------------------------------------------------------
+// dpp_ctrl encodings of the CDNA ISA
+constexpr int DPP_QUAD_1032 = 0xB1;        // quad_perm:[1,0,3,2]
+constexpr int DPP_QUAD_2301 = 0x4E;        // quad_perm:[2,3,0,1]
+constexpr int DPP_ROW_HALF_MIRROR = 0x141;
+constexpr int DPP_ROW_MIRROR = 0x140;
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, true);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {
+    return __uint_as_float(dpp_u32<CTRL>(__float_as_uint(x)));
+}
+template <int CTRL>
+__device__ __forceinline__ uint64_t dpp_u64(uint64_t x) {
+    uint32_t lo = dpp_u32<CTRL>((uint32_t)x), hi = dpp_u32<CTRL>((uint32_t)(x >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// sum over the 16 lanes of a DPP row; every lane of the row ends with the row's sum
+__device__ __forceinline__ float row16_sum(float x) {
+    x += dpp_f32<DPP_QUAD_1032>(x);
+    x += dpp_f32<DPP_QUAD_2301>(x);
+    x += dpp_f32<DPP_ROW_HALF_MIRROR>(x);
+    x += dpp_f32<DPP_ROW_MIRROR>(x);
+    return x;
+}
+
+__device__ __forceinline__ float readlane_f32(float x, int lane) {
+    return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(x), lane));
+}
+
+// sum over all 64 lanes, result uniform across the wave. All lanes must be active.
+__device__ __forceinline__ float wave_sum(float x) {
+    x = row16_sum(x);
+    return (readlane_f32(x, 0) + readlane_f32(x, 16)) + (readlane_f32(x, 32) + readlane_f32(x, 48));
+}
+
+__device__ __forceinline__ uint64_t umax64(uint64_t a, uint64_t b) { return a > b ? a : b; }
+
+__device__ __forceinline__ uint64_t readlane_u64(uint64_t x, int lane) {
+    uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, lane);
+    uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), lane);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// max over all 64 lanes, result uniform across the wave. All lanes must be active.
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t x) {
+    x = umax64(x, dpp_u64<DPP_QUAD_1032>(x));
+    x = umax64(x, dpp_u64<DPP_QUAD_2301>(x));
+    x = umax64(x, dpp_u64<DPP_ROW_HALF_MIRROR>(x));
+    x = umax64(x, dpp_u64<DPP_ROW_MIRROR>(x));
+    return umax64(umax64(readlane_u64(x, 0), readlane_u64(x, 16)),
+                  umax64(readlane_u64(x, 32), readlane_u64(x, 48)));
+}
+
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x) {
+    x += dpp_u32<DPP_QUAD_1032>(x);
+    x += dpp_u32<DPP_QUAD_2301>(x);
+    x += dpp_u32<DPP_ROW_HALF_MIRROR>(x);
+    x += dpp_u32<DPP_ROW_MIRROR>(x);
+    return (uint32_t)__builtin_amdgcn_readlane((int)x, 0) + (uint32_t)__builtin_amdgcn_readlane((int)x, 16) +
+           (uint32_t)__builtin_amdgcn_readlane((int)x, 32) + (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
+}
+
+// ---- order-preserving keys ----------------------------------------------------------------
+// a > b (floats, -0 == +0)  <=>  ord(a) > ord(b) (unsigned); finite inputs map to keys >= 0x00800000
+__device__ __forceinline__ uint32_t f32_to_ord(float f) {
+    uint32_t u = __float_as_uint(f + 0.0f);   // -0.0 + 0.0 = +0.0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float ord_to_f32(uint32_t k) {
+    uint32_t u = (k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k;
+    return __uint_as_float(u);
+}
+// (value, token) -> 64-bit key: larger value first, equal values -> smaller token id first
+__device__ __forceinline__ uint64_t make_key(float z, int32_t tok) {
+    return ((uint64_t)f32_to_ord(z) << 32) | (uint32_t)(~(uint32_t)tok);
+}
+__device__ __forceinline__ int32_t key_token(uint64_t k) { return (int32_t)(~(uint32_t)k); }
+__device__ __forceinline__ float key_value(uint64_t k) { return ord_to_f32((uint32_t)(k >> 32)); }
+
+}  // namespace sv

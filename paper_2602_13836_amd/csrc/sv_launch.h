@@ -1,0 +1,77 @@
+// Host-side launch interface between the C ABI (api.hip) and the kernel files.
+// Every launcher only enqueues kernels on `stream` and returns the hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace sv {
+
+struct DeviceInfo {
+    int cus;         // compute units of the current device
+    int valid;
+};
+// cached per process; queries the current device the first time
+hipError_t device_info(DeviceInfo* out);
+
+// out[r, j] = < M[row(r, j), :], x[r, :] >  for j in [0, n_items)
+//   row(r, j) = j                       if idx == nullptr   (dense)
+//             = idx[r * idx_row_stride + j]                 (gathered; stride 0 = one set per step)
+// M: rows of `chunks` 16-byte units, row stride m_row_bytes.  x: [rows x d], row stride x_row_bytes.
+// out_f32 [rows x out_row_stride] or, if out_bf16 != nullptr, bf16 (RNE) to out_bf16 instead.
+struct GemvArgs {
+    const char* x;
+    int64_t x_row_bytes;
+    const char* M;
+    int64_t m_row_bytes;
+    const int32_t* idx;
+    int64_t idx_row_stride;
+    int64_t n_items;
+    int chunks;
+    int rows;
+    float* out_f32;
+    uint16_t* out_bf16;
+    int64_t out_row_stride;
+};
+hipError_t launch_gemv(int dt, const GemvArgs& a, hipStream_t stream);
+
+// s[r, v] = < W_vocab[v, :], hp[r, :] > for short rows (d_prime * esize <= 1024 bytes)
+struct ScoresArgs {
+    const char* hp;        // [rows x d_prime] in dt
+    const char* Wv;        // [V x d_prime] in dt, dense rows
+    int64_t V;
+    int chunks;            // d_prime * esize / 16
+    int rows;
+    float* s;              // [rows x V]
+};
+bool scores_supported(int chunks);
+hipError_t launch_scores(int dt, const ScoresArgs& a, hipStream_t stream);
+
+// exact top-k of every row of s by MSB-first radix selection, ids ascending
+struct RadixArgs {
+    const float* s;        // [rows x V]
+    int64_t V;
+    int rows;
+    int64_t k;
+    int32_t* idx_out;      // [rows x k]
+    float* scores_out;     // [rows x k] or nullptr
+    uint32_t* scratch;     // radix_scratch_words(rows, V) uint32 words
+};
+size_t radix_scratch_words(int64_t rows, int64_t V);
+hipError_t launch_radix_select(const RadixArgs& a, hipStream_t stream);
+
+// subset softmax + top-kd
+struct TopkArgs {
+    const float* logits;   // [rows x k]
+    const int32_t* idx;
+    int64_t idx_row_stride;  // k (per row) or 0 (per step)
+    int rows;
+    int64_t k;
+    int kd;
+    int32_t* tok_out;
+    float* prob_out;
+    float* probs_full_out;
+};
+hipError_t launch_softmax_topk(const TopkArgs& a, hipStream_t stream);
+
+}  // namespace sv

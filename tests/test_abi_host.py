@@ -1,0 +1,119 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before enqueueing anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2602_13836_amd as sv
+from paper_2602_13836_amd import build as sv_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "specvocab.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(sv.LIB_PATH):
+        sv_build.build_library()
+    return sv.load_library()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(specvocab_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree_on_exports(lib):
+    names = _declared_functions()
+    assert names == sorted(sv.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings(lib):
+    assert sv.version() == 100
+    assert sv.status_string(0) == "ok"
+    seen = {sv.status_string(s) for s in (1, 2, 3, 4, 5, 6, 8)}
+    assert len(seen) == 7 and "unknown status" not in seen
+    assert sv.status_string(77) == "unknown status"
+
+
+def test_workspace_bytes(lib):
+    assert sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 1, 4096, 128256, 8192) == 0
+    assert sv.workspace_bytes(sv.SV_OP_DENSE_LOGITS, 1, 4096, 128256) == 0
+    assert sv.workspace_bytes(sv.SV_OP_DRAFT_TOPK, 1, 0, 0, 8192, 0, 10) == 0
+    n = sv.workspace_bytes(sv.SV_OP_SELECT, 2, 4096, 128256, 8192, 256)
+    assert n >= 2 * 128256 * 4 + 2 * 256 * 2           # the score matrix and h'
+    assert n % 256 == 0
+    with pytest.raises(sv.SpecVocabError) as e:
+        sv.workspace_bytes(sv.SV_OP_SELECT, 1, 4096, 100, 101, 256)     # k > V
+    assert e.value.status == 2
+    with pytest.raises(sv.SpecVocabError) as e:
+        sv.workspace_bytes(99)
+    assert e.value.status == 3
+    assert lib.specvocab_workspace_bytes(0, 1, 8, 8, 1, 8, 0, 1, 0, None) == 1
+
+
+# fake, never dereferenced device addresses: every call below must fail validation on the host
+A = ctypes.c_void_p(0x10000)          # 16-byte aligned
+MIS = ctypes.c_void_p(0x10008)        # misaligned
+
+
+def test_subset_logits_rejects_bad_arguments(lib):
+    f = lib.specvocab_subset_logits
+    ok = dict(h=A, rows=1, d=256, ldh=256, U=A, V=1000, ldu=256, dt=1, idx=A, k=10, mode=0, out=A)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["h"], a["rows"], a["d"], a["ldh"], a["U"], a["V"], a["ldu"], a["dt"], a["idx"], a["k"],
+                 a["mode"], a["out"], None, 0, None)
+
+    assert call(h=None) == 1 and call(U=None) == 1 and call(idx=None) == 1 and call(out=None) == 1
+    assert call(rows=0) == 2 and call(k=0) == 2 and call(V=0) == 2
+    assert call(ldh=128) == 2 and call(ldu=255) == 2
+    assert call(dt=7) == 3 and call(mode=5) == 3
+    assert call(d=252, ldh=252, ldu=252) == 6             # row not a whole number of 16-byte units
+    assert call(ldu=260) == 4                              # stride not 16-byte aligned
+    assert call(h=MIS) == 4 and call(U=MIS) == 4
+    assert call(rows=70000) == 2
+
+
+def test_dense_select_topk_reject_bad_arguments(lib):
+    d = lib.specvocab_dense_logits
+    assert d(None, 1, 256, 256, A, 10, 256, 1, A, None, 0, None) == 1
+    assert d(A, 1, 256, 256, A, 10, 256, 9, A, None, 0, None) == 3
+    assert d(A, 1, 256, 100, A, 10, 256, 1, A, None, 0, None) == 2
+    assert d(A, 1, 256, 256, MIS, 10, 256, 1, A, None, 0, None) == 4
+
+    s = lib.specvocab_select
+    assert s(A, 1, 256, 256, A, 32, A, 1000, 1, 10, None, None, A, 1 << 30, None) == 1
+    assert s(A, 1, 256, 256, A, 32, A, 1000, 1, 1001, A, None, A, 1 << 30, None) == 2      # k > V
+    assert s(A, 1, 256, 256, A, 32, A, 1000, 1, 10, A, None, None, 0, None) == 5            # no workspace
+    assert s(A, 1, 256, 256, A, 32, A, 1000, 1, 10, A, None, A, 16, None) == 5              # too small
+    assert s(A, 1, 256, 256, A, 30, A, 1000, 1, 10, A, None, A, 1 << 30, None) == 6         # d' % 8
+    assert s(A, 1, 256, 256, A, 32, A, 1000, 4, 10, A, None, A, 1 << 30, None) == 3
+
+    t = lib.specvocab_draft_topk
+    assert t(None, A, 0, 1, 100, 10, A, A, None, None, 0, None) == 1
+    assert t(A, A, 0, 1, 100, 101, A, A, None, None, 0, None) == 2                          # kd > k
+    assert t(A, A, 0, 1, 100, 0, A, A, None, None, 0, None) == 2
+    assert t(A, A, 0, 1, 1000, 65, A, A, None, None, 0, None) == 6                          # kd > 64
+    assert t(A, A, 3, 1, 100, 10, A, A, None, None, 0, None) == 3
+
+
+def test_binding_refuses_cpu_tensors(lib):
+    import torch
+    h = torch.zeros(1, 256, dtype=torch.bfloat16)
+    U = torch.zeros(10, 256, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        sv.dense_logits(h, U)
+    with pytest.raises(ValueError):
+        sv.subset_logits(h, U, torch.zeros(4, dtype=torch.int32))
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    with pytest.raises(FileNotFoundError):
+        sv.load_library(str(tmp_path / "libspecvocab.so"))

@@ -1,0 +1,359 @@
+"""GPU parity: the HIP library (through its C ABI binding) against the CPU oracle on the same
+seeded inputs.  Small shapes cover several tiles, ragged tails and the degenerate cases; the
+full-size cases run in the launch configuration the benchmark times."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2602_13836_amd as sv
+from compare import (assert_logits_close, check_draft_tokens, check_selected_set)
+from workloads import CONFIGS, f32_to_bf16_bits, make_rng, tree_subsets, zipf_subset
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def to_dev(a: np.ndarray) -> torch.Tensor:
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(DEV).view(torch.bfloat16)
+    return torch.from_numpy(a).to(DEV)
+
+
+def rand(rng, shape, std, dtype):
+    x = rng.standard_normal(shape).astype(np.float32) * np.float32(std)
+    return x if dtype == "f32" else f32_to_bf16_bits(x)
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ---------------------------------------------------------------- subset / dense logits
+LOGIT_SHAPES = [
+    # dtype, rows, d,    V,    k,    mode
+    ("f32", 1, 256, 8192, 512, "per_row"),       # config 1
+    ("bf16", 1, 256, 8192, 512, "per_row"),
+    ("bf16", 3, 264, 1000, 77, "per_row"),       # 33 16-byte units: ragged last load
+    ("bf16", 2, 3840, 3000, 333, "per_step"),    # Gemma-style d, 7.5 KiB rows
+    ("bf16", 5, 4096, 2048, 1, "per_row"),       # k = 1
+    ("bf16", 2, 520, 301, 301, "per_step"),      # k = V
+    ("bf16", 1, 8192, 600, 129, "per_row"),      # 16 loads per lane
+    ("bf16", 2, 8200, 300, 50, "per_row"),       # longer than the register-resident path
+    ("f32", 2, 260, 500, 64, "per_row"),
+    ("f32", 1, 4096, 700, 100, "per_step"),      # 16 loads per lane, float32
+    ("f32", 2, 4100, 300, 33, "per_row"),        # long-row path, float32
+    ("bf16", 7, 1024, 5000, 1000, "per_row"),
+]
+
+
+@pytest.mark.parametrize("dtype,rows,d,V,k,mode", LOGIT_SHAPES)
+def test_subset_and_dense_logits(dtype, rows, d, V, k, mode):
+    say(f"subset/dense logits {dtype} rows={rows} d={d} V={V} k={k} {mode}")
+    rng = np.random.default_rng(hash((rows, d, V, k)) % (2 ** 31))
+    U = rand(rng, (V, d), 0.02, dtype)
+    h = rand(rng, (rows, d), 1.0, dtype)
+    if mode == "per_step":
+        idx = rng.permutation(V)[:k].astype(np.int32)
+    else:
+        idx = np.stack([rng.permutation(V)[:k] for _ in range(rows)]).astype(np.int32)
+    tU, th, tidx = to_dev(U), to_dev(h), torch.from_numpy(idx).to(DEV)
+    z = sv.subset_logits(th, tU, tidx).cpu().numpy()
+    zd = sv.dense_logits(th, tU).cpu().numpy()
+    z_ref = oracle.subset_logits(h, U, idx)
+    zd_ref = oracle.dense_logits(h, U)
+    assert_logits_close(z, z_ref, dtype, "subset logits")
+    assert_logits_close(zd, zd_ref, dtype, "dense logits")
+    # also against the float64-accumulated oracle (bounds the oracle's own rounding)
+    assert_logits_close(z, oracle.subset_logits(h, U, idx, acc="f64"), dtype, "subset logits vs f64")
+
+
+def test_strided_rows():
+    """h and U taken as column slices of wider matrices (row stride > d)."""
+    say("strided rows")
+    rng = np.random.default_rng(5)
+    rows, d, V, k = 3, 512, 700, 200
+    Uw = rand(rng, (V, d + 64), 0.02, "bf16")
+    hw = rand(rng, (rows, d + 8), 1.0, "bf16")
+    idx = np.stack([rng.permutation(V)[:k] for _ in range(rows)]).astype(np.int32)
+    tU, th = to_dev(Uw)[:, :d], to_dev(hw)[:, :d]
+    z = sv.subset_logits(th, tU, torch.from_numpy(idx).to(DEV)).cpu().numpy()
+    zd = sv.dense_logits(th, tU).cpu().numpy()
+    assert_logits_close(z, oracle.subset_logits(hw[:, :d], Uw[:, :d], idx), "bf16")
+    assert_logits_close(zd, oracle.dense_logits(hw[:, :d], Uw[:, :d]), "bf16")
+
+
+def test_duplicate_and_unsorted_indices_are_just_gathered():
+    say("duplicate indices")
+    rng = np.random.default_rng(6)
+    d, V = 1024, 100
+    U, h = rand(rng, (V, d), 0.02, "bf16"), rand(rng, (1, d), 1.0, "bf16")
+    idx = np.array([[99, 0, 0, 50, 99, 1, 0]], dtype=np.int32)
+    z = sv.subset_logits(to_dev(h), to_dev(U), torch.from_numpy(idx).to(DEV)).cpu().numpy()
+    assert_logits_close(z, oracle.subset_logits(h, U, idx), "bf16")
+    assert z[0, 1] == z[0, 2] == z[0, 6] and z[0, 0] == z[0, 4]
+
+
+# ---------------------------------------------------------------- softmax + draft top-kd
+TOPK_SHAPES = [
+    # rows, k, kd, mode
+    (1, 1, 1, "per_row"), (3, 7, 7, "per_row"), (2, 64, 64, "per_step"), (4, 300, 10, "per_row"),
+    (2, 2048, 10, "per_row"), (2, 2049, 10, "per_row"), (1, 8192, 10, "per_row"),
+    (3, 8192, 64, "per_step"), (2, 20000, 10, "per_row"), (2, 32768, 8, "per_row"),
+    (1, 40000, 10, "per_row"), (60, 4096, 10, "per_row"),
+]
+
+
+@pytest.mark.parametrize("rows,k,kd,mode", TOPK_SHAPES)
+@pytest.mark.parametrize("ties", [False, True])
+def test_draft_topk_matches_oracle_on_identical_logits(rows, k, kd, mode, ties):
+    """Both sides get the same float32 logits, so tokens must match bit-exactly, ties included."""
+    say(f"draft_topk rows={rows} k={k} kd={kd} {mode} ties={ties}")
+    rng = np.random.default_rng(1000 * k + kd + rows)
+    z = (rng.standard_normal((rows, k)) * 3.0).astype(np.float32)
+    if ties:
+        z = np.round(z * 2.0) / 2.0           # a handful of distinct values: ties everywhere
+        z[z == 0.0] = -0.0                    # -0.0 must order like +0.0
+    V = max(4 * k, 1000)
+    if mode == "per_step":
+        idx = rng.permutation(V)[:k].astype(np.int32)
+    else:
+        idx = np.stack([rng.permutation(V)[:k] for _ in range(rows)]).astype(np.int32)
+    tok, prob, q = sv.draft_topk(torch.from_numpy(z).to(DEV), torch.from_numpy(idx).to(DEV), kd,
+                                 want_probs=True)
+    tok, prob, q = tok.cpu().numpy(), prob.cpu().numpy(), q.cpu().numpy()
+    tok_ref, prob_ref, q_ref = oracle.softmax_topk(z, idx, kd, full=True)
+    assert np.array_equal(tok, tok_ref)
+    assert np.allclose(prob, prob_ref, rtol=1e-3, atol=1e-5)
+    assert np.allclose(q, q_ref, rtol=1e-3, atol=1e-5)
+    assert np.allclose(q.sum(axis=1), 1.0, atol=1e-4)
+
+
+# ---------------------------------------------------------------- select
+SELECT_SHAPES = [
+    # dtype, rows, d,   d',  V,     k
+    ("f32", 1, 256, 32, 8192, 512),           # config 1 with a selector
+    ("bf16", 2, 512, 64, 5000, 1000),         # two vocabulary blocks, ragged
+    ("bf16", 1, 256, 8, 4096, 1),             # k = 1, one 16-byte unit per selector row
+    ("bf16", 3, 256, 24, 4097, 4097),         # k = V, one entry spills into a second block
+    ("bf16", 2, 1024, 240, 9000, 300),        # 30 units: two idle lanes per row group
+    ("bf16", 1, 1024, 256, 20000, 2048),
+    ("bf16", 2, 1024, 512, 6000, 100),        # a full wave per selector row
+    ("bf16", 1, 1024, 520, 3000, 64),         # longer than a wave-wide load: generic row kernel
+    ("f32", 2, 264, 12, 700, 33),
+]
+
+
+@pytest.mark.parametrize("dtype,rows,d,dp,V,k", SELECT_SHAPES)
+def test_select(dtype, rows, d, dp, V, k):
+    say(f"select {dtype} rows={rows} d={d} d'={dp} V={V} k={k}")
+    rng = np.random.default_rng(V + k + dp)
+    h = rand(rng, (rows, d), 1.0, dtype)
+    Wd = rand(rng, (dp, d), 0.05, dtype)
+    Wv = rand(rng, (V, dp), 0.05, dtype)
+    idx, sc = sv.select(to_dev(h), to_dev(Wd), to_dev(Wv), k, want_scores=True)
+    idx, sc = idx.cpu().numpy(), sc.cpu().numpy()
+    ref_idx, _, s_ref, _ = oracle.select(h, Wd, Wv, k, full=True)
+    for r in range(rows):
+        band, diff = check_selected_set(idx[r], s_ref[r], ref_idx[r], k, dtype)
+        say(f"  row {r}: {band} scores within tolerance of the k-th, {diff} ids differ from the oracle")
+        assert_logits_close(sc[r], s_ref[r, idx[r]], dtype, "scores at the selected ids")
+
+
+def test_select_ties_go_to_smaller_ids():
+    """Rows of W_vocab repeated: repeated rows score bit-identically on the GPU as well, so the
+    set is decided by the tie rule alone wherever the distinct scores are far apart."""
+    say("select ties")
+    rng = np.random.default_rng(77)
+    d, dp, V = 256, 16, 10000
+    h = rand(rng, (2, d), 1.0, "bf16")
+    Wd = rand(rng, (dp, d), 0.05, "bf16")
+    base = rand(rng, (5, dp), 0.5, "bf16")                # 5 distinct rows, well separated scores
+    Wv = base[rng.integers(0, 5, size=V)]
+    for k in (1, 1999, 2000, 5000, V):
+        idx, _ = sv.select(to_dev(h), to_dev(Wd), to_dev(Wv), k)
+        ref_idx, _, s_ref, _ = oracle.select(h, Wd, Wv, k, full=True)
+        for r in range(2):                                    # the premise of an exact comparison
+            vals = np.unique(s_ref[r])
+            assert len(vals) == 5 and np.diff(vals).min() > 0.1
+        assert np.array_equal(idx.cpu().numpy(), ref_idx), k
+    Wv[:] = Wv[0]
+    idx, _ = sv.select(to_dev(h), to_dev(Wd), to_dev(Wv), 4321)
+    assert np.array_equal(idx.cpu().numpy(), np.tile(np.arange(4321, dtype=np.int32), (2, 1)))
+
+
+def test_exact_selector_reduces_to_dense_topk():
+    """d' = d, W_down = I, W_vocab = U: select must return the top-k of the true logits."""
+    say("select with the exact selector")
+    rng = np.random.default_rng(78)
+    d, V, k = 256, 3000, 200
+    U, h = rand(rng, (V, d), 0.05, "bf16"), rand(rng, (2, d), 1.0, "bf16")
+    eye = f32_to_bf16_bits(np.eye(d, dtype=np.float32))
+    idx, _ = sv.select(to_dev(h), to_dev(eye), to_dev(U), k)
+    z_ref = oracle.dense_logits(h, U)
+    for r in range(2):
+        ref = np.sort(np.argsort(-z_ref[r], kind="stable")[:k]).astype(np.int32)
+        check_selected_set(idx[r].cpu().numpy(), z_ref[r], ref, k, "bf16")
+
+
+# ---------------------------------------------------------------- whole draft step, config 1
+def test_config1_all_steps():
+    c = CONFIGS[1]
+    say("config 1: every step, float32")
+    U, hs, idxs = c.weights(), c.hidden(), c.indices()
+    Wd, Wv = c.selector()
+    tU = to_dev(U)
+    allv = torch.arange(c.V, dtype=torch.int32, device=DEV)
+    for t in range(c.steps):
+        h, idx = hs[t], idxs[t]
+        th, tidx = to_dev(h), torch.from_numpy(idx).to(DEV)
+        z = sv.subset_logits(th, tU, tidx)
+        z_ref = oracle.subset_logits(h, U, idx)
+        assert_logits_close(z.cpu().numpy(), z_ref, "f32")
+        tok, prob, _ = sv.draft_topk(z, tidx, c.kd)
+        tok_ref, prob_ref = oracle.softmax_topk(z_ref, idx, c.kd)
+        for r in range(c.rows):
+            check_draft_tokens(tok[r].cpu().numpy(), prob[r].cpu().numpy(), z_ref[r], idx[r], tok_ref[r],
+                               prob_ref[r], "f32")
+        # the full-vocabulary check: subset = all V reproduces the dense projection
+        zd = sv.dense_logits(th, tU)
+        za = sv.subset_logits(th, tU, allv)
+        assert torch.equal(zd, za) or np.allclose(zd.cpu().numpy(), za.cpu().numpy(), rtol=1e-5, atol=1e-6)
+        assert_logits_close(zd.cpu().numpy(), oracle.dense_logits(h, U), "f32")
+        assert_logits_close(z.cpu().numpy(), zd.cpu().numpy()[np.arange(c.rows)[:, None], idx].astype(np.float64),
+                            "f32", "subset vs slice of dense")
+        tokf, _, _ = sv.draft_topk(zd, allv, c.kd)
+        tokf_ref, _ = oracle.softmax_topk(zd.cpu().numpy(), np.arange(c.V, dtype=np.int32), c.kd)
+        assert np.array_equal(tokf.cpu().numpy(), tokf_ref)
+        sel, _ = sv.select(th, to_dev(Wd), to_dev(Wv), c.k)
+        ref_sel, _, s_ref, _ = oracle.select(h, Wd, Wv, c.k, full=True)
+        check_selected_set(sel[0].cpu().numpy(), s_ref[0], ref_sel[0], c.k, "f32")
+
+
+# ---------------------------------------------------------------- full-size configurations
+@pytest.fixture(scope="module")
+def llama_head():
+    say("drawing the Llama-3-8B-shaped output embedding (128256 x 4096 bf16)")
+    U = CONFIGS[2].weights()
+    return U, to_dev(U)
+
+
+def test_config2_chain_full_size(llama_head):
+    """d=4096, V=128256, k=8192, one row per step: the configuration the benchmark times."""
+    c = CONFIGS[2]
+    U, tU = llama_head
+    steps = 3
+    hs, idxs = c.hidden(steps), c.indices(steps)
+    Wd, Wv = c.selector()
+    tWd, tWv = to_dev(Wd), to_dev(Wv)
+    for t in range(steps):
+        say(f"config 2 step {t}")
+        h, idx = hs[t], idxs[t]
+        th, tidx = to_dev(h), torch.from_numpy(idx).to(DEV)
+        z = sv.subset_logits(th, tU, tidx)
+        z_ref = oracle.subset_logits(h, U, idx)
+        err = assert_logits_close(z.cpu().numpy(), z_ref, "bf16")
+        say(f"  subset logits max |err| = {err:.3e}")
+        tok, prob, _ = sv.draft_topk(z, tidx, c.kd)
+        tok_ref, prob_ref = oracle.softmax_topk(z_ref, idx, c.kd)
+        check_draft_tokens(tok[0].cpu().numpy(), prob[0].cpu().numpy(), z_ref[0], idx[0], tok_ref[0],
+                           prob_ref[0], "bf16")
+        tok_same, prob_same = oracle.softmax_topk(z.cpu().numpy(), idx, c.kd)
+        assert np.array_equal(tok.cpu().numpy(), tok_same)
+        assert np.allclose(prob.cpu().numpy(), prob_same, rtol=1e-3, atol=1e-6)
+    say("config 2 dense baseline, all 128256 logits")
+    zd = sv.dense_logits(to_dev(hs[0]), tU).cpu().numpy()
+    assert_logits_close(zd, oracle.dense_logits(hs[0], U), "bf16", "dense logits")
+    assert_logits_close(sv.subset_logits(to_dev(hs[0]), tU, torch.from_numpy(idxs[0]).to(DEV)).cpu().numpy(),
+                        zd[:, idxs[0][0]].astype(np.float64), "bf16", "subset vs slice of dense")
+    say("config 2 shape with the selector (d'=256)")
+    sel, sc = sv.select(to_dev(hs[0]), tWd, tWv, c.k, want_scores=True)
+    ref_sel, _, s_ref, _ = oracle.select(hs[0], Wd, Wv, c.k, full=True)
+    band, diff = check_selected_set(sel[0].cpu().numpy(), s_ref[0], ref_sel[0], c.k, "bf16")
+    say(f"  {band} scores within tolerance of the k-th, {diff} ids differ from the oracle")
+    assert_logits_close(sc[0].cpu().numpy(), s_ref[0, sel[0].cpu().numpy()], "bf16")
+
+
+def test_config3_tree_full_size(llama_head):
+    """60 tree rows, own k=4096 subset each (half shared step-wide), top-10 per row."""
+    c = CONFIGS[3]
+    U, tU = llama_head
+    say("config 3: 60 rows x 4096")
+    h = c.hidden(1)[0]
+    idx = c.indices(1)[0]
+    th, tidx = to_dev(h), torch.from_numpy(idx).to(DEV)
+    z = sv.subset_logits(th, tU, tidx)
+    tok, prob, _ = sv.draft_topk(z, tidx, c.kd)
+    zn, tokn, probn = z.cpu().numpy(), tok.cpu().numpy(), prob.cpu().numpy()
+    for r in (0, 17, 59):
+        z_ref = oracle.subset_logits(h[r:r + 1], U, idx[r:r + 1])
+        assert_logits_close(zn[r:r + 1], z_ref, "bf16")
+        tok_ref, prob_ref = oracle.softmax_topk(z_ref, idx[r:r + 1], c.kd)
+        check_draft_tokens(tokn[r], probn[r], z_ref[0], idx[r], tok_ref[0], prob_ref[0], "bf16")
+    tok_same, _ = oracle.softmax_topk(zn, idx, c.kd)
+    assert np.array_equal(tokn, tok_same)
+    # property that holds for every row: shared tokens get the logit <U[tok], h_r> whichever row asks
+    zd = sv.dense_logits(th, tU).cpu().numpy()
+    assert np.abs(np.take_along_axis(zd, idx.astype(np.int64), axis=1) - zn).max() <= 2e-2
+
+
+def test_config4_gemma_head_full_size():
+    """d=3840, V=262144, 8 rows, k in {2048, 8192, 32768}, one set per step and one per row."""
+    c = CONFIGS[4]
+    say("drawing the 262144 x 3840 output embedding")
+    U = c.weights()
+    tU = to_dev(U)
+    h = c.hidden(1)[0]
+    th = to_dev(h)
+    rng = make_rng(4, 2)
+    for k in c.k_sweep:
+        say(f"config 4 k={k}")
+        shared = zipf_subset(rng, c.V, k)
+        z = sv.subset_logits(th, tU, torch.from_numpy(shared).to(DEV)).cpu().numpy()
+        sample = rng.permutation(k)[:512]
+        z_ref = oracle.subset_logits(h, U, shared[sample])
+        assert_logits_close(z[:, sample], z_ref, "bf16")
+        per_row = np.stack([zipf_subset(rng, c.V, k) for _ in range(c.rows)])
+        z = sv.subset_logits(th, tU, torch.from_numpy(per_row).to(DEV))
+        z_ref = oracle.subset_logits(h, U, per_row[:, sample])
+        assert_logits_close(z.cpu().numpy()[:, sample], z_ref, "bf16")
+        tok, _, _ = sv.draft_topk(z, torch.from_numpy(per_row).to(DEV), c.kd)
+        tok_same, _ = oracle.softmax_topk(z.cpu().numpy(), per_row, c.kd)
+        assert np.array_equal(tok.cpu().numpy(), tok_same)
+    say("config 4 dense baseline on sampled vocabulary entries")
+    zd = sv.dense_logits(th, tU).cpu().numpy()
+    sample = rng.permutation(c.V)[:2048].astype(np.int32)
+    assert_logits_close(zd[:, sample], oracle.subset_logits(h, U, sample), "bf16")
+    del tU
+    torch.cuda.empty_cache()
+
+
+def test_config5_full_step_with_selection():
+    """d=4096, V=151936, 512 rows, selector d'=256, k=8192, top-10: select -> logits -> top-kd."""
+    c = CONFIGS[5]
+    say("drawing the Qwen3-8B-shaped head and selector")
+    U = c.weights()
+    Wd, Wv = c.selector()
+    h = c.hidden(1)[0]
+    tU, tWd, tWv, th = to_dev(U), to_dev(Wd), to_dev(Wv), to_dev(h)
+    say("config 5 select")
+    sel, _ = sv.select(th, tWd, tWv, c.k)
+    say("config 5 subset logits")
+    z = sv.subset_logits(th, tU, sel)
+    say("config 5 draft top-kd")
+    tok, prob, _ = sv.draft_topk(z, sel, c.kd)
+    torch.cuda.synchronize()
+    seln, zn, tokn, probn = sel.cpu().numpy(), z.cpu().numpy(), tok.cpu().numpy(), prob.cpu().numpy()
+    # every row: a valid, ascending, unique id set
+    assert seln.min() >= 0 and seln.max() < c.V and np.all(np.diff(seln, axis=1) > 0)
+    tok_same, prob_same = oracle.softmax_topk(zn, seln, c.kd)
+    assert np.array_equal(tokn, tok_same)
+    assert np.allclose(probn, prob_same, rtol=1e-3, atol=1e-6)
+    for r in (0, 255, 511):                       # sampled rows against the oracle
+        say(f"config 5 oracle row {r}")
+        ref_sel, _, s_ref, _ = oracle.select(h[r:r + 1], Wd, Wv, c.k, full=True)
+        band, diff = check_selected_set(seln[r], s_ref[0], ref_sel[0], c.k, "bf16")
+        say(f"  {band} scores within tolerance of the k-th, {diff} ids differ from the oracle")
+        z_ref = oracle.subset_logits(h[r:r + 1], U, seln[r:r + 1])
+        assert_logits_close(zn[r:r + 1], z_ref, "bf16")

@@ -51,24 +51,35 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 
 
 def normal_matrix(rng: np.random.Generator, shape, std: float, dtype: str,
-                  chunk_rows: int = 8192) -> np.ndarray:
-    """N(0, std^2) matrix. dtype 'f32' -> float32 array; 'bf16' -> uint16 bit patterns."""
+                  chunk_rows: int = 4096, workers: int = 8) -> np.ndarray:
+    """N(0, std^2) matrix. dtype 'f32' -> float32 array; 'bf16' -> uint16 bit patterns.
+
+    Matrices are drawn in blocks of `chunk_rows` rows, block i from the i-th child generator
+    spawned from `rng`, so the result does not depend on how many threads fill the blocks."""
     shape = tuple(int(s) for s in shape)
-    if dtype == "f32":
-        out = rng.standard_normal(shape, dtype=np.float32)
-        out *= np.float32(std)
-        return out
-    if dtype != "bf16":
+    if dtype not in ("f32", "bf16"):
         raise ValueError(f"unknown dtype {dtype!r}")
     if len(shape) == 1:
-        return f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32) * np.float32(std))
-    out = np.empty(shape, dtype=np.uint16)
+        x = rng.standard_normal(shape, dtype=np.float32) * np.float32(std)
+        return x if dtype == "f32" else f32_to_bf16_bits(x)
     rows = shape[0]
-    for r0 in range(0, rows, chunk_rows):
+    starts = list(range(0, rows, chunk_rows))
+    children = rng.spawn(len(starts))
+    out = np.empty(shape, dtype=np.float32 if dtype == "f32" else np.uint16)
+
+    def fill(i):
+        r0 = starts[i]
         r1 = min(rows, r0 + chunk_rows)
-        blk = rng.standard_normal((r1 - r0,) + shape[1:], dtype=np.float32)
+        blk = children[i].standard_normal((r1 - r0,) + shape[1:], dtype=np.float32)
         blk *= np.float32(std)
-        out[r0:r1] = f32_to_bf16_bits(blk)
+        out[r0:r1] = blk if dtype == "f32" else f32_to_bf16_bits(blk)
+
+    if len(starts) == 1:
+        fill(0)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=workers) as pool:
+            list(pool.map(fill, range(len(starts))))
     return out
 
 
