@@ -7,7 +7,6 @@
 namespace sv {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 enum { DT_F32 = 0, DT_BF16 = 1 };
 
@@ -26,14 +25,17 @@ __device__ __forceinline__ u32x4 load16(const u32x4* p) {
     else return *p;
 }
 
-// acc + <w, x> over the 16 bytes held in w and x (8 bf16 pairs or 4 float32 pairs), fp32 accumulate
+// acc + <w, x> over the 16 bytes held in w and x (8 bf16 pairs or 4 float32 pairs), fp32 accumulate.
+// bf16 -> fp32 widening is a shift (low element) or a mask (high element); each product is exact in
+// fp32 and enters the accumulator through one fused multiply-add.
 template <int DT>
 __device__ __forceinline__ float dot16(const u32x4 w, const u32x4 x, float acc) {
     if constexpr (DT == DT_BF16) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w[i]),
-                                                  __builtin_bit_cast(bf16x2_t, x[i]), acc, false);
+        for (int i = 0; i < 4; ++i) {
+            acc = fmaf(__uint_as_float(w[i] << 16), __uint_as_float(x[i] << 16), acc);
+            acc = fmaf(__uint_as_float(w[i] & 0xFFFF0000u), __uint_as_float(x[i] & 0xFFFF0000u), acc);
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < 4; ++i) acc = fmaf(__uint_as_float(w[i]), __uint_as_float(x[i]), acc);
