@@ -1,0 +1,249 @@
+#!/usr/bin/env python3
+"""Benchmark of the SpecVocab draft-step hot path on one MI355X.
+
+Workload (N=1): the Llama-3-8B-shaped chain-drafting configuration -- d=4096, V=128256, bf16
+output embedding, one hidden row per draft step, k=8192 Zipf(1.1)-biased sorted unique indices,
+1000 distinct seeded (h, idx) steps.  One "step" = subset logits (gathered rows of U) -> subset
+softmax -> top-10 draft tokens.  The K timed steps are replayed from one HIP graph (the paper
+benchmarks under device graphs for the same reason: launch overhead would hide the kernel).
+
+Prints ONE JSON line.  Besides the contract fields it carries
+  roofline      the dominant kernel (the row gather) alone, algorithmic bytes / launch duration
+  cpu_baseline  the CPU oracle on a bounded sample of the same steps
+  dense         the full-vocabulary projection on the same GPU and the resulting speed-up
+  cold          the same step with U rotated over 8 copies, so that no row can be served from the
+                256 MB last-level cache (the one-U numbers are what a drafter really sees)
+  select        the selector (W_down, W_vocab, top-k) at the same shape, and the step with it
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E, published peak
+
+
+def parse_args():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=1000)
+    p.add_argument("--warmup", type=int, default=1000)
+    p.add_argument("--distinct", type=int, default=1000, help="distinct (h, idx) steps to draw")
+    p.add_argument("--cold-copies", type=int, default=8)
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-extras", action="store_true", help="skip dense / cold / select legs")
+    p.add_argument("--cpu-seconds", type=float, default=12.0)
+    return p.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2602_13836_amd as sv
+    from workloads import CONFIGS
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    sv.load_library()                       # fails loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    c = CONFIGS[2]
+    K, W = int(args.steps), int(args.warmup)
+    nd = max(1, min(int(args.distinct), c.steps))
+    es = c.esize()
+
+    def dev_bf16(a):
+        return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+
+    t0 = time.time()
+    U_np = c.weights()
+    h_np = c.hidden(nd)                     # [nd, 1, d]
+    idx_np = c.indices(nd)                  # [nd, 1, k]
+    U = dev_bf16(U_np)
+    h = dev_bf16(h_np.reshape(nd * c.rows, c.d)).reshape(nd, c.rows, c.d)
+    idx = torch.from_numpy(idx_np).to(dev)
+    z = torch.empty((nd, c.rows, c.k), dtype=torch.float32, device=dev)
+    tok = torch.empty((nd, c.rows, c.kd), dtype=torch.int32, device=dev)
+    prob = torch.empty((nd, c.rows, c.kd), dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    t_setup = time.time() - t0
+
+    stream = torch.cuda.Stream()            # default priority
+
+    def step(t, U_t=U):
+        i = t % nd
+        sv.subset_logits(h[i], U_t, idx[i], out=z[i])
+        sv.draft_topk(z[i], idx[i], c.kd, tok_out=tok[i], prob_out=prob[i])
+
+    def capture(fn, n):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(stream):
+            fn(0)                           # eager once: loads code objects before capture
+            torch.cuda.synchronize()
+            with torch.cuda.graph(g, stream=stream):
+                for t in range(n):
+                    fn(t)
+        torch.cuda.synchronize()
+        return g
+
+    def timed_replays(g, reps):
+        """ms per replay, HIP events on the replay stream."""
+        out = []
+        with torch.cuda.stream(stream):
+            for _ in range(reps):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                g.replay()
+                e1.record(stream)
+                e1.synchronize()
+                out.append(e0.elapsed_time(e1))
+        return out
+
+    # ---------------- the timed region: exactly K steps, one graph replay
+    g_step = capture(step, K)
+    with torch.cuda.stream(stream):
+        for _ in range((W + K - 1) // K if W > 0 else 0):
+            g_step.replay()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    with torch.cuda.stream(stream):
+        g_step.replay()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t1) * 1e3
+    rep = sorted(timed_replays(g_step, 10))
+    us_per_step = wall_ms * 1e3 / K
+    us_per_step_median = rep[len(rep) // 2] * 1e3 / K
+
+    # ---------------- roofline of the dominant kernel: the row gather alone
+    gather_bytes = c.k * c.d * es + c.k * 4 + c.d * es + c.k * 4      # U rows + idx + h + logits out
+    g_gather = capture(lambda t: sv.subset_logits(h[t % nd], U, idx[t % nd], out=z[t % nd]), K)
+    timed_replays(g_gather, 2)
+    gr = sorted(timed_replays(g_gather, 10))
+    gather_us = gr[len(gr) // 2] * 1e3 / K
+    gather_gbps = gather_bytes / (gather_us * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": "gemv_rows_kernel (row gather, 1 row x 8192 indices)",
+                "achieved": round(gather_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(gather_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                "bytes_per_launch": gather_bytes, "us_per_launch": round(gather_us, 3)}
+
+    result = {
+        "metric": "subset-logits us/draft-step",
+        "value": round(us_per_step, 3),
+        "unit": "us/draft-step",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": round(wall_ms / K, 6),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "config 2, Llama-3-8B-shaped chain drafting: d=4096 V=128256 bf16 U, rows=1, "
+                               "k=8192 Zipf(1.1) sorted unique idx, kd=10; step = subset logits + softmax + top-10",
+                   "distinct_steps": nd, "graph_replay": True, "d": c.d, "V": c.V, "k": c.k, "kd": c.kd,
+                   "rows": c.rows},
+        "us_per_step_median_of_10_replays": round(us_per_step_median, 3),
+        "achieved_GBps_whole_step": round(gather_bytes / (us_per_step * 1e-6) / 1e9, 1),
+        "pct_hbm_peak_whole_step": round(100 * gather_bytes / (us_per_step * 1e-6) / 1e9 / HBM_PEAK_GBPS, 2),
+        "roofline": roofline,
+        "setup_s": round(t_setup, 1),
+    }
+
+    if not args.no_extras:
+        # ---------------- dense full-vocabulary baseline on the same GPU
+        nden = 50
+        zd = torch.empty((c.rows, c.V), dtype=torch.float32, device=dev)
+        g_dense = capture(lambda t: sv.dense_logits(h[t % nd], U, out=zd), nden)
+        timed_replays(g_dense, 2)
+        dr = sorted(timed_replays(g_dense, 5))
+        dense_us = dr[len(dr) // 2] * 1e3 / nden
+        dense_bytes = c.V * c.d * es + c.V * 4 + c.d * es
+        result["dense"] = {"us_per_step": round(dense_us, 2),
+                           "GBps": round(dense_bytes / (dense_us * 1e-6) / 1e9, 1),
+                           "frac_hbm_peak": round(dense_bytes / (dense_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                           "speedup_subset_logits_kernel": round(dense_us / gather_us, 2),
+                           "speedup_whole_step": round(dense_us / us_per_step, 2)}
+        del g_dense, zd
+
+        # ---------------- cold: rotate U over several copies so no row is re-touched in cache
+        ncopy = max(1, int(args.cold_copies))
+        copies = [U] + [U.clone() for _ in range(ncopy - 1)]
+        g_cold = capture(lambda t: step(t, copies[t % ncopy]), K)
+        timed_replays(g_cold, 1)
+        cr = sorted(timed_replays(g_cold, 5))
+        cold_us = cr[len(cr) // 2] * 1e3 / K
+        g_coldg = capture(lambda t: sv.subset_logits(h[t % nd], copies[t % ncopy], idx[t % nd], out=z[t % nd]), K)
+        timed_replays(g_coldg, 1)
+        cgr = sorted(timed_replays(g_coldg, 5))
+        coldg_us = cgr[len(cgr) // 2] * 1e3 / K
+        result["cold"] = {"copies_of_U": ncopy, "us_per_step": round(cold_us, 3),
+                          "gather_kernel_us": round(coldg_us, 3),
+                          "gather_GBps": round(gather_bytes / (coldg_us * 1e-6) / 1e9, 1),
+                          "gather_frac_hbm_peak": round(gather_bytes / (coldg_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
+        del g_cold, g_coldg, copies
+        torch.cuda.empty_cache()
+
+        # ---------------- the selector at the same shape, and the whole step including it
+        Wd_np, Wv_np = c.selector()
+        Wd, Wv = dev_bf16(Wd_np), dev_bf16(Wv_np)
+        ws = torch.empty(sv.workspace_bytes(sv.SV_OP_SELECT, c.rows, c.d, c.V, c.k, c.d_prime, 0, sv.SV_BF16),
+                         dtype=torch.uint8, device=dev)
+        sel = torch.empty((c.rows, c.k), dtype=torch.int32, device=dev)
+        nsel = 200
+        g_sel = capture(lambda t: sv.select(h[t % nd], Wd, Wv, c.k, idx_out=sel, ws=ws), nsel)
+        timed_replays(g_sel, 2)
+        sr = sorted(timed_replays(g_sel, 5))
+        sel_us = sr[len(sr) // 2] * 1e3 / nsel
+
+        def full(t):
+            i = t % nd
+            sv.select(h[i], Wd, Wv, c.k, idx_out=sel, ws=ws)
+            sv.subset_logits(h[i], U, sel, out=z[i])
+            sv.draft_topk(z[i], sel, c.kd, tok_out=tok[i], prob_out=prob[i])
+        g_full = capture(full, nsel)
+        timed_replays(g_full, 2)
+        fr = sorted(timed_replays(g_full, 5))
+        full_us = fr[len(fr) // 2] * 1e3 / nsel
+        result["select"] = {"d_prime": c.d_prime, "select_us": round(sel_us, 2),
+                            "step_with_select_us": round(full_us, 2),
+                            "speedup_vs_dense": round(result["dense"]["us_per_step"] / full_us, 2)}
+
+    # ---------------- CPU oracle on a bounded sample of the same steps
+    if not args.no_cpu_baseline:
+        import oracle
+        n_cpu, t_cpu = 0, 0.0
+        tc0 = time.perf_counter()
+        while n_cpu < nd and (time.perf_counter() - tc0) < args.cpu_seconds:
+            i = n_cpu
+            z_ref = oracle.subset_logits(h_np[i], U_np, idx_np[i])
+            oracle.softmax_topk(z_ref, idx_np[i], c.kd)
+            n_cpu += 1
+        t_cpu = time.perf_counter() - tc0
+        result["cpu_baseline"] = {"value": round(t_cpu / n_cpu * 1e6, 1), "unit": "us/draft-step", "cores": 1,
+                                  "kind": "oracle",
+                                  "sample": f"first {n_cpu} of the {nd} steps of the same workload "
+                                            f"(subset logits + softmax + top-{c.kd}), single thread",
+                                  "host_cpus": os.cpu_count()}
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -55,7 +55,7 @@ SelectWs select_ws(int64_t rows, int64_t V, int64_t d_prime, int dt) {
     w.hp_off = 0;
     w.s_off = round256((size_t)rows * (size_t)d_prime * (size_t)esize_of(dt));
     w.radix_off = w.s_off + round256((size_t)rows * (size_t)V * sizeof(float));
-    w.total = w.radix_off + round256(sv::radix_scratch_words(rows, V) * sizeof(uint32_t));
+    w.total = w.radix_off + round256(sv::select_scratch_words(rows, V) * sizeof(uint32_t));
     return w;
 }
 
@@ -66,7 +66,7 @@ int check_select_shape(int64_t rows, int64_t d, int64_t V, int64_t k, int64_t d_
     if (st != SV_OK) return st;
     st = check_row(d_prime, d_prime, dt);
     if (st != SV_OK) return st;
-    if (d > (1 << 24) || d_prime > (1 << 24)) return SV_ERR_UNSUPPORTED;
+    if (d > (1 << 24) || d_prime > (1 << 24) || V > sv::select_max_vocab()) return SV_ERR_UNSUPPORTED;
     return SV_OK;
 }
 
@@ -145,19 +145,22 @@ int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh, const 
     g.out_f32 = dt == SV_BF16 ? nullptr : reinterpret_cast<float*>(hp);
     g.out_bf16 = dt == SV_BF16 ? reinterpret_cast<uint16_t*>(hp) : nullptr;
     g.out_row_stride = d_prime;
+    g.zero_ptr = radix;                      // the selection's counters and histogram start at zero
+    sv::select_zero_range(rows, V, &g.zero_words);
     if (sv::launch_gemv(dt, g, s) != hipSuccess) return SV_ERR_HIP;
 
-    // Step 1b: s = W_vocab h'
+    // Step 1b: s = W_vocab h' (with the first histogram pass of the selection)
     const int vchunks = (int)(d_prime * es / 16);
     if (sv::scores_supported(vchunks)) {
         sv::ScoresArgs sa{};
         sa.hp = hp;
         sa.Wv = static_cast<const char*>(W_vocab);
         sa.V = V;
+        sa.k = k;
         sa.chunks = vchunks;
         sa.rows = (int)rows;
         sa.s = scores;
-        if (sv::launch_scores(dt, sa, s) != hipSuccess) return SV_ERR_HIP;
+        if (sv::launch_scores_hist(dt, sa, radix, s) != hipSuccess) return SV_ERR_HIP;
     } else {
         sv::GemvArgs g2{};
         g2.x = hp;
@@ -170,6 +173,7 @@ int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh, const 
         g2.out_f32 = scores;
         g2.out_row_stride = V;
         if (sv::launch_gemv(dt, g2, s) != hipSuccess) return SV_ERR_HIP;
+        if (sv::launch_hist(scores, V, k, (int)rows, radix, s) != hipSuccess) return SV_ERR_HIP;
     }
 
     // Step 2: exact top-k, ascending ids
@@ -181,7 +185,7 @@ int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh, const 
     ra.idx_out = idx_out;
     ra.scores_out = scores_out;
     ra.scratch = radix;
-    if (sv::launch_radix_select(ra, s) != hipSuccess) return SV_ERR_HIP;
+    if (sv::launch_topk_of_scores(ra, s) != hipSuccess) return SV_ERR_HIP;
     return SV_OK;
 }
 

@@ -18,6 +18,12 @@ __global__ __launch_bounds__(256) void gemv_rows_kernel(const GemvArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t r = blockIdx.y;
     const int C = a.chunks;
+    if (a.zero_words) {     // clear a later kernel's scratch with this launch
+        const size_t nthr = (size_t)gridDim.x * gridDim.y * blockDim.x;
+        for (size_t i = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x; i < a.zero_words;
+             i += nthr)
+            a.zero_ptr[i] = 0u;
+    }
 
     const u32x4* xp = reinterpret_cast<const u32x4*>(a.x + r * a.x_row_bytes);
     u32x4 xreg[NL];
@@ -74,6 +80,12 @@ __global__ __launch_bounds__(256) void gemv_long_rows_kernel(const GemvArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t r = blockIdx.y;
     const int C = a.chunks;
+    if (a.zero_words) {     // clear a later kernel's scratch with this launch
+        const size_t nthr = (size_t)gridDim.x * gridDim.y * blockDim.x;
+        for (size_t i = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x; i < a.zero_words;
+             i += nthr)
+            a.zero_ptr[i] = 0u;
+    }
     const u32x4* xp = reinterpret_cast<const u32x4*>(a.x + r * a.x_row_bytes);
     const int32_t* idx = a.idx ? a.idx + r * a.idx_row_stride : nullptr;
     const int64_t n = a.n_items;

@@ -108,6 +108,19 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t x) {
                   umax64(readlane_u64(x, 32), readlane_u64(x, 48)));
 }
 
+__device__ __forceinline__ uint32_t umax32(uint32_t a, uint32_t b) { return a > b ? a : b; }
+
+// max over all 64 lanes, result uniform across the wave. All lanes must be active.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
+    x = umax32(x, dpp_u32<DPP_QUAD_1032>(x));
+    x = umax32(x, dpp_u32<DPP_QUAD_2301>(x));
+    x = umax32(x, dpp_u32<DPP_ROW_HALF_MIRROR>(x));
+    x = umax32(x, dpp_u32<DPP_ROW_MIRROR>(x));
+    const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)x, 0), b = (uint32_t)__builtin_amdgcn_readlane((int)x, 16);
+    const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)x, 32), d = (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
+    return umax32(umax32(a, b), umax32(c, d));
+}
+
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x) {
     x += dpp_u32<DPP_QUAD_1032>(x);
     x += dpp_u32<DPP_QUAD_2301>(x);

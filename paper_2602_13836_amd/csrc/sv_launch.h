@@ -32,22 +32,28 @@ struct GemvArgs {
     float* out_f32;
     uint16_t* out_bf16;
     int64_t out_row_stride;
+    uint32_t* zero_ptr;      // optional: words cleared by the same launch (scratch of a later kernel)
+    size_t zero_words;
 };
 hipError_t launch_gemv(int dt, const GemvArgs& a, hipStream_t stream);
 
-// s[r, v] = < W_vocab[v, :], hp[r, :] > for short rows (d_prime * esize <= 1024 bytes)
+// s[r, v] = < W_vocab[v, :], hp[r, :] > for short rows (d_prime * esize <= 1024 bytes), fused with the
+// first histogram pass of the top-k selection
 struct ScoresArgs {
     const char* hp;        // [rows x d_prime] in dt
     const char* Wv;        // [V x d_prime] in dt, dense rows
     int64_t V;
+    int64_t k;
     int chunks;            // d_prime * esize / 16
     int rows;
     float* s;              // [rows x V]
 };
 bool scores_supported(int chunks);
-hipError_t launch_scores(int dt, const ScoresArgs& a, hipStream_t stream);
+hipError_t launch_scores_hist(int dt, const ScoresArgs& a, uint32_t* scratch, hipStream_t stream);
+// the histogram pass alone, for scores produced by another kernel
+hipError_t launch_hist(const float* s, int64_t V, int64_t k, int rows, uint32_t* scratch, hipStream_t stream);
 
-// exact top-k of every row of s by MSB-first radix selection, ids ascending
+// exact top-k of every row of s (after the histogram pass), ids ascending
 struct RadixArgs {
     const float* s;        // [rows x V]
     int64_t V;
@@ -55,10 +61,13 @@ struct RadixArgs {
     int64_t k;
     int32_t* idx_out;      // [rows x k]
     float* scores_out;     // [rows x k] or nullptr
-    uint32_t* scratch;     // radix_scratch_words(rows, V) uint32 words
+    uint32_t* scratch;     // select_scratch_words(rows, V) uint32 words; the first
+                           // select_zero_range() words must be zero before the histogram pass
 };
-size_t radix_scratch_words(int64_t rows, int64_t V);
-hipError_t launch_radix_select(const RadixArgs& a, hipStream_t stream);
+int64_t select_max_vocab();
+size_t select_scratch_words(int64_t rows, int64_t V);
+void select_zero_range(int64_t rows, int64_t V, size_t* words);
+hipError_t launch_topk_of_scores(const RadixArgs& a, hipStream_t stream);
 
 // subset softmax + top-kd
 struct TopkArgs {
