@@ -40,6 +40,9 @@ def parse_args():
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-extras", action="store_true", help="skip dense / cold / select legs")
     p.add_argument("--cpu-seconds", type=float, default=12.0)
+    p.add_argument("--counter-run", action="store_true",
+                   help="for rocprofv3 --pmc: a few eager (ungraphed) steps plus 1 GiB reference copies, "
+                        "no timing, no JSON line")
     return p.parse_args()
 
 
@@ -87,9 +90,10 @@ def main():
     stream = torch.cuda.Stream()            # default priority
 
     def step(t, U_t=U):
+        """one draft step: gathered logits + subset softmax + top-kd (specvocab_draft_step)"""
         i = t % nd
-        sv.subset_logits(h[i], U_t, idx[i], out=z[i])
-        sv.draft_topk(z[i], idx[i], c.kd, tok_out=tok[i], prob_out=prob[i])
+        sv.draft_step(h[i], U_t, idx[i], c.kd, logits_out=z[i], tok_out=tok[i], prob_out=prob[i])
+
 
     def capture(fn, n):
         g = torch.cuda.CUDAGraph()
@@ -115,6 +119,19 @@ def main():
                 out.append(e0.elapsed_time(e1))
         return out
 
+    if args.counter_run:
+        # hardware counters are read per dispatch; a plain copy of known size calibrates them
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        for _ in range(3):
+            dst.copy_(src)
+        for t in range(min(K, 40)):
+            step(t)
+        torch.cuda.synchronize()
+        print("counter run done: 3 x 1 GiB copies, then eager steps", flush=True)
+        return
+
     # ---------------- the timed region: exactly K steps, one graph replay
     g_step = capture(step, K)
     with torch.cuda.stream(stream):
@@ -130,16 +147,22 @@ def main():
     us_per_step = wall_ms * 1e3 / K
     us_per_step_median = rep[len(rep) // 2] * 1e3 / K
 
-    # ---------------- roofline of the dominant kernel: the row gather alone
-    gather_bytes = c.k * c.d * es + c.k * 4 + c.d * es + c.k * 4      # U rows + idx + h + logits out
+    # ---------------- roofline of the dominant kernel: the row gather (specvocab_subset_logits)
+    # algorithmic bytes of one launch: the k gathered rows of U + idx + h + the logits written
+    gather_bytes = c.k * c.d * es + c.k * 4 + c.d * es + c.k * 4
     g_gather = capture(lambda t: sv.subset_logits(h[t % nd], U, idx[t % nd], out=z[t % nd]), K)
     timed_replays(g_gather, 2)
     gr = sorted(timed_replays(g_gather, 10))
     gather_us = gr[len(gr) // 2] * 1e3 / K
     gather_gbps = gather_bytes / (gather_us * 1e-6) / 1e9
-    roofline = {"bound": "hbm", "kernel": "gemv_rows_kernel (row gather, 1 row x 8192 indices)",
+    # HBM-side bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB plain copy
+    # (profiles/gather_gemv_config2_hbm_traffic.md)
+    traffic_bytes = 67.385e6 + 0.033e6
+    roofline = {"bound": "hbm",
+                "kernel": "gemv_rows_kernel<bf16, 8 loads/lane, 2 rows/wave>: row gather of 8192 rows of U "
+                          "(specvocab_subset_logits), 1 of the 2 launches of a step",
                 "achieved": round(gather_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(gather_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                "frac": round(gather_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic_bytes,
                 "bytes_per_launch": gather_bytes, "us_per_launch": round(gather_us, 3)}
 
     result = {

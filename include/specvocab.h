@@ -66,7 +66,8 @@ typedef enum {
     SV_OP_SELECT = 0,
     SV_OP_SUBSET_LOGITS = 1,
     SV_OP_DRAFT_TOPK = 2,
-    SV_OP_DENSE_LOGITS = 3
+    SV_OP_DENSE_LOGITS = 3,
+    SV_OP_DRAFT_STEP = 4
 } sv_op;
 
 /* Largest kd the draft top-kd accepts. */
@@ -124,6 +125,18 @@ int specvocab_subset_logits(const void* h, int64_t rows, int64_t d, int64_t ldh,
 int specvocab_draft_topk(const float* logits, const int32_t* idx, int idx_mode,
                          int64_t rows, int64_t k, int64_t kd,
                          int32_t* tok_out, float* prob_out, float* probs_full_out,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/* The whole draft step after selection: specvocab_subset_logits followed by specvocab_draft_topk on
+ * the logits it produced (Section 3.3 Step 3 and q_K = softmax(z'), then the top-kd tokens), with the
+ * same arguments, results and tie rule as those two calls, enqueued back to back on `stream`.
+ * (Two kernels on purpose: on this multi-die GPU a kernel boundary is the cheapest device-wide
+ * synchronisation; a single-launch version with an in-kernel hand-over measured slower.)
+ * logits_out: device [rows x k] float32, required (the top-kd stage reads it). */
+int specvocab_draft_step(const void* h, int64_t rows, int64_t d, int64_t ldh,
+                         const void* U, int64_t V, int64_t ldu, int dt,
+                         const int32_t* idx, int64_t k, int idx_mode, int64_t kd,
+                         float* logits_out, int32_t* tok_out, float* prob_out, float* probs_full_out,
                          void* ws, size_t ws_bytes, void* stream);
 
 /* Section 3.1, the full-vocabulary baseline:  logits_out[r, v] = < U[v, :], h[r, :] >.

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libspecvocab.so")
 SV_OK = 0
 SV_F32, SV_BF16 = 0, 1
 SV_IDX_PER_ROW, SV_IDX_PER_STEP = 0, 1
-SV_OP_SELECT, SV_OP_SUBSET_LOGITS, SV_OP_DRAFT_TOPK, SV_OP_DENSE_LOGITS = 0, 1, 2, 3
+SV_OP_SELECT, SV_OP_SUBSET_LOGITS, SV_OP_DRAFT_TOPK, SV_OP_DENSE_LOGITS, SV_OP_DRAFT_STEP = 0, 1, 2, 3, 4
 MAX_KD = 64
 
 EXPORTS = (
@@ -28,6 +28,7 @@ EXPORTS = (
     "specvocab_select",
     "specvocab_subset_logits",
     "specvocab_draft_topk",
+    "specvocab_draft_step",
     "specvocab_dense_logits",
 )
 
@@ -68,6 +69,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
                                             ctypes.c_size_t, vp]
     lib.specvocab_draft_topk.restype = ci
     lib.specvocab_draft_topk.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.specvocab_draft_step.restype = ci
+    lib.specvocab_draft_step.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, ci, i64, vp, vp, vp, vp, vp,
+                                         ctypes.c_size_t, vp]
     lib.specvocab_dense_logits.restype = ci
     lib.specvocab_dense_logits.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, vp, ctypes.c_size_t, vp]
     if path is None:
@@ -218,6 +222,41 @@ def draft_topk(logits: torch.Tensor, idx: torch.Tensor, kd: int,
                                                0 if ws is None else ws.numel(), _stream(stream)),
            "specvocab_draft_topk")
     return tok_out, prob_out, probs_full_out
+
+
+def draft_step(h: torch.Tensor, U: torch.Tensor, idx: torch.Tensor, kd: int,
+               logits_out: Optional[torch.Tensor] = None, tok_out: Optional[torch.Tensor] = None,
+               prob_out: Optional[torch.Tensor] = None, probs_full_out: Optional[torch.Tensor] = None,
+               want_probs: bool = False, ws: Optional[torch.Tensor] = None,
+               stream: Optional[torch.cuda.Stream] = None):
+    """specvocab_draft_step: subset logits, subset softmax and top-kd tokens of every row, in one
+    launch where the shape allows. Returns (logits [rows x k], tok [rows x kd], prob [rows x kd],
+    q_K [rows x k] or None)."""
+    rows, d, ldh = _mat(h, "h")
+    V, d2, ldu = _mat(U, "U")
+    if d2 != d:
+        raise ValueError("U and h disagree on d")
+    dt = _dt(h)
+    if _dt(U) != dt:
+        raise TypeError("h and U must share a dtype")
+    mode, k = _idx(idx, rows)
+    dev = h.device
+    if logits_out is None:
+        logits_out = torch.empty((rows, k), dtype=torch.float32, device=dev)
+    if tok_out is None:
+        tok_out = torch.empty((rows, kd), dtype=torch.int32, device=dev)
+    if prob_out is None:
+        prob_out = torch.empty((rows, kd), dtype=torch.float32, device=dev)
+    if probs_full_out is None and want_probs:
+        probs_full_out = torch.empty((rows, k), dtype=torch.float32, device=dev)
+    nbytes = workspace_bytes(SV_OP_DRAFT_STEP, rows, d, V, k, 0, kd, dt, mode)
+    ws = _workspace(nbytes, dev, ws)
+    _check(load_library().specvocab_draft_step(_ptr(h), rows, d, ldh, _ptr(U), V, ldu, dt, _ptr(idx), k, mode, kd,
+                                               _ptr(logits_out), _ptr(tok_out), _ptr(prob_out),
+                                               _ptr(probs_full_out), _ptr(ws), 0 if ws is None else ws.numel(),
+                                               _stream(stream)),
+           "specvocab_draft_step")
+    return logits_out, tok_out, prob_out, probs_full_out
 
 
 def dense_logits(h: torch.Tensor, U: torch.Tensor, out: Optional[torch.Tensor] = None,

@@ -106,6 +106,7 @@ int specvocab_workspace_bytes(int op, int64_t rows, int64_t d, int64_t V, int64_
         case SV_OP_SUBSET_LOGITS:
         case SV_OP_DRAFT_TOPK:
         case SV_OP_DENSE_LOGITS:
+        case SV_OP_DRAFT_STEP:
             return SV_OK;
         default:
             return SV_ERR_DTYPE;
@@ -242,6 +243,52 @@ int specvocab_draft_topk(const float* logits, const int32_t* idx, int idx_mode, 
     t.prob_out = prob_out;
     t.probs_full_out = probs_full_out;
     if (sv::launch_softmax_topk(t, static_cast<hipStream_t>(stream)) != hipSuccess) return SV_ERR_HIP;
+    return SV_OK;
+}
+
+int specvocab_draft_step(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* U, int64_t V,
+                         int64_t ldu, int dt, const int32_t* idx, int64_t k, int idx_mode, int64_t kd,
+                         float* logits_out, int32_t* tok_out, float* prob_out, float* probs_full_out, void* ws,
+                         size_t ws_bytes, void* stream) {
+    (void)ws;
+    (void)ws_bytes;
+    if (!h || !U || !idx || !logits_out || !tok_out || !prob_out) return SV_ERR_NULL;
+    if (!dtype_ok(dt) || !mode_ok(idx_mode)) return SV_ERR_DTYPE;
+    if (rows < 1 || rows > kMaxRows || V < 1 || V > kMaxVocab || k < 1 || k > kMaxVocab || kd < 1 || kd > k)
+        return SV_ERR_SHAPE;
+    if (kd > SPECVOCAB_MAX_KD) return SV_ERR_UNSUPPORTED;
+    int st = check_row(d, ldh, dt);
+    if (st != SV_OK) return st;
+    st = check_row(d, ldu, dt);
+    if (st != SV_OK) return st;
+    if (!aligned16(h) || !aligned16(U)) return SV_ERR_ALIGN;
+
+    const int es = esize_of(dt);
+    sv::GemvArgs g{};
+    g.x = static_cast<const char*>(h);
+    g.x_row_bytes = ldh * es;
+    g.M = static_cast<const char*>(U);
+    g.m_row_bytes = ldu * es;
+    g.idx = idx;
+    g.idx_row_stride = idx_mode == SV_IDX_PER_ROW ? k : 0;
+    g.n_items = k;
+    g.chunks = (int)(d * es / 16);
+    g.rows = (int)rows;
+    g.out_f32 = logits_out;
+    g.out_row_stride = k;
+    sv::TopkArgs t{};
+    t.logits = logits_out;
+    t.idx = idx;
+    t.idx_row_stride = g.idx_row_stride;
+    t.rows = (int)rows;
+    t.k = k;
+    t.kd = (int)kd;
+    t.tok_out = tok_out;
+    t.prob_out = prob_out;
+    t.probs_full_out = probs_full_out;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (sv::launch_gemv(dt, g, s) != hipSuccess) return SV_ERR_HIP;
+    if (sv::launch_softmax_topk(t, s) != hipSuccess) return SV_ERR_HIP;
     return SV_OK;
 }
 

@@ -1,21 +1,24 @@
 // Candidate-vocabulary selection (Section 3.3): approximate logits s = W_vocab h' (Step 1) and
 // k_t = top-k(s_t, k) (Step 2), exact, ids in ascending order, ties to the smaller id.
 //
-// Five launches after the down-projection.  Steps that need a result of the whole row sit behind a
-// kernel boundary rather than behind a device-scope fence inside a kernel: on this multi-die part a
-// release fence writes back a whole L2, which costs more than a launch.
+// Four launches after the down-projection.  Every step that needs a result of the whole row sits
+// behind a kernel boundary: on this multi-die part a kernel boundary is the cheapest device-wide
+// synchronisation (a device-scope release fence writes back a whole L2, and atomics on one address
+// serialise at ~50 ns each), so there is no "last block" hand-over and no contended counter.
 //   scores_hist   streams W_vocab once.  A selector row is short (d' = d/16 .. d/8: a few hundred
 //                 bytes), so a wavefront is split into groups of G lanes, one row per group, and
 //                 every load instruction still covers 1 KiB of consecutive memory.  Each score is
 //                 stored and counted into a 4096-bin histogram of the top 12 bits of its
-//                 order-preserving key (LDS per block, merged with global atomics).
-//   locate        one block per row finds the bin B that holds the k-th largest score.
-//   collect       counts, per vocabulary block, the scores in bins above B (all selected) and
-//                 appends the ids of the scores in bin B to a candidate list.
+//                 order-preserving key: in LDS per block, then merged into one of several global
+//                 replicas of the histogram (replicas keep same-address atomics apart).
+//   collect       every block first sums the replicas and finds the bin B that holds the k-th
+//                 largest score (redundantly: cheaper than one more launch); it then counts its
+//                 scores in bins above B (all selected) and appends (key, id) of its scores in
+//                 bin B to the row's candidate list.
 //   resolve       one block per row: MSB-first radix selection among the candidates over the
-//                 remaining 20 key bits and, only if scores tie exactly, the inverted id bits, which
-//                 yields a 64-bit threshold T with  selected(v) <=> (key(v) << 32 | ~v) >= T ; it
-//                 also turns the per-block counts into output offsets.
+//                 remaining 20 key bits and, only if scores tie exactly, the inverted id bits,
+//                 which yields a 64-bit threshold T with  selected(v) <=> (key(v) << 32 | ~v) >= T ;
+//                 it also turns the per-block counts into output offsets.
 //   emit          every block re-evaluates the predicate on its entries in id order and writes the
 //                 selected ids (and scores) at its offset: the output is ascending by construction.
 #include "sv_device.h"
@@ -28,69 +31,107 @@ namespace {
 constexpr int kHistBits = 12;
 constexpr int kHistBins = 1 << kHistBits;                // 4096
 constexpr int kKeyLowBits = 32 - kHistBits;              // 20
-constexpr int kSelThreads = 256;
+constexpr int kScoreThreads = 256;                       // scores_hist workgroup
+constexpr int kSelThreads = 1024;                        // collect / resolve / emit workgroup
+constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kMaxBlocksPerRow = 1024;                   // vocabulary blocks per row in collect / emit
-constexpr int kMaxEpt = 32;                              // entries per thread in collect / emit
+constexpr int kEpt = 4;                                  // entries per thread in collect / emit
+constexpr int kCandPerThread = 8;                        // candidates a resolve thread keeps in registers
 
-// per-row state words (zeroed before every call together with the histogram)
-enum { ST_BIN = 2, ST_ABOVE = 3, ST_NCAND = 4, ST_T_HI = 5, ST_T_LO = 6,
-       ST_WORDS = 8 };
+// per-row state words (zeroed before every call together with the histogram replicas)
+enum { ST_NCAND = 0, ST_T_HI = 1, ST_T_LO = 2, ST_WORDS = 4 };
 
 struct SelLayout {
-    int64_t ept;        // vocabulary entries per thread of a collect / emit block
-    int64_t chunk;      // entries per block
-    int64_t nb;         // blocks per row
-    size_t zero_words;  // per row: state + histogram
-    size_t row_words;   // per row: everything
+    int64_t V;
+    int64_t chunk;      // vocabulary entries per collect / emit block
+    int64_t nb;         // blocks per row (<= kMaxBlocksPerRow)
+    int replicas;       // copies of the global histogram per row
+    size_t zero_words;  // per row: state + histogram replicas
+    size_t rest_words;  // per row: candidate list, per-block counts and offsets, bin info (even)
 };
-__host__ __device__ inline SelLayout sel_layout(int64_t V) {
+__host__ __device__ inline SelLayout sel_layout(int64_t V, int64_t rows) {
     SelLayout L;
-    L.ept = (V + (int64_t)kSelThreads * kMaxBlocksPerRow - 1) / ((int64_t)kSelThreads * kMaxBlocksPerRow);
-    if (L.ept < 4) L.ept = 4;
-    L.chunk = L.ept * kSelThreads;
+    L.V = V;
+    L.chunk = (int64_t)kEpt * kSelThreads;
     L.nb = (V + L.chunk - 1) / L.chunk;
-    L.zero_words = ST_WORDS + kHistBins;
-    L.row_words = L.zero_words + 2 * (size_t)L.nb + (size_t)V;
+    L.replicas = rows <= 2 ? 8 : (rows <= 16 ? 2 : 1);
+    L.zero_words = ST_WORDS + (size_t)L.replicas * kHistBins;
+    L.rest_words = 2 * (size_t)V + 2 * (size_t)L.nb + 2;
     return L;
 }
 struct SelPtrs {
     uint32_t* state;    // [ST_WORDS]
-    uint32_t* hist;     // [kHistBins]
+    uint32_t* hist;     // [replicas][kHistBins]
+    uint64_t* cand;     // [V]   (key << 32 | ~id) of the entries in bin B
     uint32_t* sure;     // [nb]  entries in bins above B per block
     uint32_t* offset;   // [nb]  first output slot of each block
-    uint32_t* cand;     // [V]   ids of the entries in bin B
+    uint32_t* binfo;    // [2]   B, entries above B (every collect block computes the same values)
 };
-// zeroed words of all rows come first so that one contiguous range is cleared
+// the zeroed words of all rows come first, so that one contiguous range is cleared
+__host__ __device__ inline size_t sel_zero_total(int64_t rows, const SelLayout& L) {
+    return ((size_t)rows * L.zero_words + 1) & ~(size_t)1;      // keeps the 64-bit lists 8-byte aligned
+}
 __host__ __device__ inline SelPtrs sel_ptrs(uint32_t* base, int64_t rows, int64_t r, const SelLayout& L) {
     SelPtrs p;
     p.state = base + (size_t)r * L.zero_words;
     p.hist = p.state + ST_WORDS;
-    uint32_t* rest = base + (size_t)rows * L.zero_words + (size_t)r * (L.row_words - L.zero_words);
-    p.sure = rest;
-    p.offset = rest + L.nb;
-    p.cand = rest + 2 * L.nb;
+    uint32_t* rest = base + sel_zero_total(rows, L) + (size_t)r * L.rest_words;
+    p.cand = reinterpret_cast<uint64_t*>(rest);
+    p.sure = rest + 2 * (size_t)L.V;
+    p.offset = p.sure + L.nb;
+    p.binfo = p.offset + L.nb;
     return p;
 }
 
-// Suffix scan of a histogram held as `per` bins per thread: finds the bin with
-//   above(bin) < remain <= above(bin) + count(bin)   (above = entries in higher bins)
-// and reports (bin, above, count) through LDS to every thread.  Exactly one bin qualifies whenever
-// the histogram holds at least `remain` entries.
+// ---- block-wide scans over kSelThreads threads (one value per thread) -----------------------
+// exclusive sum over the threads with a HIGHER index (suffix); s_w: kSelWaves words of LDS
+__device__ __forceinline__ uint32_t block_suffix_exclusive(uint32_t x, uint32_t* s_w) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl = x;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = __shfl_down(incl, off);
+        if (lane + off < 64) incl += o;
+    }
+    __syncthreads();                                       // s_w may still be read from a previous scan
+    if (lane == 0) s_w[wave] = incl;
+    __syncthreads();
+    uint32_t higher = 0;
+    for (int w = wave + 1; w < kSelWaves; ++w) higher += s_w[w];
+    return incl - x + higher;
+}
+// exclusive sum over the threads with a LOWER index (prefix)
+__device__ __forceinline__ uint32_t block_prefix_exclusive(uint32_t x, uint32_t* s_w) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl = x;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = __shfl_up(incl, off);
+        if (lane >= off) incl += o;
+    }
+    __syncthreads();
+    if (lane == 63) s_w[wave] = incl;
+    __syncthreads();
+    uint32_t lower = 0;
+    for (int w = 0; w < wave; ++w) lower += s_w[w];
+    return incl - x + lower;
+}
+
+// Histogram held as PER consecutive bins per thread (thread t owns bins [t*PER, t*PER+PER)):
+// finds the bin with  above(bin) < remain <= above(bin) + count(bin)  (above = entries in higher
+// bins) and reports (bin, above, count) in s_out to every thread.  Exactly one bin qualifies
+// whenever the histogram holds at least `remain` entries.
 template <int PER>
-__device__ __forceinline__ void locate_bin(const uint32_t (&c)[PER], uint32_t remain, uint32_t* s_sum,
+__device__ __forceinline__ void locate_bin(const uint32_t (&c)[PER], uint32_t remain, uint32_t* s_w,
                                            uint32_t* s_out) {
-    const int tid = threadIdx.x;
     uint32_t local = 0;
 #pragma unroll
     for (int i = 0; i < PER; ++i) local += c[i];
-    s_sum[tid] = local;
-    __syncthreads();
-    uint32_t above = 0;
-    for (int t = tid + 1; t < kSelThreads; ++t) above += s_sum[t];
+    uint32_t above = block_suffix_exclusive(local, s_w);
 #pragma unroll
     for (int i = PER - 1; i >= 0; --i) {
         if (above < remain && remain <= above + c[i]) {
-            s_out[0] = (uint32_t)(tid * PER + i);
+            s_out[0] = (uint32_t)(threadIdx.x * PER + i);
             s_out[1] = above;
             s_out[2] = c[i];
         }
@@ -103,7 +144,7 @@ __device__ __forceinline__ void locate_bin(const uint32_t (&c)[PER], uint32_t re
 // scores (+ histogram)
 // ------------------------------------------------------------------------------------------
 template <int DT, int G, int UNR>
-__global__ __launch_bounds__(kSelThreads) void scores_hist_kernel(const ScoresArgs a, uint32_t* scratch) {
+__global__ __launch_bounds__(kScoreThreads) void scores_hist_kernel(const ScoresArgs a, uint32_t* scratch) {
     constexpr int RPW = 64 / G;                       // vocabulary rows per wave-wide load
     __shared__ uint32_t lh[kHistBins];
     const int tid = threadIdx.x;
@@ -116,7 +157,7 @@ __global__ __launch_bounds__(kSelThreads) void scores_hist_kernel(const ScoresAr
     const int64_t V = a.V;
     const int64_t row_bytes = (int64_t)C * 16;
 
-    for (int b = tid; b < kHistBins; b += kSelThreads) lh[b] = 0u;
+    for (int b = tid; b < kHistBins; b += kScoreThreads) lh[b] = 0u;
     const u32x4 xreg = g < C ? reinterpret_cast<const u32x4*>(a.hp + r * row_bytes)[g] : zero16();
     float* s = a.s + r * V;
     __syncthreads();
@@ -151,49 +192,33 @@ __global__ __launch_bounds__(kSelThreads) void scores_hist_kernel(const ScoresAr
     }
     __syncthreads();
 
-    const SelLayout L = sel_layout(V);
+    const SelLayout L = sel_layout(V, a.rows);
     const SelPtrs p = sel_ptrs(scratch, a.rows, r, L);
-    for (int b = tid; b < kHistBins; b += kSelThreads) {
+    uint32_t* hist = p.hist + (size_t)(blockIdx.x % L.replicas) * kHistBins;
+    for (int b = tid; b < kHistBins; b += kScoreThreads) {
         const uint32_t c = lh[b];
-        if (c) atomicAdd(&p.hist[b], c);
+        if (c) atomicAdd(&hist[b], c);
     }
 }
 
 // histogram only (scores produced by another kernel)
-__global__ __launch_bounds__(kSelThreads) void hist_kernel(const float* s_all, int64_t V, int64_t k,
-                                                           uint32_t* scratch, int rows) {
+__global__ __launch_bounds__(kScoreThreads) void hist_kernel(const float* s_all, int64_t V, uint32_t* scratch,
+                                                             int rows) {
     __shared__ uint32_t lh[kHistBins];
     const int tid = threadIdx.x;
     const int64_t r = blockIdx.y;
     const float* s = s_all + r * V;
-    for (int b = tid; b < kHistBins; b += kSelThreads) lh[b] = 0u;
+    for (int b = tid; b < kHistBins; b += kScoreThreads) lh[b] = 0u;
     __syncthreads();
-    for (int64_t v = (int64_t)blockIdx.x * kSelThreads + tid; v < V; v += (int64_t)gridDim.x * kSelThreads)
+    for (int64_t v = (int64_t)blockIdx.x * kScoreThreads + tid; v < V; v += (int64_t)gridDim.x * kScoreThreads)
         atomicAdd(&lh[f32_to_ord(s[v]) >> kKeyLowBits], 1u);
     __syncthreads();
-    const SelLayout L = sel_layout(V);
+    const SelLayout L = sel_layout(V, rows);
     const SelPtrs p = sel_ptrs(scratch, rows, r, L);
-    for (int b = tid; b < kHistBins; b += kSelThreads) {
+    uint32_t* hist = p.hist + (size_t)(blockIdx.x % L.replicas) * kHistBins;
+    for (int b = tid; b < kHistBins; b += kScoreThreads) {
         const uint32_t c = lh[b];
-        if (c) atomicAdd(&p.hist[b], c);
-    }
-}
-
-// the bin that holds the k-th largest score of each row
-__global__ __launch_bounds__(kSelThreads) void locate_kernel(int64_t V, int64_t k, uint32_t* scratch, int rows) {
-    __shared__ uint32_t s_sum[kSelThreads];
-    __shared__ uint32_t s_out[4];
-    const int tid = threadIdx.x;
-    const SelLayout L = sel_layout(V);
-    const SelPtrs p = sel_ptrs(scratch, rows, blockIdx.x, L);
-    constexpr int PER = kHistBins / kSelThreads;      // 16
-    uint32_t c[PER];
-#pragma unroll
-    for (int i = 0; i < PER; ++i) c[i] = p.hist[tid * PER + i];
-    locate_bin<PER>(c, (uint32_t)k, s_sum, s_out);
-    if (tid == 0) {
-        p.state[ST_BIN] = s_out[0];
-        p.state[ST_ABOVE] = s_out[1];
+        if (c) atomicAdd(&hist[b], c);
     }
 }
 
@@ -206,7 +231,7 @@ hipError_t launch_scores_g(const ScoresArgs& a, uint32_t* scratch, int cus, hipS
     if (cap < 1) cap = 1;
     if (bx > cap) bx = cap;
     hipLaunchKernelGGL((scores_hist_kernel<DT, G, UNR>), dim3((unsigned)bx, (unsigned)a.rows),
-                       dim3(kSelThreads), 0, stream, a, scratch);
+                       dim3(kScoreThreads), 0, stream, a, scratch);
     return hipGetLastError();
 }
 
@@ -219,42 +244,68 @@ hipError_t launch_scores_dt(const ScoresArgs& a, uint32_t* scratch, int cus, hip
 }
 
 // ------------------------------------------------------------------------------------------
-// collect + resolve
+// collect
 // ------------------------------------------------------------------------------------------
-// 52-bit sub-key of a candidate: the 20 low key bits, then the inverted id (smaller id = larger)
-__device__ __forceinline__ uint64_t sub_key(uint32_t key, uint32_t v) {
-    return ((uint64_t)(key & ((1u << kKeyLowBits) - 1u)) << 32) | (uint32_t)(~v);
+__device__ __forceinline__ uint64_t key64(uint32_t key, uint32_t v) {
+    return ((uint64_t)key << 32) | (uint32_t)(~v);      // larger score first, then smaller id
 }
 
-__global__ __launch_bounds__(kSelThreads) void collect_kernel(const float* s_all, int64_t V, uint32_t* scratch,
-                                                              int rows) {
-    __shared__ uint32_t s_list[kSelThreads * kMaxEpt];    // ids of this block's bin-B entries
-    __shared__ uint32_t s_n, s_gbase, s_sure[4];
+__global__ __launch_bounds__(kSelThreads) void collect_kernel(const float* s_all, int64_t V, int64_t k,
+                                                              uint32_t* scratch, int rows) {
+    __shared__ uint64_t s_list[kSelThreads * kEpt];    // this block's bin-B entries
+    __shared__ uint32_t s_w[kSelWaves];
+    __shared__ uint32_t s_out[4];
+    __shared__ uint32_t s_n, s_gbase;
     const int tid = threadIdx.x;
     const int64_t r = blockIdx.y;
-    const SelLayout L = sel_layout(V);
+    const SelLayout L = sel_layout(V, rows);
     const SelPtrs p = sel_ptrs(scratch, rows, r, L);
     const float* s = s_all + r * V;
-    const uint32_t B = p.state[ST_BIN];
 
-    if (tid == 0) s_n = 0u;
-    __syncthreads();
+    // this block's scores first: their latency overlaps the histogram reduction below
     const int64_t base = (int64_t)blockIdx.x * L.chunk;
+    uint32_t key[kEpt];
+#pragma unroll
+    for (int i = 0; i < kEpt; ++i) {
+        const int64_t v = base + (int64_t)i * kSelThreads + tid;
+        key[i] = (v < V) ? f32_to_ord(s[v]) : 0u;    // 0: below every finite score
+    }
+
+    // the bin B of the k-th largest score, from the sum of the histogram replicas
+    constexpr int PER = kHistBins / kSelThreads;          // 4 consecutive bins per thread
+    uint32_t c[PER] = {0u, 0u, 0u, 0u};
+    for (int rep = 0; rep < L.replicas; ++rep) {
+        const u32x4 q = reinterpret_cast<const u32x4*>(p.hist + (size_t)rep * kHistBins)[tid];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) c[i] += q[i];
+    }
+    if (tid == 0) s_n = 0u;
+    locate_bin<PER>(c, (uint32_t)k, s_w, s_out);
+    const uint32_t B = s_out[0];
+    if (blockIdx.x == 0 && tid == 0) {
+        p.binfo[0] = B;
+        p.binfo[1] = s_out[1];
+    }
+
     uint32_t sure = 0u;
-    for (int64_t i = 0; i < L.ept; ++i) {
-        const int64_t v = base + i * kSelThreads + tid;
+#pragma unroll
+    for (int i = 0; i < kEpt; ++i) {
+        const int64_t v = base + (int64_t)i * kSelThreads + tid;
         if (v < V) {
-            const uint32_t bin = f32_to_ord(s[v]) >> kKeyLowBits;
+            const uint32_t bin = key[i] >> kKeyLowBits;
             sure += bin > B;
-            if (bin == B) s_list[atomicAdd(&s_n, 1u)] = (uint32_t)v;
+            if (bin == B) s_list[atomicAdd(&s_n, 1u)] = key64(key[i], (uint32_t)v);
         }
     }
     sure = wave_sum_u32(sure);
-    if ((tid & 63) == 0) s_sure[tid >> 6] = sure;
+    __syncthreads();                                      // s_w free again, s_list complete
+    if ((tid & 63) == 0) s_w[tid >> 6] = sure;
     __syncthreads();
     const uint32_t n_local = s_n;
     if (tid == 0) {
-        p.sure[blockIdx.x] = s_sure[0] + s_sure[1] + s_sure[2] + s_sure[3];
+        uint32_t tot = 0u;
+        for (int w = 0; w < kSelWaves; ++w) tot += s_w[w];
+        p.sure[blockIdx.x] = tot;
         s_gbase = n_local ? atomicAdd(&p.state[ST_NCAND], n_local) : 0u;
     }
     __syncthreads();
@@ -262,23 +313,32 @@ __global__ __launch_bounds__(kSelThreads) void collect_kernel(const float* s_all
     for (uint32_t i = tid; i < n_local; i += kSelThreads) p.cand[gbase + i] = s_list[i];
 }
 
-// one block per row: threshold among the candidates of bin B, then the output offset of every block
-__global__ __launch_bounds__(kSelThreads) void resolve_kernel(const float* s_all, int64_t V, int64_t k,
-                                                              uint32_t* scratch, int rows) {
+// ------------------------------------------------------------------------------------------
+// resolve: one block per row
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kSelThreads) void resolve_kernel(int64_t V, int64_t k, uint32_t* scratch, int rows) {
     __shared__ uint32_t s_hist[2048];
-    __shared__ uint32_t s_sum[kSelThreads];
+    __shared__ uint32_t s_w[kSelWaves];
     __shared__ uint32_t s_out[4];
     __shared__ uint32_t s_cnt[kMaxBlocksPerRow];
     const int tid = threadIdx.x;
     const int64_t r = blockIdx.x;
-    const SelLayout L = sel_layout(V);
+    const SelLayout L = sel_layout(V, rows);
     const SelPtrs p = sel_ptrs(scratch, rows, r, L);
-    const float* s = s_all + r * V;
-    const uint32_t B = p.state[ST_BIN];
-    const uint32_t above = p.state[ST_ABOVE];
-
-    // ---- resolver: the m-th largest sub-key among the n candidates of bin B
+    const uint32_t B = p.binfo[0];
+    const uint32_t above = p.binfo[1];
     const uint32_t n = p.state[ST_NCAND];
+    const bool in_regs = n <= (uint32_t)(kSelThreads * kCandPerThread);
+
+    // candidates: 52-bit sub-keys (20 low key bits, then the inverted id); the top 12 bits are all B
+    constexpr uint64_t kSubMask = (1ull << 52) - 1ull;
+    uint64_t sk[kCandPerThread];
+#pragma unroll
+    for (int i = 0; i < kCandPerThread; ++i) {
+        const uint32_t j = (uint32_t)i * kSelThreads + tid;
+        sk[i] = (in_regs && j < n) ? (p.cand[j] & kSubMask) : 0ull;
+    }
+
     uint32_t remain = (uint32_t)k - above;              // 1 <= remain <= n
     uint64_t prefix = 0ull;                             // decided high bits of the threshold sub-key
     int decided = 0;                                    // how many of the 52 bits are decided
@@ -288,19 +348,23 @@ __global__ __launch_bounds__(kSelThreads) void resolve_kernel(const float* s_all
     for (int pass = 0; pass < 5 && !all_of_prefix; ++pass) {
         const int w = widths[pass];
         const int shift = 52 - decided - w;
-        for (int b = tid; b < 2048; b += kSelThreads) s_hist[b] = 0u;
+        s_hist[tid] = 0u;
+        s_hist[tid + kSelThreads] = 0u;
         __syncthreads();
-        for (uint32_t i = tid; i < n; i += kSelThreads) {
-            const uint32_t v = p.cand[i];
-            const uint64_t sk = sub_key(f32_to_ord(s[v]), v);
-            if (decided == 0 || (sk >> (52 - decided)) == (prefix >> (52 - decided)))
-                atomicAdd(&s_hist[(uint32_t)(sk >> shift) & ((1u << w) - 1u)], 1u);
+        auto count = [&](uint64_t x) {
+            if (decided == 0 || (x >> (52 - decided)) == (prefix >> (52 - decided)))
+                atomicAdd(&s_hist[(uint32_t)(x >> shift) & ((1u << w) - 1u)], 1u);
+        };
+        if (in_regs) {
+#pragma unroll
+            for (int i = 0; i < kCandPerThread; ++i)
+                if ((uint32_t)i * kSelThreads + tid < n) count(sk[i]);
+        } else {
+            for (uint32_t j = tid; j < n; j += kSelThreads) count(p.cand[j] & kSubMask);
         }
         __syncthreads();
-        uint32_t c[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) c[i] = s_hist[tid * 8 + i];
-        locate_bin<8>(c, remain, s_sum, s_out);
+        const uint32_t c[2] = {s_hist[tid * 2], s_hist[tid * 2 + 1]};
+        locate_bin<2>(c, remain, s_w, s_out);
         prefix |= (uint64_t)s_out[0] << shift;
         remain -= s_out[1];
         decided += w;
@@ -308,40 +372,28 @@ __global__ __launch_bounds__(kSelThreads) void resolve_kernel(const float* s_all
         __syncthreads();
     }
     // threshold: selected(v) <=> (key << 32 | ~v) >= T, T = (B << 20 | prefix.hi) << 32 | prefix.lo
-    const uint32_t t_hi = (B << kKeyLowBits) | (uint32_t)(prefix >> 32);
-    const uint32_t t_lo = (uint32_t)prefix;
     if (tid == 0) {
-        p.state[ST_T_HI] = t_hi;
-        p.state[ST_T_LO] = t_lo;
+        p.state[ST_T_HI] = (B << kKeyLowBits) | (uint32_t)(prefix >> 32);
+        p.state[ST_T_LO] = (uint32_t)prefix;
     }
     // ---- output offsets: selected entries per block = sure + selected candidates, exclusive scan
     const int nb = (int)L.nb;
-    for (int b = tid; b < nb; b += kSelThreads) s_cnt[b] = 0u;
+    s_cnt[tid] = 0u;
     __syncthreads();
-    for (uint32_t i = tid; i < n; i += kSelThreads) {
-        const uint32_t v = p.cand[i];
-        if (sub_key(f32_to_ord(s[v]), v) >= prefix) atomicAdd(&s_cnt[v / (uint32_t)L.chunk], 1u);
-    }
-    __syncthreads();
-    constexpr int PERB = kMaxBlocksPerRow / kSelThreads;   // 4 consecutive blocks per thread
-    uint32_t tot[PERB];
-    uint32_t local = 0u;
+    auto tally = [&](uint64_t x) {
+        if (x >= prefix) atomicAdd(&s_cnt[(uint32_t)(~(uint32_t)x) / (uint32_t)L.chunk], 1u);
+    };
+    if (in_regs) {
 #pragma unroll
-    for (int i = 0; i < PERB; ++i) {
-        const int b = tid * PERB + i;
-        tot[i] = b < nb ? s_cnt[b] + p.sure[b] : 0u;
-        local += tot[i];
+        for (int i = 0; i < kCandPerThread; ++i)
+            if ((uint32_t)i * kSelThreads + tid < n) tally(sk[i]);
+    } else {
+        for (uint32_t j = tid; j < n; j += kSelThreads) tally(p.cand[j] & kSubMask);
     }
-    s_sum[tid] = local;
     __syncthreads();
-    uint32_t run = 0u;
-    for (int t = 0; t < tid; ++t) run += s_sum[t];
-#pragma unroll
-    for (int i = 0; i < PERB; ++i) {
-        const int b = tid * PERB + i;
-        if (b < nb) p.offset[b] = run;
-        run += tot[i];
-    }
+    const uint32_t mine = tid < nb ? s_cnt[tid] + p.sure[tid] : 0u;
+    const uint32_t off = block_prefix_exclusive(mine, s_w);
+    if (tid < nb) p.offset[tid] = off;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -350,45 +402,35 @@ __global__ __launch_bounds__(kSelThreads) void resolve_kernel(const float* s_all
 __global__ __launch_bounds__(kSelThreads) void emit_kernel(const float* s_all, int64_t V, int64_t k,
                                                            uint32_t* scratch, int rows, int32_t* idx_out,
                                                            float* scores_out) {
-    __shared__ uint32_t s_wave[4];
+    __shared__ uint32_t s_w[kSelWaves];
     const int tid = threadIdx.x;
-    const int lane = tid & 63;
     const int64_t r = blockIdx.y;
-    const SelLayout L = sel_layout(V);
+    const SelLayout L = sel_layout(V, rows);
     const SelPtrs p = sel_ptrs(scratch, rows, r, L);
     const float* s = s_all + r * V;
+
+    // thread t owns kEpt consecutive ids, so (thread, i) order is ascending id order
+    const int64_t v0 = (int64_t)blockIdx.x * L.chunk + (int64_t)tid * kEpt;
+    float val[kEpt];
+#pragma unroll
+    for (int i = 0; i < kEpt; ++i) val[i] = (v0 + i < V) ? s[v0 + i] : 0.0f;
     const uint64_t T = ((uint64_t)p.state[ST_T_HI] << 32) | p.state[ST_T_LO];
     const uint32_t block_off = p.offset[blockIdx.x];
 
-    // thread t owns ept consecutive ids, so (thread, i) order is ascending id order
-    const int64_t v0 = (int64_t)blockIdx.x * L.chunk + (int64_t)tid * L.ept;
     uint32_t mask = 0u;
-    for (int64_t i = 0; i < L.ept; ++i) {
-        const int64_t v = v0 + i;
-        if (v < V) {
-            const uint64_t key64 = ((uint64_t)f32_to_ord(s[v]) << 32) | (uint32_t)(~(uint32_t)v);
-            if (key64 >= T) mask |= 1u << i;
-        }
-    }
-    const uint32_t mine = (uint32_t)__popc(mask);
-    // exclusive prefix over the block: wave scan, then the four wave totals
-    uint32_t incl = mine;
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t o = __shfl_up(incl, off);
-        if (lane >= off) incl += o;
-    }
-    if (lane == 63) s_wave[tid >> 6] = incl;
-    __syncthreads();
-    uint32_t pos = block_off + incl - mine;
-    for (int w = 0; w < (tid >> 6); ++w) pos += s_wave[w];
+    for (int i = 0; i < kEpt; ++i)
+        if (v0 + i < V && key64(f32_to_ord(val[i]), (uint32_t)(v0 + i)) >= T) mask |= 1u << i;
+    const uint32_t mine = (uint32_t)__popc(mask);
+    uint32_t pos = block_off + block_prefix_exclusive(mine, s_w);
 
     int32_t* out = idx_out + r * k;
-    for (int64_t i = 0; i < L.ept; ++i) {
+#pragma unroll
+    for (int i = 0; i < kEpt; ++i) {
         if (mask & (1u << i)) {
             if (pos < (uint32_t)k) {                      // always true for a consistent threshold
                 out[pos] = (int32_t)(v0 + i);
-                if (scores_out) scores_out[r * k + pos] = s[v0 + i];
+                if (scores_out) scores_out[r * k + pos] = val[i];
             }
             ++pos;
         }
@@ -399,11 +441,16 @@ __global__ __launch_bounds__(kSelThreads) void emit_kernel(const float* s_all, i
 
 bool scores_supported(int chunks) { return chunks >= 1 && chunks <= 64; }
 
-int64_t select_max_vocab() { return (int64_t)kSelThreads * kMaxBlocksPerRow * kMaxEpt; }
+int64_t select_max_vocab() { return (int64_t)kSelThreads * kMaxBlocksPerRow * kEpt; }
 
-size_t select_scratch_words(int64_t rows, int64_t V) { return (size_t)rows * sel_layout(V).row_words; }
+size_t select_scratch_words(int64_t rows, int64_t V) {
+    const SelLayout L = sel_layout(V, rows);
+    return sel_zero_total(rows, L) + (size_t)rows * L.rest_words;
+}
 
-void select_zero_range(int64_t rows, int64_t V, size_t* words) { *words = (size_t)rows * sel_layout(V).zero_words; }
+void select_zero_range(int64_t rows, int64_t V, size_t* words) {
+    *words = (size_t)rows * sel_layout(V, rows).zero_words;
+}
 
 hipError_t launch_scores_hist(int dt, const ScoresArgs& a, uint32_t* scratch, hipStream_t stream) {
     DeviceInfo di;
@@ -414,24 +461,24 @@ hipError_t launch_scores_hist(int dt, const ScoresArgs& a, uint32_t* scratch, hi
 }
 
 hipError_t launch_hist(const float* s, int64_t V, int64_t k, int rows, uint32_t* scratch, hipStream_t stream) {
+    (void)k;
     DeviceInfo di;
     hipError_t e = device_info(&di);
     if (e != hipSuccess) return e;
-    int64_t bx = (V + kSelThreads * 4 - 1) / (kSelThreads * 4);
-    int64_t cap = ((int64_t)di.cus * 4 + rows - 1) / rows;
+    int64_t bx = (V + kScoreThreads * 4 - 1) / (kScoreThreads * 4);
+    int64_t cap = ((int64_t)di.cus * 2 + rows - 1) / rows;
     if (cap < 1) cap = 1;
     if (bx > cap) bx = cap;
-    hipLaunchKernelGGL(hist_kernel, dim3((unsigned)bx, (unsigned)rows), dim3(kSelThreads), 0, stream, s, V, k,
+    hipLaunchKernelGGL(hist_kernel, dim3((unsigned)bx, (unsigned)rows), dim3(kScoreThreads), 0, stream, s, V,
                        scratch, rows);
     return hipGetLastError();
 }
 
 hipError_t launch_topk_of_scores(const RadixArgs& a, hipStream_t stream) {
-    const SelLayout L = sel_layout(a.V);
+    const SelLayout L = sel_layout(a.V, a.rows);
     const dim3 grid((unsigned)L.nb, (unsigned)a.rows), block(kSelThreads);
-    hipLaunchKernelGGL(locate_kernel, dim3((unsigned)a.rows), block, 0, stream, a.V, a.k, a.scratch, a.rows);
-    hipLaunchKernelGGL(collect_kernel, grid, block, 0, stream, a.s, a.V, a.scratch, a.rows);
-    hipLaunchKernelGGL(resolve_kernel, dim3((unsigned)a.rows), block, 0, stream, a.s, a.V, a.k, a.scratch, a.rows);
+    hipLaunchKernelGGL(collect_kernel, grid, block, 0, stream, a.s, a.V, a.k, a.scratch, a.rows);
+    hipLaunchKernelGGL(resolve_kernel, dim3((unsigned)a.rows), block, 0, stream, a.V, a.k, a.scratch, a.rows);
     hipLaunchKernelGGL(emit_kernel, grid, block, 0, stream, a.s, a.V, a.k, a.scratch, a.rows, a.idx_out,
                        a.scores_out);
     return hipGetLastError();

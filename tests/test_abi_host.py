@@ -96,6 +96,12 @@ def test_dense_select_topk_reject_bad_arguments(lib):
     assert s(A, 1, 256, 256, A, 30, A, 1000, 1, 10, A, None, A, 1 << 30, None) == 6         # d' % 8
     assert s(A, 1, 256, 256, A, 32, A, 1000, 4, 10, A, None, A, 1 << 30, None) == 3
 
+    f = lib.specvocab_draft_step
+    assert f(A, 1, 256, 256, A, 1000, 256, 1, A, 100, 0, 10, None, A, A, None, None, 0, None) == 1   # no logits_out
+    assert f(A, 1, 256, 256, A, 1000, 256, 1, A, 100, 0, 101, A, A, A, None, None, 0, None) == 2     # kd > k
+    assert f(A, 1, 256, 256, A, 1000, 256, 1, A, 100, 0, 65, A, A, A, None, None, 0, None) == 6
+    assert f(A, 1, 256, 256, MIS, 1000, 256, 1, A, 100, 0, 10, A, A, A, None, None, 0, None) == 4
+
     t = lib.specvocab_draft_topk
     assert t(None, A, 0, 1, 100, 10, A, A, None, None, 0, None) == 1
     assert t(A, A, 0, 1, 100, 101, A, A, None, None, 0, None) == 2                          # kd > k

@@ -130,6 +130,63 @@ def test_draft_topk_matches_oracle_on_identical_logits(rows, k, kd, mode, ties):
     assert np.allclose(q.sum(axis=1), 1.0, atol=1e-4)
 
 
+# ---------------------------------------------------------------- draft step in one call
+STEP_SHAPES = [
+    # dtype, rows, d,   V,    k,    kd, mode
+    ("f32", 1, 256, 8192, 512, 8, "per_row"),         # config 1
+    ("bf16", 3, 1024, 5000, 1000, 10, "per_row"),
+    ("bf16", 2, 3840, 9000, 4096, 10, "per_step"),
+    ("bf16", 1, 4096, 20000, 8192, 64, "per_row"),
+    ("bf16", 2, 512, 3000, 1001, 5, "per_row"),
+    ("bf16", 65, 256, 2000, 64, 3, "per_step"),
+]
+
+
+@pytest.mark.parametrize("dtype,rows,d,V,k,kd,mode", STEP_SHAPES)
+def test_draft_step_equals_the_two_calls(dtype, rows, d, V, k, kd, mode):
+    say(f"draft_step {dtype} rows={rows} d={d} V={V} k={k} kd={kd} {mode}")
+    rng = np.random.default_rng(d + V + k)
+    U = rand(rng, (V, d), 0.02, dtype)
+    h = rand(rng, (rows, d), 1.0, dtype)
+    if mode == "per_step":
+        idx = np.sort(rng.permutation(V)[:k]).astype(np.int32)
+    else:
+        idx = np.stack([np.sort(rng.permutation(V)[:k]) for _ in range(rows)]).astype(np.int32)
+    tU, th, tidx = to_dev(U), to_dev(h), torch.from_numpy(idx).to(DEV)
+    for rep in range(2):
+        z, tok, prob, q = sv.draft_step(th, tU, tidx, kd, want_probs=True)
+        z2 = sv.subset_logits(th, tU, tidx)
+        tok2, prob2, q2 = sv.draft_topk(z2, tidx, kd, want_probs=True)
+        assert torch.equal(z, z2) and torch.equal(tok, tok2)
+        # the softmax denominator may be summed in another order (different elements per thread)
+        assert torch.allclose(prob, prob2, rtol=1e-5, atol=1e-9) and torch.allclose(q, q2, rtol=1e-5, atol=1e-9)
+    z_ref = oracle.subset_logits(h, U, idx)
+    assert_logits_close(z.cpu().numpy(), z_ref, dtype)
+    tok_same, prob_same = oracle.softmax_topk(z.cpu().numpy(), idx, kd)
+    assert np.array_equal(tok.cpu().numpy(), tok_same)
+    assert np.allclose(prob.cpu().numpy(), prob_same, rtol=1e-3, atol=1e-6)
+
+
+def test_draft_step_sees_fresh_logits_in_a_reused_buffer():
+    """The top-kd stage reads logits written just before it on the same stream; with one output
+    buffer reused over many different inputs a stale read would show."""
+    say("draft_step with reused output buffers")
+    rng = np.random.default_rng(99)
+    d, V, k, kd = 2048, 30000, 8192, 10
+    U = to_dev(rand(rng, (V, d), 0.02, "bf16"))
+    z = torch.empty((1, k), dtype=torch.float32, device=DEV)
+    tok = torch.empty((1, kd), dtype=torch.int32, device=DEV)
+    prob = torch.empty((1, kd), dtype=torch.float32, device=DEV)
+    hs = to_dev(rand(rng, (40, d), 1.0, "bf16"))
+    idxs = torch.from_numpy(np.stack([np.sort(rng.permutation(V)[:k]) for _ in range(40)]).astype(np.int32)).to(DEV)
+    for t in range(40):
+        sv.draft_step(hs[t:t + 1], U, idxs[t:t + 1], kd, logits_out=z, tok_out=tok, prob_out=prob)
+        z2 = sv.subset_logits(hs[t:t + 1], U, idxs[t:t + 1])
+        tok2, prob2, _ = sv.draft_topk(z2, idxs[t:t + 1], kd)
+        assert torch.equal(z, z2) and torch.equal(tok, tok2), t
+        assert torch.allclose(prob, prob2, rtol=1e-5, atol=1e-9), t
+
+
 # ---------------------------------------------------------------- select
 SELECT_SHAPES = [
     # dtype, rows, d,   d',  V,     k
@@ -262,6 +319,8 @@ def test_config2_chain_full_size(llama_head):
         tok_same, prob_same = oracle.softmax_topk(z.cpu().numpy(), idx, c.kd)
         assert np.array_equal(tok.cpu().numpy(), tok_same)
         assert np.allclose(prob.cpu().numpy(), prob_same, rtol=1e-3, atol=1e-6)
+        zf, tokf, probf, _ = sv.draft_step(th, tU, tidx, c.kd)        # the launch the benchmark times
+        assert torch.equal(zf, z) and torch.equal(tokf, tok) and torch.allclose(probf, prob, rtol=1e-5, atol=1e-9)
     say("config 2 dense baseline, all 128256 logits")
     zd = sv.dense_logits(to_dev(hs[0]), tU).cpu().numpy()
     assert_logits_close(zd, oracle.dense_logits(hs[0], U), "bf16", "dense logits")
