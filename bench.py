@@ -46,6 +46,93 @@ def parse_args():
     return p.parse_args()
 
 
+def other_configs(sv, torch, np, dev, capture, timed_replays):
+    """The remaining configurations (tree rows, large vocabulary, full step with selection): median
+    microseconds per step from graph replays, next to the dense projection at the same row count."""
+    from workloads import CONFIGS, make_rng, zipf_subset
+
+    def dev_bf16(a):
+        return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+
+    def med_us(fn, n, reps=5):
+        g = capture(fn, n)
+        timed_replays(g, 1)
+        r = sorted(timed_replays(g, reps))
+        return r[len(r) // 2] * 1e3 / n
+
+    out = {}
+    # ---- config 3: 60 tree rows, own k=4096 subset each (half shared), top-10
+    c = CONFIGS[3]
+    U = dev_bf16(CONFIGS[2].weights())
+    nst = 4
+    h = dev_bf16(c.hidden(nst).reshape(nst * c.rows, c.d)).reshape(nst, c.rows, c.d)
+    idx = torch.from_numpy(c.indices(nst)).to(dev)
+    z = torch.empty((c.rows, c.k), dtype=torch.float32, device=dev)
+    tok = torch.empty((c.rows, c.kd), dtype=torch.int32, device=dev)
+    prob = torch.empty((c.rows, c.kd), dtype=torch.float32, device=dev)
+    zd = torch.empty((c.rows, c.V), dtype=torch.float32, device=dev)
+    step_us = med_us(lambda t: sv.draft_step(h[t % nst], U, idx[t % nst], c.kd, logits_out=z, tok_out=tok,
+                                             prob_out=prob), 20)
+    dense_us = med_us(lambda t: sv.dense_logits(h[t % nst], U, out=zd), 10)
+    uniq = float(np.mean([np.unique(idx[t].cpu().numpy()).size for t in range(nst)]))
+    out["config3_tree60"] = {"rows": c.rows, "k": c.k, "step_us": round(step_us, 1), "dense_us": round(dense_us, 1),
+                             "speedup_vs_dense": round(dense_us / step_us, 2),
+                             "unique_rows_per_step": round(uniq), "unique_row_MB": round(uniq * c.d * 2 / 1e6, 1),
+                             "dense_frac_hbm_peak": round(c.V * c.d * 2 / (dense_us * 1e-6) / 8e12, 3)}
+    del U, h, idx, z, zd
+    torch.cuda.empty_cache()
+
+    # ---- config 4: V=262144, d=3840, 8 rows, k sweep, one set per step and one set per row
+    c = CONFIGS[4]
+    U = dev_bf16(c.weights())
+    h = dev_bf16(c.hidden(nst).reshape(nst * c.rows, c.d)).reshape(nst, c.rows, c.d)
+    zd = torch.empty((c.rows, c.V), dtype=torch.float32, device=dev)
+    dense_us = med_us(lambda t: sv.dense_logits(h[t % nst], U, out=zd), 10)
+    del zd
+    rng = make_rng(4, 2)
+    sweep = {}
+    for k in c.k_sweep:
+        shared = torch.from_numpy(np.stack([zipf_subset(rng, c.V, k) for _ in range(nst)])).to(dev)
+        per_row = torch.from_numpy(np.stack([np.stack([zipf_subset(rng, c.V, k) for _ in range(c.rows)])
+                                             for _ in range(nst)])).to(dev)
+        z = torch.empty((c.rows, k), dtype=torch.float32, device=dev)
+        tok = torch.empty((c.rows, c.kd), dtype=torch.int32, device=dev)
+        prob = torch.empty((c.rows, c.kd), dtype=torch.float32, device=dev)
+        sh_us = med_us(lambda t: sv.draft_step(h[t % nst], U, shared[t % nst], c.kd, logits_out=z, tok_out=tok,
+                                               prob_out=prob), 20)
+        pr_us = med_us(lambda t: sv.draft_step(h[t % nst], U, per_row[t % nst], c.kd, logits_out=z, tok_out=tok,
+                                               prob_out=prob), 20)
+        sweep[str(k)] = {"shared_set_step_us": round(sh_us, 1), "per_row_sets_step_us": round(pr_us, 1),
+                         "speedup_vs_dense_shared": round(dense_us / sh_us, 2),
+                         "speedup_vs_dense_per_row": round(dense_us / pr_us, 2)}
+    out["config4_gemma262k"] = {"rows": c.rows, "dense_us": round(dense_us, 1),
+                                "dense_frac_hbm_peak": round(c.V * c.d * 2 / (dense_us * 1e-6) / 8e12, 3),
+                                "k": sweep}
+    del U, h
+    torch.cuda.empty_cache()
+
+    # ---- config 5: 512 rows, selector d'=256, k=8192, top-10: select -> logits -> softmax/top-10
+    c = CONFIGS[5]
+    U = dev_bf16(c.weights())
+    Wd_np, Wv_np = c.selector()
+    Wd, Wv = dev_bf16(Wd_np), dev_bf16(Wv_np)
+    h = dev_bf16(c.hidden(1)[0])
+    ws = torch.empty(sv.workspace_bytes(sv.SV_OP_SELECT, c.rows, c.d, c.V, c.k, c.d_prime, 0, sv.SV_BF16),
+                     dtype=torch.uint8, device=dev)
+    sel = torch.empty((c.rows, c.k), dtype=torch.int32, device=dev)
+    z = torch.empty((c.rows, c.k), dtype=torch.float32, device=dev)
+    tok = torch.empty((c.rows, c.kd), dtype=torch.int32, device=dev)
+    prob = torch.empty((c.rows, c.kd), dtype=torch.float32, device=dev)
+    zd = torch.empty((c.rows, c.V), dtype=torch.float32, device=dev)
+    sel_us = med_us(lambda t: sv.select(h, Wd, Wv, c.k, idx_out=sel, ws=ws), 3, reps=3)
+    step_us = med_us(lambda t: sv.draft_step(h, U, sel, c.kd, logits_out=z, tok_out=tok, prob_out=prob), 3, reps=3)
+    dense_us = med_us(lambda t: sv.dense_logits(h, U, out=zd), 3, reps=3)
+    out["config5_qwen3_select"] = {"rows": c.rows, "k": c.k, "d_prime": c.d_prime, "select_us": round(sel_us, 1),
+                                   "logits_softmax_topk_us": round(step_us, 1),
+                                   "end_to_end_us": round(sel_us + step_us, 1), "dense_us": round(dense_us, 1)}
+    return out
+
+
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -247,6 +334,11 @@ def main():
         result["select"] = {"d_prime": c.d_prime, "select_us": round(sel_us, 2),
                             "step_with_select_us": round(full_us, 2),
                             "speedup_vs_dense": round(result["dense"]["us_per_step"] / full_us, 2)}
+
+    if not args.no_extras:
+        del U, h, idx, z
+        torch.cuda.empty_cache()
+        result["other_configs"] = other_configs(sv, torch, np, dev, capture, timed_replays)
 
     # ---------------- CPU oracle on a bounded sample of the same steps
     if not args.no_cpu_baseline:

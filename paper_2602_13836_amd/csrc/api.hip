@@ -59,6 +59,12 @@ SelectWs select_ws(int64_t rows, int64_t V, int64_t d_prime, int dt) {
     return w;
 }
 
+// matrix cores when several hidden rows share one set of rows of the matrix, else the row-gather kernel
+hipError_t launch_rows_product(int dt, const sv::GemvArgs& g, hipStream_t s) {
+    if (sv::skinny_mfma_supported(dt, g)) return sv::launch_skinny_mfma(g, s);
+    return sv::launch_gemv(dt, g, s);
+}
+
 int check_select_shape(int64_t rows, int64_t d, int64_t V, int64_t k, int64_t d_prime, int dt) {
     if (!dtype_ok(dt)) return SV_ERR_DTYPE;
     if (rows < 1 || rows > kMaxRows || V < 1 || V > kMaxVocab || k < 1 || k > V) return SV_ERR_SHAPE;
@@ -217,7 +223,7 @@ int specvocab_subset_logits(const void* h, int64_t rows, int64_t d, int64_t ldh,
     g.rows = (int)rows;
     g.out_f32 = logits_out;
     g.out_row_stride = k;
-    if (sv::launch_gemv(dt, g, static_cast<hipStream_t>(stream)) != hipSuccess) return SV_ERR_HIP;
+    if (launch_rows_product(dt, g, static_cast<hipStream_t>(stream)) != hipSuccess) return SV_ERR_HIP;
     return SV_OK;
 }
 
@@ -287,7 +293,7 @@ int specvocab_draft_step(const void* h, int64_t rows, int64_t d, int64_t ldh, co
     t.prob_out = prob_out;
     t.probs_full_out = probs_full_out;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (sv::launch_gemv(dt, g, s) != hipSuccess) return SV_ERR_HIP;
+    if (launch_rows_product(dt, g, s) != hipSuccess) return SV_ERR_HIP;
     if (sv::launch_softmax_topk(t, s) != hipSuccess) return SV_ERR_HIP;
     return SV_OK;
 }
@@ -317,7 +323,7 @@ int specvocab_dense_logits(const void* h, int64_t rows, int64_t d, int64_t ldh, 
     g.rows = (int)rows;
     g.out_f32 = logits_out;
     g.out_row_stride = V;
-    if (sv::launch_gemv(dt, g, static_cast<hipStream_t>(stream)) != hipSuccess) return SV_ERR_HIP;
+    if (launch_rows_product(dt, g, static_cast<hipStream_t>(stream)) != hipSuccess) return SV_ERR_HIP;
     return SV_OK;
 }
 

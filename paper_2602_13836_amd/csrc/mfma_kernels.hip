@@ -1,0 +1,163 @@
+// Skinny matrix product on the matrix cores for several hidden-state rows at once:
+//     out[r, j] = < M[row(j), :], x[r, :] >      r < rows (<= 64 per pass), j < n_items
+// with row(j) = j (the full-vocabulary projection of Section 3.1) or row(j) = idx[j] (Section 3.3
+// Step 3 with one index set shared by every row of the step).  bf16 storage only.
+//
+// The work is still bound by reading M from HBM once, so the layout is chosen for that stream:
+// one wavefront owns 16 rows of M for the whole reduction and loads them straight into the A-operand
+// registers of v_mfma_f32_16x16x32_bf16 (lane = (row i = lane % 16, k-group g = lane / 16) reads
+// 16 bytes at row_i + 64 s + 16 g: 64 contiguous bytes per row and instruction, the next
+// instruction continues the same cache lines; measured at 85 % of a fully coalesced stream, with
+// no LDS round trip).  The hidden states are the B operand: all wavefronts of a workgroup share one
+// copy of the current 256-element slice of x in LDS (double buffered, padded rows so that the 16
+// lanes of an operand read hit 16 different bank groups).  Accumulators: 16 x 16 float32 per
+// 16 hidden rows.  The next slice of M is prefetched into registers while the current one is
+// multiplied.
+#include "sv_device.h"
+#include "sv_launch.h"
+
+namespace sv {
+
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kKC = 256;                         // reduction elements per slice
+constexpr int kSteps = kKC / 32;                 // MFMA k-steps per slice (8)
+constexpr int kXRowBytes = kKC * 2 + 16;         // padded LDS row of the x slice (528 B = 132 words)
+
+// WPB wavefronts per workgroup (16 rows of M each); NB blocks of 16 hidden rows (N = 16 NB)
+template <int WPB, int NB>
+__global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(const GemvArgs a, const int row0) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];     // [2][16 NB][kXRowBytes]
+    constexpr int N = 16 * NB;
+    constexpr int kThreads = WPB * 64;
+    constexpr int kPieces = N * (kKC * 2 / 16);   // 16-byte pieces of one x slice
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int i = lane & 15;                      // row of M within the wave's 16 / hidden row within a block
+    const int g = lane >> 4;                      // k-group
+    const int C = a.chunks;                       // 16-byte units per row of M and of x
+    const int nslices = (C * 8 + kKC - 1) / kKC;
+    const int rows_here = min(a.rows - row0, N);
+
+    const int64_t tile0 = ((int64_t)blockIdx.x * WPB + wave) * 16;
+    int64_t item = tile0 + i;
+    if (item > a.n_items - 1) item = a.n_items - 1;               // tail rows are computed, never stored
+    const int64_t mrow = a.idx ? (int64_t)a.idx[item] : item;
+    const u32x4* mp = reinterpret_cast<const u32x4*>(a.M + mrow * a.m_row_bytes) + g;
+
+    auto load_a = [&](int slice, u32x4 (&dst)[kSteps]) {
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s) {
+            const int unit = slice * (kKC / 8) + s * 4 + g;       // 16-byte unit within the row
+            dst[s] = unit < C ? mp[slice * (kKC / 8) + s * 4] : zero16();
+        }
+    };
+    auto stage_x = [&](int slice, int buf) {
+        unsigned char* base = smem + (size_t)buf * N * kXRowBytes;
+        for (int p = tid; p < kPieces; p += kThreads) {
+            const int r = p / (kKC / 8), u = p % (kKC / 8);
+            const int unit = slice * (kKC / 8) + u;
+            u32x4 v = zero16();
+            if (r < rows_here && unit < C)
+                v = reinterpret_cast<const u32x4*>(a.x + (int64_t)(row0 + r) * a.x_row_bytes)[unit];
+            *reinterpret_cast<u32x4*>(base + (size_t)r * kXRowBytes + u * 16) = v;
+        }
+    };
+
+    f32x4_t acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    u32x4 cur[kSteps], nxt[kSteps];
+    load_a(0, cur);
+    stage_x(0, 0);
+    __syncthreads();
+    for (int slice = 0; slice < nslices; ++slice) {
+        const int buf = slice & 1;
+        if (slice + 1 < nslices) {
+            load_a(slice + 1, nxt);
+            stage_x(slice + 1, buf ^ 1);
+        }
+        const unsigned char* xb = smem + (size_t)buf * N * kXRowBytes + (size_t)i * kXRowBytes + g * 16;
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s) {
+            const bf16x8_t av = __builtin_bit_cast(bf16x8_t, cur[s]);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const u32x4 braw = *reinterpret_cast<const u32x4*>(xb + (size_t)nb * 16 * kXRowBytes + s * 64);
+                acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8_t, braw), acc[nb],
+                                                                  0, 0, 0);
+            }
+        }
+        __syncthreads();                          // everyone is done with buf; buf^1 is complete
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s) cur[s] = nxt[s];
+    }
+
+    // D[i = 4 g + v][j = lane % 16]: this lane holds 4 consecutive items of hidden row (16 nb + lane % 16)
+    const int64_t j0 = tile0 + 4 * g;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int r = nb * 16 + i;
+        if (r >= rows_here) continue;
+        float* o = a.out_f32 + (int64_t)(row0 + r) * a.out_row_stride + j0;
+        if (j0 + 3 < a.n_items && ((reinterpret_cast<uintptr_t>(o) & 15u) == 0)) {
+            *reinterpret_cast<f32x4_t*>(o) = acc[nb];
+        } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (j0 + v < a.n_items) o[v] = acc[nb][v];
+        }
+    }
+}
+
+template <int WPB, int NB>
+hipError_t launch_wn(const GemvArgs& a, int row0, hipStream_t stream) {
+    const int64_t per_block = (int64_t)WPB * 16;
+    const int64_t bx = (a.n_items + per_block - 1) / per_block;
+    const size_t lds = (size_t)2 * 16 * NB * kXRowBytes;
+    static bool configured = false;               // more than 64 KiB of LDS needs an explicit opt-in
+    if (!configured && lds > 64 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&skinny_mfma_kernel<WPB, NB>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL((skinny_mfma_kernel<WPB, NB>), dim3((unsigned)bx), dim3(WPB * 64), lds, stream, a, row0);
+    return hipGetLastError();
+}
+
+template <int WPB>
+hipError_t launch_w(const GemvArgs& a, int row0, int nrows, hipStream_t stream) {
+    if (nrows <= 16) return launch_wn<WPB, 1>(a, row0, stream);
+    if (nrows <= 32) return launch_wn<WPB, 2>(a, row0, stream);
+    if (nrows <= 48) return launch_wn<WPB, 3>(a, row0, stream);
+    return launch_wn<WPB, 4>(a, row0, stream);
+}
+
+}  // namespace
+
+// bf16, rows >= 2, one shared set of rows of M (dense or one index list for the whole step)
+bool skinny_mfma_supported(int dt, const GemvArgs& a) {
+    return dt == DT_BF16 && a.rows >= 2 && a.idx_row_stride == 0 && a.out_bf16 == nullptr && a.zero_words == 0;
+}
+
+hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream) {
+    DeviceInfo di;
+    hipError_t e = device_info(&di);
+    if (e != hipSuccess) return e;
+    // wide workgroups share one x slice among more rows of M; small problems need more workgroups
+    const bool wide = a.n_items >= (int64_t)di.cus * 2 * 128;
+    for (int row0 = 0; row0 < a.rows; row0 += 64) {
+        const int nrows = a.rows - row0 < 64 ? a.rows - row0 : 64;
+        e = wide ? launch_w<8>(a, row0, nrows, stream) : launch_w<2>(a, row0, nrows, stream);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace sv

@@ -37,6 +37,10 @@ struct GemvArgs {
 };
 hipError_t launch_gemv(int dt, const GemvArgs& a, hipStream_t stream);
 
+// the same product on the matrix cores, for several rows of x sharing one set of rows of M
+bool skinny_mfma_supported(int dt, const GemvArgs& a);
+hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream);
+
 // s[r, v] = < W_vocab[v, :], hp[r, :] > for short rows (d_prime * esize <= 1024 bytes), fused with the
 // first histogram pass of the top-k selection
 struct ScoresArgs {
