@@ -59,10 +59,43 @@ SelectWs select_ws(int64_t rows, int64_t V, int64_t d_prime, int dt) {
     return w;
 }
 
-// matrix cores when several hidden rows share one set of rows of the matrix, else the row-gather kernel
-hipError_t launch_rows_product(int dt, const sv::GemvArgs& g, hipStream_t s) {
-    if (sv::skinny_mfma_supported(dt, g)) return sv::launch_skinny_mfma(g, s);
-    return sv::launch_gemv(dt, g, s);
+// Picks the kernel family for out[r, j] = <M[row(r, j)], x[r]>:
+//   several hidden rows sharing one set of rows of M  -> matrix cores, M read once
+//   several hidden rows with their own sets           -> union of the sets, then matrix cores
+//   otherwise (one hidden row, float32, small cases)  -> row-gather kernel
+int launch_rows_product(int dt, const sv::GemvArgs& g, int64_t V, void* ws, size_t ws_bytes, hipStream_t s) {
+    if (sv::skinny_mfma_supported(dt, g)) return sv::launch_skinny_mfma(g, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
+    if (sv::union_path_wanted(dt, g)) {
+        if (!ws || ws_bytes < sv::union_ws_bytes(g.rows, V, g.n_items)) return SV_ERR_WORKSPACE;
+        if (!aligned16(ws)) return SV_ERR_ALIGN;
+        return sv::launch_union_logits(g, V, ws, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
+    }
+    return sv::launch_gemv(dt, g, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
+}
+
+// the gather arguments shared by specvocab_subset_logits and specvocab_draft_step
+sv::GemvArgs gather_args(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* U, int64_t ldu, int dt,
+                         const int32_t* idx, int64_t k, int idx_mode, float* logits_out) {
+    const int es = esize_of(dt);
+    sv::GemvArgs g{};
+    g.x = static_cast<const char*>(h);
+    g.x_row_bytes = ldh * es;
+    g.M = static_cast<const char*>(U);
+    g.m_row_bytes = ldu * es;
+    g.idx = idx;
+    g.idx_row_stride = idx_mode == SV_IDX_PER_ROW ? k : 0;
+    g.n_items = k;
+    g.chunks = (int)(d * es / 16);
+    g.rows = (int)rows;
+    g.out_f32 = logits_out;
+    g.out_row_stride = k;
+    return g;
+}
+
+size_t gather_ws_bytes(int64_t rows, int64_t d, int64_t V, int64_t k, int dt, int idx_mode) {
+    sv::GemvArgs g = gather_args(nullptr, rows, d, d, nullptr, d, dt, reinterpret_cast<const int32_t*>(16), k,
+                                 idx_mode, nullptr);
+    return sv::union_path_wanted(dt, g) ? sv::union_ws_bytes(rows, V, k) : 0;
 }
 
 int check_select_shape(int64_t rows, int64_t d, int64_t V, int64_t k, int64_t d_prime, int dt) {
@@ -110,9 +143,13 @@ int specvocab_workspace_bytes(int op, int64_t rows, int64_t d, int64_t V, int64_
             return SV_OK;
         }
         case SV_OP_SUBSET_LOGITS:
+        case SV_OP_DRAFT_STEP:
+            if (!dtype_ok(dt) || !mode_ok(idx_mode)) return SV_ERR_DTYPE;
+            if (rows < 1 || rows > kMaxRows || V < 1 || V > kMaxVocab || k < 1 || d < 1) return SV_ERR_SHAPE;
+            *bytes_out = gather_ws_bytes(rows, d, V, k, dt, idx_mode);
+            return SV_OK;
         case SV_OP_DRAFT_TOPK:
         case SV_OP_DENSE_LOGITS:
-        case SV_OP_DRAFT_STEP:
             return SV_OK;
         default:
             return SV_ERR_DTYPE;
@@ -156,9 +193,23 @@ int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh, const 
     sv::select_zero_range(rows, V, &g.zero_words);
     if (sv::launch_gemv(dt, g, s) != hipSuccess) return SV_ERR_HIP;
 
-    // Step 1b: s = W_vocab h' (with the first histogram pass of the selection)
+    // Step 1b: s = W_vocab h'.  One hidden row: a bandwidth-bound stream over W_vocab fused with the
+    // first histogram pass of the selection.  Several rows: a real matrix product -> matrix cores.
     const int vchunks = (int)(d_prime * es / 16);
-    if (sv::scores_supported(vchunks)) {
+    sv::GemvArgs g2{};
+    g2.x = hp;
+    g2.x_row_bytes = d_prime * es;
+    g2.M = static_cast<const char*>(W_vocab);
+    g2.m_row_bytes = d_prime * es;
+    g2.n_items = V;
+    g2.chunks = vchunks;
+    g2.rows = (int)rows;
+    g2.out_f32 = scores;
+    g2.out_row_stride = V;
+    if (sv::skinny_mfma_supported(dt, g2)) {
+        if (sv::launch_skinny_mfma(g2, s) != hipSuccess) return SV_ERR_HIP;
+        if (sv::launch_hist(scores, V, k, (int)rows, radix, s) != hipSuccess) return SV_ERR_HIP;
+    } else if (sv::scores_supported(vchunks)) {
         sv::ScoresArgs sa{};
         sa.hp = hp;
         sa.Wv = static_cast<const char*>(W_vocab);
@@ -169,16 +220,6 @@ int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh, const 
         sa.s = scores;
         if (sv::launch_scores_hist(dt, sa, radix, s) != hipSuccess) return SV_ERR_HIP;
     } else {
-        sv::GemvArgs g2{};
-        g2.x = hp;
-        g2.x_row_bytes = d_prime * es;
-        g2.M = static_cast<const char*>(W_vocab);
-        g2.m_row_bytes = d_prime * es;
-        g2.n_items = V;
-        g2.chunks = vchunks;
-        g2.rows = (int)rows;
-        g2.out_f32 = scores;
-        g2.out_row_stride = V;
         if (sv::launch_gemv(dt, g2, s) != hipSuccess) return SV_ERR_HIP;
         if (sv::launch_hist(scores, V, k, (int)rows, radix, s) != hipSuccess) return SV_ERR_HIP;
     }
@@ -199,8 +240,6 @@ int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh, const 
 int specvocab_subset_logits(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* U, int64_t V,
                             int64_t ldu, int dt, const int32_t* idx, int64_t k, int idx_mode,
                             float* logits_out, void* ws, size_t ws_bytes, void* stream) {
-    (void)ws;
-    (void)ws_bytes;
     if (!h || !U || !idx || !logits_out) return SV_ERR_NULL;
     if (!dtype_ok(dt) || !mode_ok(idx_mode)) return SV_ERR_DTYPE;
     if (rows < 1 || rows > kMaxRows || V < 1 || V > kMaxVocab || k < 1) return SV_ERR_SHAPE;
@@ -209,22 +248,8 @@ int specvocab_subset_logits(const void* h, int64_t rows, int64_t d, int64_t ldh,
     st = check_row(d, ldu, dt);
     if (st != SV_OK) return st;
     if (!aligned16(h) || !aligned16(U)) return SV_ERR_ALIGN;
-
-    const int es = esize_of(dt);
-    sv::GemvArgs g{};
-    g.x = static_cast<const char*>(h);
-    g.x_row_bytes = ldh * es;
-    g.M = static_cast<const char*>(U);
-    g.m_row_bytes = ldu * es;
-    g.idx = idx;
-    g.idx_row_stride = idx_mode == SV_IDX_PER_ROW ? k : 0;
-    g.n_items = k;
-    g.chunks = (int)(d * es / 16);
-    g.rows = (int)rows;
-    g.out_f32 = logits_out;
-    g.out_row_stride = k;
-    if (launch_rows_product(dt, g, static_cast<hipStream_t>(stream)) != hipSuccess) return SV_ERR_HIP;
-    return SV_OK;
+    const sv::GemvArgs g = gather_args(h, rows, d, ldh, U, ldu, dt, idx, k, idx_mode, logits_out);
+    return launch_rows_product(dt, g, V, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 int specvocab_draft_topk(const float* logits, const int32_t* idx, int idx_mode, int64_t rows, int64_t k,
@@ -269,19 +294,7 @@ int specvocab_draft_step(const void* h, int64_t rows, int64_t d, int64_t ldh, co
     if (st != SV_OK) return st;
     if (!aligned16(h) || !aligned16(U)) return SV_ERR_ALIGN;
 
-    const int es = esize_of(dt);
-    sv::GemvArgs g{};
-    g.x = static_cast<const char*>(h);
-    g.x_row_bytes = ldh * es;
-    g.M = static_cast<const char*>(U);
-    g.m_row_bytes = ldu * es;
-    g.idx = idx;
-    g.idx_row_stride = idx_mode == SV_IDX_PER_ROW ? k : 0;
-    g.n_items = k;
-    g.chunks = (int)(d * es / 16);
-    g.rows = (int)rows;
-    g.out_f32 = logits_out;
-    g.out_row_stride = k;
+    const sv::GemvArgs g = gather_args(h, rows, d, ldh, U, ldu, dt, idx, k, idx_mode, logits_out);
     sv::TopkArgs t{};
     t.logits = logits_out;
     t.idx = idx;
@@ -293,7 +306,8 @@ int specvocab_draft_step(const void* h, int64_t rows, int64_t d, int64_t ldh, co
     t.prob_out = prob_out;
     t.probs_full_out = probs_full_out;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (launch_rows_product(dt, g, s) != hipSuccess) return SV_ERR_HIP;
+    st = launch_rows_product(dt, g, V, ws, ws_bytes, s);
+    if (st != SV_OK) return st;
     if (sv::launch_softmax_topk(t, s) != hipSuccess) return SV_ERR_HIP;
     return SV_OK;
 }
@@ -323,8 +337,7 @@ int specvocab_dense_logits(const void* h, int64_t rows, int64_t d, int64_t ldh, 
     g.rows = (int)rows;
     g.out_f32 = logits_out;
     g.out_row_stride = V;
-    if (launch_rows_product(dt, g, static_cast<hipStream_t>(stream)) != hipSuccess) return SV_ERR_HIP;
-    return SV_OK;
+    return launch_rows_product(dt, g, V, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -122,7 +122,11 @@ hipError_t launch_dt(const GemvArgs& a, int cus, hipStream_t stream) {
     if (nl <= 1) return launch_rows<DT, 1, 4>(a, cus, stream);
     if (nl <= 2) return launch_rows<DT, 2, 4>(a, cus, stream);
     if (nl <= 4) return launch_rows<DT, 4, 2>(a, cus, stream);
-    if (nl <= 8) return launch_rows<DT, 8, 2>(a, cus, stream);
+    if (nl <= 8) {
+        // a short gather (one pass of the chip) runs slightly faster with one row per wavefront
+        if (a.n_items <= (int64_t)cus * 32) return launch_rows<DT, 8, 1>(a, cus, stream);
+        return launch_rows<DT, 8, 2>(a, cus, stream);
+    }
     if (nl <= 16) return launch_rows<DT, 16, 1>(a, cus, stream);
     int64_t bx = (a.n_items + 3) / 4;
     const int64_t cap = ((int64_t)cus * 8 + a.rows - 1) / a.rows;

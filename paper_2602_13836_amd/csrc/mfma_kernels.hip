@@ -42,10 +42,12 @@ __global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(const GemvArgs a,
     const int C = a.chunks;                       // 16-byte units per row of M and of x
     const int nslices = (C * 8 + kKC - 1) / kKC;
     const int rows_here = min(a.rows - row0, N);
+    const int64_t n_items = a.n_items_dev ? (int64_t)*a.n_items_dev : a.n_items;
+    if ((int64_t)blockIdx.x * WPB * 16 >= n_items) return;        // whole workgroup past the end
 
     const int64_t tile0 = ((int64_t)blockIdx.x * WPB + wave) * 16;
     int64_t item = tile0 + i;
-    if (item > a.n_items - 1) item = a.n_items - 1;               // tail rows are computed, never stored
+    if (item > n_items - 1) item = n_items - 1;                   // tail rows are computed, never stored
     const int64_t mrow = a.idx ? (int64_t)a.idx[item] : item;
     const u32x4* mp = reinterpret_cast<const u32x4*>(a.M + mrow * a.m_row_bytes) + g;
 
@@ -56,7 +58,23 @@ __global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(const GemvArgs a,
             dst[s] = unit < C ? mp[slice * (kKC / 8) + s * 4] : zero16();
         }
     };
-    auto stage_x = [&](int slice, int buf) {
+    // the x slice goes global -> registers -> LDS in two steps, so that its latency hides behind the
+    // multiplications of the current slice
+    constexpr int kXAll = (kPieces + kThreads - 1) / kThreads;     // 16-byte pieces per thread
+    constexpr bool kSplit = kXAll <= 4;                            // else: too many registers, stage in one go
+    constexpr int kXPer = kSplit ? kXAll : 1;
+    auto load_x = [&](int slice, u32x4 (&dst)[kXPer]) {
+#pragma unroll
+        for (int q = 0; q < kXPer; ++q) {
+            const int p = q * kThreads + tid;
+            const int r = p / (kKC / 8), u = p % (kKC / 8);
+            const int unit = slice * (kKC / 8) + u;
+            dst[q] = zero16();
+            if (p < kPieces && r < rows_here && unit < C)
+                dst[q] = reinterpret_cast<const u32x4*>(a.x + (int64_t)(row0 + r) * a.x_row_bytes)[unit];
+        }
+    };
+    auto stage_x = [&](int slice, int buf) {                       // one step: load and store at once
         unsigned char* base = smem + (size_t)buf * N * kXRowBytes;
         for (int p = tid; p < kPieces; p += kThreads) {
             const int r = p / (kKC / 8), u = p % (kKC / 8);
@@ -67,20 +85,32 @@ __global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(const GemvArgs a,
             *reinterpret_cast<u32x4*>(base + (size_t)r * kXRowBytes + u * 16) = v;
         }
     };
+    auto store_x = [&](const u32x4 (&src)[kXPer], int buf) {
+        unsigned char* base = smem + (size_t)buf * N * kXRowBytes;
+#pragma unroll
+        for (int q = 0; q < kXPer; ++q) {
+            const int p = q * kThreads + tid;
+            const int r = p / (kKC / 8), u = p % (kKC / 8);
+            if (p < kPieces) *reinterpret_cast<u32x4*>(base + (size_t)r * kXRowBytes + u * 16) = src[q];
+        }
+    };
 
     f32x4_t acc[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     u32x4 cur[kSteps], nxt[kSteps];
+    u32x4 xr[kXPer];
     load_a(0, cur);
     stage_x(0, 0);
     __syncthreads();
     for (int slice = 0; slice < nslices; ++slice) {
         const int buf = slice & 1;
-        if (slice + 1 < nslices) {
+        const bool more = slice + 1 < nslices;
+        if (more) {
             load_a(slice + 1, nxt);
-            stage_x(slice + 1, buf ^ 1);
+            if constexpr (kSplit) load_x(slice + 1, xr);
+            else stage_x(slice + 1, buf ^ 1);
         }
         const unsigned char* xb = smem + (size_t)buf * N * kXRowBytes + (size_t)i * kXRowBytes + g * 16;
 #pragma unroll
@@ -93,6 +123,8 @@ __global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(const GemvArgs a,
                                                                   0, 0, 0);
             }
         }
+        if constexpr (kSplit)
+            if (more) store_x(xr, buf ^ 1);       // the other buffer: nobody reads it during this slice
         __syncthreads();                          // everyone is done with buf; buf^1 is complete
 #pragma unroll
         for (int s = 0; s < kSteps; ++s) cur[s] = nxt[s];
@@ -105,12 +137,12 @@ __global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(const GemvArgs a,
         const int r = nb * 16 + i;
         if (r >= rows_here) continue;
         float* o = a.out_f32 + (int64_t)(row0 + r) * a.out_row_stride + j0;
-        if (j0 + 3 < a.n_items && ((reinterpret_cast<uintptr_t>(o) & 15u) == 0)) {
+        if (j0 + 3 < n_items && ((reinterpret_cast<uintptr_t>(o) & 15u) == 0)) {
             *reinterpret_cast<f32x4_t*>(o) = acc[nb];
         } else {
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-                if (j0 + v < a.n_items) o[v] = acc[nb][v];
+                if (j0 + v < n_items) o[v] = acc[nb][v];
         }
     }
 }

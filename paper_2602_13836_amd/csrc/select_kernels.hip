@@ -83,40 +83,6 @@ __host__ __device__ inline SelPtrs sel_ptrs(uint32_t* base, int64_t rows, int64_
     return p;
 }
 
-// ---- block-wide scans over kSelThreads threads (one value per thread) -----------------------
-// exclusive sum over the threads with a HIGHER index (suffix); s_w: kSelWaves words of LDS
-__device__ __forceinline__ uint32_t block_suffix_exclusive(uint32_t x, uint32_t* s_w) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t incl = x;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t o = __shfl_down(incl, off);
-        if (lane + off < 64) incl += o;
-    }
-    __syncthreads();                                       // s_w may still be read from a previous scan
-    if (lane == 0) s_w[wave] = incl;
-    __syncthreads();
-    uint32_t higher = 0;
-    for (int w = wave + 1; w < kSelWaves; ++w) higher += s_w[w];
-    return incl - x + higher;
-}
-// exclusive sum over the threads with a LOWER index (prefix)
-__device__ __forceinline__ uint32_t block_prefix_exclusive(uint32_t x, uint32_t* s_w) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t incl = x;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t o = __shfl_up(incl, off);
-        if (lane >= off) incl += o;
-    }
-    __syncthreads();
-    if (lane == 63) s_w[wave] = incl;
-    __syncthreads();
-    uint32_t lower = 0;
-    for (int w = 0; w < wave; ++w) lower += s_w[w];
-    return incl - x + lower;
-}
-
 // Histogram held as PER consecutive bins per thread (thread t owns bins [t*PER, t*PER+PER)):
 // finds the bin with  above(bin) < remain <= above(bin) + count(bin)  (above = entries in higher
 // bins) and reports (bin, above, count) in s_out to every thread.  Exactly one bin qualifies
@@ -127,7 +93,7 @@ __device__ __forceinline__ void locate_bin(const uint32_t (&c)[PER], uint32_t re
     uint32_t local = 0;
 #pragma unroll
     for (int i = 0; i < PER; ++i) local += c[i];
-    uint32_t above = block_suffix_exclusive(local, s_w);
+    uint32_t above = block_suffix_exclusive<kSelWaves>(local, s_w);
 #pragma unroll
     for (int i = PER - 1; i >= 0; --i) {
         if (above < remain && remain <= above + c[i]) {
@@ -392,7 +358,7 @@ __global__ __launch_bounds__(kSelThreads) void resolve_kernel(int64_t V, int64_t
     }
     __syncthreads();
     const uint32_t mine = tid < nb ? s_cnt[tid] + p.sure[tid] : 0u;
-    const uint32_t off = block_prefix_exclusive(mine, s_w);
+    const uint32_t off = block_prefix_exclusive<kSelWaves>(mine, s_w);
     if (tid < nb) p.offset[tid] = off;
 }
 
@@ -422,7 +388,7 @@ __global__ __launch_bounds__(kSelThreads) void emit_kernel(const float* s_all, i
     for (int i = 0; i < kEpt; ++i)
         if (v0 + i < V && key64(f32_to_ord(val[i]), (uint32_t)(v0 + i)) >= T) mask |= 1u << i;
     const uint32_t mine = (uint32_t)__popc(mask);
-    uint32_t pos = block_off + block_prefix_exclusive(mine, s_w);
+    uint32_t pos = block_off + block_prefix_exclusive<kSelWaves>(mine, s_w);
 
     int32_t* out = idx_out + r * k;
 #pragma unroll

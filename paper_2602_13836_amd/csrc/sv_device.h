@@ -130,6 +130,43 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x) {
            (uint32_t)__builtin_amdgcn_readlane((int)x, 32) + (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
 }
 
+// ---- block-wide exclusive scans, one value per thread, WAVES wavefronts per workgroup -------
+// s_w: WAVES words of LDS.  Every thread of the workgroup must call.
+// sum over the threads with a LOWER index
+template <int WAVES>
+__device__ __forceinline__ uint32_t block_prefix_exclusive(uint32_t x, uint32_t* s_w) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl = x;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = __shfl_up(incl, off);
+        if (lane >= off) incl += o;
+    }
+    __syncthreads();                                   // s_w may still be read from an earlier scan
+    if (lane == 63) s_w[wave] = incl;
+    __syncthreads();
+    uint32_t lower = 0;
+    for (int w = 0; w < wave; ++w) lower += s_w[w];
+    return incl - x + lower;
+}
+// sum over the threads with a HIGHER index
+template <int WAVES>
+__device__ __forceinline__ uint32_t block_suffix_exclusive(uint32_t x, uint32_t* s_w) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl = x;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = __shfl_down(incl, off);
+        if (lane + off < 64) incl += o;
+    }
+    __syncthreads();
+    if (lane == 0) s_w[wave] = incl;
+    __syncthreads();
+    uint32_t higher = 0;
+    for (int w = wave + 1; w < WAVES; ++w) higher += s_w[w];
+    return incl - x + higher;
+}
+
 // ---- order-preserving keys ----------------------------------------------------------------
 // a > b (floats, -0 == +0)  <=>  ord(a) > ord(b) (unsigned); finite inputs map to keys >= 0x00800000
 __device__ __forceinline__ uint32_t f32_to_ord(float f) {

@@ -34,12 +34,21 @@ struct GemvArgs {
     int64_t out_row_stride;
     uint32_t* zero_ptr;      // optional: words cleared by the same launch (scratch of a later kernel)
     size_t zero_words;
+    const uint32_t* n_items_dev;   // optional (matrix-core kernel only): the item count lives on the
+                                   // device; n_items is then an upper bound that sizes the grid
 };
 hipError_t launch_gemv(int dt, const GemvArgs& a, hipStream_t stream);
 
 // the same product on the matrix cores, for several rows of x sharing one set of rows of M
 bool skinny_mfma_supported(int dt, const GemvArgs& a);
 hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream);
+
+// Per-row index sets for several hidden rows (a draft tree): the union of the sets is formed on the
+// device, every row of M in the union is read once and multiplied with all hidden rows on the matrix
+// cores, and each (row, j) picks its logit out of that product.
+bool union_path_wanted(int dt, const GemvArgs& a);
+size_t union_ws_bytes(int64_t rows, int64_t V, int64_t k);
+hipError_t launch_union_logits(const GemvArgs& a, int64_t V, void* ws, hipStream_t stream);
 
 // s[r, v] = < W_vocab[v, :], hp[r, :] > for short rows (d_prime * esize <= 1024 bytes), fused with the
 // first histogram pass of the top-k selection

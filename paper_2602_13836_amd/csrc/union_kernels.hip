@@ -1,0 +1,148 @@
+// Gathered logits for several hidden rows with one index set per row (Section 3.3 Step 3 on the
+// batches of hidden states of a draft tree, Section 3.5).
+//
+// Gathering per (row, j) pair would read a row of U once for every hidden row that wants it; the
+// sets of one step overlap heavily (a tree's rows share most of their likely tokens), so the bytes
+// that have to move are the UNIQUE rows of U.  Per step:
+//   mark     flag[v] = 1 for every token any row asks for                       (plain stores)
+//   compact  the flagged tokens become the union list, and flag[v] becomes the token's position
+//            in it (block-local prefix sums, one atomic per workgroup to reserve a range)
+//   product  every row of U in the union x all hidden rows, on the matrix cores (mfma_kernels.hip),
+//            reading each needed row of U exactly once
+//   pick     logits[r, j] = product[r, pos[idx[r, j]]]
+// The product computes entries nobody asked for; on this part those flops are free next to the HBM
+// stream, and the kernel stays a dense, coalesced read of whole rows.
+#include "sv_device.h"
+#include "sv_launch.h"
+
+namespace sv {
+
+namespace {
+
+constexpr int kUThreads = 1024;
+constexpr int kUWaves = kUThreads / 64;
+constexpr int kUEpt = 4;
+
+struct UnionWs {
+    uint32_t* counter;   // [4]  number of tokens in the union (word 0)
+    uint32_t* pos;       // [V]  flag, then position in the union list
+    int32_t* ulist;      // [V]  union list (any order)
+    float* zu;           // [rows][zu_stride] product
+    int64_t zu_stride;
+};
+__host__ __device__ inline int64_t union_cap(int64_t rows, int64_t V, int64_t k) {
+    const int64_t pairs = rows * k;
+    const int64_t cap = pairs < V ? pairs : V;
+    return (cap + 3) & ~(int64_t)3;
+}
+inline UnionWs carve(void* ws, int64_t rows, int64_t V, int64_t k) {
+    UnionWs w;
+    uint32_t* base = static_cast<uint32_t*>(ws);
+    const size_t vpad = ((size_t)V + 3) & ~(size_t)3;
+    w.counter = base;
+    w.pos = base + 4;
+    w.ulist = reinterpret_cast<int32_t*>(base + 4 + vpad);
+    w.zu = reinterpret_cast<float*>(base + 4 + 2 * vpad);
+    w.zu_stride = union_cap(rows, V, k);
+    return w;
+}
+
+__global__ __launch_bounds__(256) void clear_kernel(uint32_t* p, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = 0u;
+}
+
+__global__ __launch_bounds__(256) void mark_kernel(const int32_t* idx, int64_t pairs, uint32_t* flag) {
+    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < pairs; p += (int64_t)gridDim.x * blockDim.x)
+        flag[idx[p]] = 1u;
+}
+
+__global__ __launch_bounds__(kUThreads) void compact_kernel(uint32_t* pos, int64_t V, int32_t* ulist,
+                                                            uint32_t* counter) {
+    __shared__ uint32_t s_w[kUWaves];
+    __shared__ uint32_t s_base;
+    const int tid = threadIdx.x;
+    const int64_t v0 = ((int64_t)blockIdx.x * kUThreads + tid) * kUEpt;
+    uint32_t f[kUEpt];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int i = 0; i < kUEpt; ++i) {
+        f[i] = (v0 + i < V) ? pos[v0 + i] : 0u;
+        mine += f[i];
+    }
+    const uint32_t before = block_prefix_exclusive<kUWaves>(mine, s_w);
+    if (tid == kUThreads - 1) {
+        const uint32_t total = before + mine;
+        s_base = total ? atomicAdd(counter, total) : 0u;
+    }
+    __syncthreads();
+    uint32_t slot = s_base + before;
+#pragma unroll
+    for (int i = 0; i < kUEpt; ++i) {
+        if (f[i]) {
+            ulist[slot] = (int32_t)(v0 + i);
+            pos[v0 + i] = slot;
+            ++slot;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void pick_kernel(const int32_t* idx, int64_t k, int64_t pairs, const uint32_t* pos,
+                                                   const float* zu, int64_t zu_stride, float* out) {
+    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < pairs; p += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = p / k;
+        out[p] = zu[r * zu_stride + pos[idx[p]]];
+    }
+}
+
+}  // namespace
+
+// bf16, one index set per row, at least two rows, and enough gathered bytes that reading only the
+// unique rows can pay for the four extra small launches (a few microseconds each)
+bool union_path_wanted(int dt, const GemvArgs& a) {
+    if (!(dt == DT_BF16 && a.rows >= 2 && a.idx != nullptr && a.idx_row_stride != 0 && a.out_bf16 == nullptr))
+        return false;
+    const int64_t pairs = (int64_t)a.rows * a.n_items;
+    const int64_t naive_bytes = pairs * (int64_t)a.chunks * 16;
+    return pairs >= 16384 && (a.rows >= 16 || naive_bytes >= ((int64_t)256 << 20));
+}
+
+size_t union_ws_bytes(int64_t rows, int64_t V, int64_t k) {
+    const size_t vpad = ((size_t)V + 3) & ~(size_t)3;
+    return (4 + 2 * vpad + (size_t)rows * (size_t)union_cap(rows, V, k)) * sizeof(uint32_t);
+}
+
+hipError_t launch_union_logits(const GemvArgs& a, int64_t V, void* ws, hipStream_t stream) {
+    DeviceInfo di;
+    hipError_t e = device_info(&di);
+    if (e != hipSuccess) return e;
+    const int64_t k = a.n_items;
+    const int64_t pairs = (int64_t)a.rows * k;
+    const UnionWs w = carve(ws, a.rows, V, k);
+
+    const size_t nclear = 4 + (size_t)V;                  // counter + flags (contiguous)
+    unsigned cb = (unsigned)((nclear + 1023) / 1024);
+    if (cb > (unsigned)di.cus * 4) cb = (unsigned)di.cus * 4;
+    hipLaunchKernelGGL(clear_kernel, dim3(cb), dim3(256), 0, stream, w.counter, nclear);
+    unsigned mb = (unsigned)((pairs + 1023) / 1024);
+    if (mb > (unsigned)di.cus * 8) mb = (unsigned)di.cus * 8;
+    hipLaunchKernelGGL(mark_kernel, dim3(mb), dim3(256), 0, stream, a.idx, pairs, w.pos);
+    const unsigned vb = (unsigned)((V + kUThreads * kUEpt - 1) / (kUThreads * kUEpt));
+    hipLaunchKernelGGL(compact_kernel, dim3(vb), dim3(kUThreads), 0, stream, w.pos, V, w.ulist, w.counter);
+
+    GemvArgs u = a;                                       // product over the union list, all hidden rows
+    u.idx = w.ulist;
+    u.idx_row_stride = 0;
+    u.n_items = w.zu_stride;                              // upper bound: sizes the grid
+    u.n_items_dev = w.counter;
+    u.out_f32 = w.zu;
+    u.out_row_stride = w.zu_stride;
+    e = launch_skinny_mfma(u, stream);
+    if (e != hipSuccess) return e;
+
+    hipLaunchKernelGGL(pick_kernel, dim3(mb), dim3(256), 0, stream, a.idx, k, pairs, w.pos, w.zu, w.zu_stride,
+                       a.out_f32);
+    return hipGetLastError();
+}
+
+}  // namespace sv
