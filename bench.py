@@ -246,7 +246,7 @@ def main():
     # (profiles/gather_gemv_config2_hbm_traffic.md)
     traffic_bytes = 67.385e6 + 0.033e6
     roofline = {"bound": "hbm",
-                "kernel": "gemv_rows_kernel<bf16, 8 loads/lane, 2 rows/wave>: row gather of 8192 rows of U "
+                "kernel": "gemv_rows_kernel<bf16, 8 loads/lane, 1 row/wave>: row gather of 8192 rows of U "
                           "(specvocab_subset_logits), 1 of the 2 launches of a step",
                 "achieved": round(gather_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(gather_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic_bytes,

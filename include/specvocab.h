@@ -106,7 +106,10 @@ int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh,
  * h: device [rows x d] stride ldh.  U: device [V x d] stride ldu.
  * idx: device int32, [rows x k] (SV_IDX_PER_ROW) or [k] (SV_IDX_PER_STEP), any order; every
  * entry must lie in [0, V) (caller's contract, unchecked).  Duplicates just repeat the value.
- * logits_out: device [rows x k] float32. */
+ * logits_out: device [rows x k] float32.
+ * With several hidden rows and one set per row (a draft tree) the union of the sets is formed in
+ * the workspace and each needed row of U is read once per step rather than once per asking row;
+ * specvocab_workspace_bytes(SV_OP_SUBSET_LOGITS, ...) says how much that needs (0 otherwise). */
 int specvocab_subset_logits(const void* h, int64_t rows, int64_t d, int64_t ldh,
                             const void* U, int64_t V, int64_t ldu, int dt,
                             const int32_t* idx, int64_t k, int idx_mode,

@@ -147,6 +147,89 @@ __global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(const GemvArgs a,
     }
 }
 
+// Small item counts (a few thousand rows of M): too few 16-row tiles to fill the chip with one
+// wavefront per tile, so the 8 wavefronts of a workgroup share ONE tile and split the reduction:
+// wavefront w takes slices w, w + 8, ... of both operands straight from global memory (x is small and
+// L2-resident), and the partial 16 x 16 N products are summed through LDS at the end.
+template <int NB>
+__global__ __launch_bounds__(512) void skinny_mfma_ksplit_kernel(const GemvArgs a, const int row0) {
+    constexpr int WPB = 8;
+    constexpr int N = 16 * NB;
+    __shared__ f32x4_t s_part[WPB][NB][64];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int i = lane & 15;
+    const int g = lane >> 4;
+    const int C = a.chunks;
+    const int nslices = (C * 8 + kKC - 1) / kKC;
+    const int rows_here = min(a.rows - row0, N);
+    const int64_t n_items = a.n_items_dev ? (int64_t)*a.n_items_dev : a.n_items;
+    const int64_t tile0 = (int64_t)blockIdx.x * 16;
+    if (tile0 >= n_items) return;
+
+    int64_t item = tile0 + i;
+    if (item > n_items - 1) item = n_items - 1;
+    const int64_t mrow = a.idx ? (int64_t)a.idx[item] : item;
+    const u32x4* mp = reinterpret_cast<const u32x4*>(a.M + mrow * a.m_row_bytes) + g;
+    const u32x4* xp[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        int r = nb * 16 + i;
+        if (r > rows_here - 1) r = rows_here - 1;         // padding rows repeat the last one, never stored
+        xp[nb] = reinterpret_cast<const u32x4*>(a.x + (int64_t)(row0 + r) * a.x_row_bytes) + g;
+    }
+
+    f32x4_t acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    for (int slice = wave; slice < nslices; slice += WPB) {
+        u32x4 av[kSteps], bv[NB][kSteps];
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s) {
+            const int off = slice * (kKC / 8) + s * 4;
+            const bool ok = off + g < C;
+            av[s] = ok ? mp[off] : zero16();
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) bv[nb][s] = ok ? xp[nb][off] : zero16();
+        }
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av[s]),
+                                                                  __builtin_bit_cast(bf16x8_t, bv[nb][s]), acc[nb],
+                                                                  0, 0, 0);
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) s_part[wave][nb][lane] = acc[nb];
+    __syncthreads();
+    if (wave >= NB) return;
+    const int nb = wave;                                   // wavefront nb sums and stores hidden rows 16 nb ..
+    f32x4_t sum = s_part[0][nb][lane];
+#pragma unroll
+    for (int w = 1; w < WPB; ++w) sum += s_part[w][nb][lane];
+    const int r = nb * 16 + i;
+    if (r >= rows_here) return;
+    const int64_t j0 = tile0 + 4 * g;
+    float* o = a.out_f32 + (int64_t)(row0 + r) * a.out_row_stride + j0;
+    if (j0 + 3 < n_items && ((reinterpret_cast<uintptr_t>(o) & 15u) == 0)) {
+        *reinterpret_cast<f32x4_t*>(o) = sum;
+    } else {
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            if (j0 + v < n_items) o[v] = sum[v];
+    }
+}
+
+template <int NB>
+hipError_t launch_ksplit(const GemvArgs& a, int row0, hipStream_t stream) {
+    const int64_t bx = (a.n_items + 15) / 16;
+    hipLaunchKernelGGL((skinny_mfma_ksplit_kernel<NB>), dim3((unsigned)bx), dim3(512), 0, stream, a, row0);
+    return hipGetLastError();
+}
+
 template <int WPB, int NB>
 hipError_t launch_wn(const GemvArgs& a, int row0, hipStream_t stream) {
     const int64_t per_block = (int64_t)WPB * 16;
@@ -184,9 +267,12 @@ hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream) {
     if (e != hipSuccess) return e;
     // wide workgroups share one x slice among more rows of M; small problems need more workgroups
     const bool wide = a.n_items >= (int64_t)di.cus * 2 * 128;
+    // few items and at most 32 hidden rows: split the reduction over the wavefronts of a workgroup
+    const bool ksplit = a.n_items <= (int64_t)di.cus * 64 && a.rows <= 32 && a.chunks >= 8 * (kKC / 8);
     for (int row0 = 0; row0 < a.rows; row0 += 64) {
         const int nrows = a.rows - row0 < 64 ? a.rows - row0 : 64;
-        e = wide ? launch_w<8>(a, row0, nrows, stream) : launch_w<2>(a, row0, nrows, stream);
+        if (ksplit) e = nrows <= 16 ? launch_ksplit<1>(a, row0, stream) : launch_ksplit<2>(a, row0, stream);
+        else e = wide ? launch_w<8>(a, row0, nrows, stream) : launch_w<2>(a, row0, nrows, stream);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

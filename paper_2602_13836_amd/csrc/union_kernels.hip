@@ -104,7 +104,7 @@ bool union_path_wanted(int dt, const GemvArgs& a) {
         return false;
     const int64_t pairs = (int64_t)a.rows * a.n_items;
     const int64_t naive_bytes = pairs * (int64_t)a.chunks * 16;
-    return pairs >= 16384 && (a.rows >= 16 || naive_bytes >= ((int64_t)256 << 20));
+    return pairs >= 16384 && (a.rows >= 16 || naive_bytes >= ((int64_t)768 << 20));
 }
 
 size_t union_ws_bytes(int64_t rows, int64_t V, int64_t k) {

@@ -45,7 +45,7 @@ LOGIT_SHAPES = [
     ("f32", 1, 4096, 700, 100, "per_step"),      # 16 loads per lane, float32
     ("f32", 2, 4100, 300, 33, "per_row"),        # long-row path, float32
     ("bf16", 7, 1024, 5000, 1000, "per_row"),
-    ("bf16", 5, 4096, 6000, 5000, "per_row"),    # few rows, enough gathered bytes for the union-of-sets path
+    ("bf16", 4, 8192, 30000, 13000, "per_row"),  # few rows, enough gathered bytes for the union-of-sets path
     ("bf16", 16, 1024, 6000, 1100, "per_row"),   # 16 rows: union-of-sets path
     ("bf16", 60, 520, 3000, 600, "per_row"),     # a tree's worth of rows, ragged reduction slice
     ("bf16", 70, 256, 4000, 300, "per_row"),     # more than 64 hidden rows: two passes
