@@ -12,54 +12,58 @@ namespace sv {
 
 namespace {
 
-template <int DT, int NL, int RPI, bool OUT_BF16>
+// FULL: every row is exactly NL * 64 16-byte units, so no load needs a bounds check
+template <int DT, int NL, int RPI, bool OUT_BF16, bool FULL>
 __global__ __launch_bounds__(256) void gemv_rows_kernel(const GemvArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t r = blockIdx.y;
     const int C = a.chunks;
-    if (a.zero_words) {     // clear a later kernel's scratch with this launch
-        const size_t nthr = (size_t)gridDim.x * gridDim.y * blockDim.x;
-        for (size_t i = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x; i < a.zero_words;
-             i += nthr)
-            a.zero_ptr[i] = 0u;
-    }
 
+    const int32_t* idx = a.idx ? a.idx + r * a.idx_row_stride : nullptr;
+    const int64_t n = a.n_items;
+    const int64_t step = (int64_t)gridDim.x * 4 * RPI;
+    int64_t it = ((int64_t)blockIdx.x * 4 + wave) * RPI;
+
+    // Order of the first requests matters for a launch that lasts only microseconds: the hidden-state
+    // row is requested first (vector loads, nothing waits for them yet), then the scalar index loads, and
+    // the rows of the matrix as soon as the indices arrive -- one dependent round trip, not three.
     const u32x4* xp = reinterpret_cast<const u32x4*>(a.x + r * a.x_row_bytes);
     u32x4 xreg[NL];
 #pragma unroll
     for (int c = 0; c < NL; ++c) {
         const int ch = c * 64 + lane;
-        xreg[c] = ch < C ? xp[ch] : zero16();
+        xreg[c] = (FULL || ch < C) ? xp[ch] : zero16();
     }
-    const int32_t* idx = a.idx ? a.idx + r * a.idx_row_stride : nullptr;
-    const int64_t n = a.n_items;
-    const int64_t step = (int64_t)gridDim.x * 4 * RPI;
+    auto row_of = [&](int64_t item) -> int64_t {
+        if (item > n - 1) item = n - 1;               // tail: recompute the last item, never stored
+        return idx ? (int64_t)idx[item] : item;
+    };
+    int64_t row[RPI];
+#pragma unroll
+    for (int q = 0; q < RPI; ++q) row[q] = row_of(it + q);
 
-    for (int64_t it = ((int64_t)blockIdx.x * 4 + wave) * RPI; it < n; it += step) {
-        const u32x4* mp[RPI];
+    auto load_rows = [&](u32x4 (&w)[RPI][NL]) {
 #pragma unroll
         for (int q = 0; q < RPI; ++q) {
-            int64_t item = it + q;
-            if (item > n - 1) item = n - 1;           // tail: recompute the last item, never stored
-            const int64_t row = idx ? (int64_t)idx[item] : item;
-            mp[q] = reinterpret_cast<const u32x4*>(a.M + row * a.m_row_bytes);
-        }
-        u32x4 w[RPI][NL];
-#pragma unroll
-        for (int q = 0; q < RPI; ++q)
+            const u32x4* mp = reinterpret_cast<const u32x4*>(a.M + row[q] * a.m_row_bytes);
 #pragma unroll
             for (int c = 0; c < NL; ++c) {
                 const int ch = c * 64 + lane;
-                w[q][c] = ch < C ? load16<true>(mp[q] + ch) : zero16();
+                w[q][c] = (FULL || ch < C) ? load16<true>(mp + ch) : zero16();
             }
+        }
+    };
+    auto finish = [&](const u32x4 (&w)[RPI][NL]) {
         float acc[RPI];
 #pragma unroll
         for (int q = 0; q < RPI; ++q) {
-            acc[q] = 0.0f;
+            // four independent partial sums: the 8 NL multiply-adds of a lane do not form one long
+            // dependent chain (it would sit in the tail of a launch that lasts only microseconds)
+            float part[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-            for (int c = 0; c < NL; ++c) acc[q] = dot16<DT>(w[q][c], xreg[c], acc[q]);
-            acc[q] = wave_sum(acc[q]);
+            for (int c = 0; c < NL; ++c) part[c & 3] = dot16<DT>(w[q][c], xreg[c], part[c & 3]);
+            acc[q] = wave_sum((part[0] + part[1]) + (part[2] + part[3]));
         }
         if (lane == 0) {
 #pragma unroll
@@ -70,6 +74,26 @@ __global__ __launch_bounds__(256) void gemv_rows_kernel(const GemvArgs a) {
                 }
             }
         }
+    };
+
+    {   // first items: peeled, so that nothing loop-invariant is computed (and waited for) up front
+        u32x4 w[RPI][NL];
+        load_rows(w);
+        finish(w);
+    }
+    for (it += step; it < n; it += step) {
+#pragma unroll
+        for (int q = 0; q < RPI; ++q) row[q] = row_of(it + q);
+        u32x4 w[RPI][NL];
+        load_rows(w);
+        finish(w);
+    }
+
+    if (a.zero_words) {     // clear a later kernel's scratch with this launch
+        const size_t nthr = (size_t)gridDim.x * gridDim.y * blockDim.x;
+        for (size_t i = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x; i < a.zero_words;
+             i += nthr)
+            a.zero_ptr[i] = 0u;
     }
 }
 
@@ -111,8 +135,14 @@ hipError_t launch_rows(const GemvArgs& a, int cus, hipStream_t stream) {
     if (bx > cap) bx = cap;
     if (bx < 1) bx = 1;
     dim3 grid((unsigned)bx, (unsigned)a.rows, 1), block(256, 1, 1);
-    if (a.out_bf16) hipLaunchKernelGGL((gemv_rows_kernel<DT, NL, RPI, true>), grid, block, 0, stream, a);
-    else hipLaunchKernelGGL((gemv_rows_kernel<DT, NL, RPI, false>), grid, block, 0, stream, a);
+    const bool full = a.chunks == NL * 64;
+    if (a.out_bf16) {
+        if (full) hipLaunchKernelGGL((gemv_rows_kernel<DT, NL, RPI, true, true>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((gemv_rows_kernel<DT, NL, RPI, true, false>), grid, block, 0, stream, a);
+    } else {
+        if (full) hipLaunchKernelGGL((gemv_rows_kernel<DT, NL, RPI, false, true>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((gemv_rows_kernel<DT, NL, RPI, false, false>), grid, block, 0, stream, a);
+    }
     return hipGetLastError();
 }
 
