@@ -244,7 +244,7 @@ def main():
     gather_gbps = gather_bytes / (gather_us * 1e-6) / 1e9
     # HBM-side bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB plain copy
     # (profiles/gather_gemv_config2_hbm_traffic.md)
-    traffic_bytes = 67.385e6 + 0.033e6
+    traffic_bytes = 67.490e6 + 0.066e6
     roofline = {"bound": "hbm",
                 "kernel": "gemv_rows_kernel<bf16, 8 loads/lane, 1 row/wave>: row gather of 8192 rows of U "
                           "(specvocab_subset_logits), 1 of the 2 launches of a step",
@@ -334,6 +334,33 @@ def main():
         result["select"] = {"d_prime": c.d_prime, "select_us": round(sel_us, 2),
                             "step_with_select_us": round(full_us, 2),
                             "speedup_vs_dense": round(result["dense"]["us_per_step"] / full_us, 2)}
+        del g_sel, g_full
+
+        # ---------------- the paper's break-even (Section 6, Table 4): SpecVocab wins over a static reduced
+        # vocabulary V' when V d'/d + k < |V'|.  Static V' = 32K most frequent tokens (the size the
+        # static-vocabulary baselines use) against SpecVocab with k = 2048 (the paper's typical k) and 8192.
+        static_idx = torch.arange(32768, dtype=torch.int32, device=dev)
+        zs = torch.empty((c.rows, 32768), dtype=torch.float32, device=dev)
+        st_us = sorted(timed_replays(capture(
+            lambda t: sv.draft_step(h[t % nd], U, static_idx, c.kd, logits_out=zs, tok_out=tok[t % nd],
+                                    prob_out=prob[t % nd]), nsel), 5))[2] * 1e3 / nsel
+        sel2k = torch.empty((c.rows, 2048), dtype=torch.int32, device=dev)
+        z2k = torch.empty((c.rows, 2048), dtype=torch.float32, device=dev)
+
+        def full2k(t):
+            i = t % nd
+            sv.select(h[i], Wd, Wv, 2048, idx_out=sel2k, ws=ws)
+            sv.draft_step(h[i], U, sel2k, c.kd, logits_out=z2k, tok_out=tok[i], prob_out=prob[i])
+        sp2k_us = sorted(timed_replays(capture(full2k, nsel), 5))[2] * 1e3 / nsel
+        result["break_even"] = {
+            "dense_full_vocab_us": result["dense"]["us_per_step"],
+            "static_32k_vocab_us": round(st_us, 2),
+            "specvocab_k2048_us": round(sp2k_us, 2),
+            "specvocab_k8192_us": round(full_us, 2),
+            "rows_equivalent": {"static": 32768, "specvocab_k2048": c.V * c.d_prime // c.d + 2048,
+                                "specvocab_k8192": c.V * c.d_prime // c.d + 8192},
+            "note": "whole draft step incl. softmax + top-10; SpecVocab legs include the selector "
+                    "(W_down, W_vocab, exact top-k); random-init selector, so timing only"}
 
     if not args.no_extras:
         del U, h, idx, z

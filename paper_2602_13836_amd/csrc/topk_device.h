@@ -140,7 +140,19 @@ __device__ __forceinline__ void softmax_topk_block(const TopkArgs& a, const int6
 
     if (n <= (uint32_t)kCap) {
         // ---- 4. rank the candidates by counting; ranks are unique (position breaks exact ties)
-        if (wave == 0) {
+        if (wave == 0 && n <= 64u) {
+            // the usual case: one candidate per lane, the others arrive by lane broadcast (no LDS latency)
+            const uint64_t mine = (uint32_t)lane < n ? s_cand[lane] : 0ull;
+            uint32_t rank = 0u;
+            for (uint32_t j = 0; j < n; ++j) {
+                const uint64_t o = readlane_u64(mine, (int)j);
+                rank += (o > mine) || (o == mine && j < (uint32_t)lane);
+            }
+            if ((uint32_t)lane < n && rank < (uint32_t)kd) {
+                a.tok_out[r * kd + rank] = key_token(mine);
+                a.prob_out[r * kd + rank] = __expf(key_value(mine) - zmax) * inv;
+            }
+        } else if (wave == 0) {
             for (uint32_t i = lane; i < n; i += 64) {
                 const uint64_t mine = s_cand[i];
                 uint32_t rank = 0u;
