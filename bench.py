@@ -30,6 +30,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E, published peak
 
 
+def note(msg):
+    """progress line on stderr, flushed before each GPU leg so that a failure names its leg"""
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
 def parse_args():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
@@ -62,6 +67,7 @@ def other_configs(sv, torch, np, dev, capture, timed_replays):
 
     out = {}
     # ---- config 3: 60 tree rows, own k=4096 subset each (half shared), top-10
+    note("config 3: tree of 60 rows")
     c = CONFIGS[3]
     U = dev_bf16(CONFIGS[2].weights())
     nst = 4
@@ -83,6 +89,7 @@ def other_configs(sv, torch, np, dev, capture, timed_replays):
     torch.cuda.empty_cache()
 
     # ---- config 4: V=262144, d=3840, 8 rows, k sweep, one set per step and one set per row
+    note("config 4: 262144-token head, 8 rows, k sweep")
     c = CONFIGS[4]
     U = dev_bf16(c.weights())
     h = dev_bf16(c.hidden(nst).reshape(nst * c.rows, c.d)).reshape(nst, c.rows, c.d)
@@ -112,6 +119,7 @@ def other_configs(sv, torch, np, dev, capture, timed_replays):
     torch.cuda.empty_cache()
 
     # ---- config 5: 512 rows, selector d'=256, k=8192, top-10: select -> logits -> softmax/top-10
+    note("config 5: 512 rows with selection")
     c = CONFIGS[5]
     U = dev_bf16(c.weights())
     Wd_np, Wv_np = c.selector()
@@ -130,6 +138,44 @@ def other_configs(sv, torch, np, dev, capture, timed_replays):
     out["config5_qwen3_select"] = {"rows": c.rows, "k": c.k, "d_prime": c.d_prime, "select_us": round(sel_us, 1),
                                    "logits_softmax_topk_us": round(step_us, 1),
                                    "end_to_end_us": round(sel_us + step_us, 1), "dense_us": round(dense_us, 1)}
+    return out
+
+
+def indexed_head_microbenchmark(sv, torch, dev, capture, timed_replays):
+    """The paper's kernel microbenchmark in kind (Section 6, "Our kernel achieves ..."): synthetic
+    activations and weights at model dimensions, one hidden row, graph replay; the fused row gather
+    against the indexed LM head done the naive way of Figure 3a (materialise U[idx] in memory, then a
+    matrix-vector product over the copy), both from this library.  Dimensions are those of public
+    model cards; values are seeded random (drawn on the device: only the timing matters here)."""
+    shapes = {"qwen3-8b": (4096, 151936), "qwen3-4b": (2560, 151936),
+              "olmo2-7b": (4096, 100352), "olmo2-1b": (2048, 100352)}
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(13836)
+    out = {}
+    for name, (d, V) in shapes.items():
+        note(f"indexed LM head microbenchmark: {name}")
+        U = (torch.randn((V, d), generator=gen, device=dev, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+        h = torch.randn((8, 1, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        per_k = {}
+        for k in (512, 2048, 8192):
+            idx = torch.stack([torch.randperm(V, generator=gen, device=dev)[:k].sort().values
+                               for _ in range(8)]).to(torch.int32).reshape(8, 1, k).contiguous()
+            z = torch.empty((1, k), dtype=torch.float32, device=dev)
+            ws = torch.empty(sv.workspace_bytes(sv.SV_OP_INDEXED_HEAD_NAIVE, 1, d, V, k, 0, 0, sv.SV_BF16),
+                             dtype=torch.uint8, device=dev)
+            torch.cuda.synchronize()
+            g1 = capture(lambda t: sv.subset_logits(h[t % 8], U, idx[t % 8], out=z), 200)
+            timed_replays(g1, 1)
+            ours = sorted(timed_replays(g1, 5))[2] * 1e3 / 200
+            g2 = capture(lambda t: sv.indexed_head_naive(h[t % 8], U, idx[t % 8], out=z, ws=ws), 200)
+            timed_replays(g2, 1)
+            ref = sorted(timed_replays(g2, 5))[2] * 1e3 / 200
+            per_k[str(k)] = {"fused_gather_us": round(ours, 2), "materialise_then_matvec_us": round(ref, 2),
+                             "speedup": round(ref / ours, 2)}
+            del g1, g2, ws
+        out[name] = {"d": d, "V": V, "k": per_k}
+        del U
+        torch.cuda.empty_cache()
     return out
 
 
@@ -220,6 +266,7 @@ def main():
         return
 
     # ---------------- the timed region: exactly K steps, one graph replay
+    note(f"config 2: capturing {K} draft steps")
     g_step = capture(step, K)
     with torch.cuda.stream(stream):
         for _ in range((W + K - 1) // K if W > 0 else 0):
@@ -237,6 +284,7 @@ def main():
     # ---------------- roofline of the dominant kernel: the row gather (specvocab_subset_logits)
     # algorithmic bytes of one launch: the k gathered rows of U + idx + h + the logits written
     gather_bytes = c.k * c.d * es + c.k * 4 + c.d * es + c.k * 4
+    note("config 2: row gather alone")
     g_gather = capture(lambda t: sv.subset_logits(h[t % nd], U, idx[t % nd], out=z[t % nd]), K)
     timed_replays(g_gather, 2)
     gr = sorted(timed_replays(g_gather, 10))
@@ -278,6 +326,7 @@ def main():
 
     if not args.no_extras:
         # ---------------- dense full-vocabulary baseline on the same GPU
+        note("config 2: dense baseline")
         nden = 50
         zd = torch.empty((c.rows, c.V), dtype=torch.float32, device=dev)
         g_dense = capture(lambda t: sv.dense_logits(h[t % nd], U, out=zd), nden)
@@ -293,6 +342,7 @@ def main():
         del g_dense, zd
 
         # ---------------- cold: rotate U over several copies so no row is re-touched in cache
+        note("config 2: cold (rotating copies of U)")
         ncopy = max(1, int(args.cold_copies))
         copies = [U] + [U.clone() for _ in range(ncopy - 1)]
         g_cold = capture(lambda t: step(t, copies[t % ncopy]), K)
@@ -311,6 +361,7 @@ def main():
         torch.cuda.empty_cache()
 
         # ---------------- the selector at the same shape, and the whole step including it
+        note("config 2: selector")
         Wd_np, Wv_np = c.selector()
         Wd, Wv = dev_bf16(Wd_np), dev_bf16(Wv_np)
         ws = torch.empty(sv.workspace_bytes(sv.SV_OP_SELECT, c.rows, c.d, c.V, c.k, c.d_prime, 0, sv.SV_BF16),
@@ -339,6 +390,7 @@ def main():
         # ---------------- the paper's break-even (Section 6, Table 4): SpecVocab wins over a static reduced
         # vocabulary V' when V d'/d + k < |V'|.  Static V' = 32K most frequent tokens (the size the
         # static-vocabulary baselines use) against SpecVocab with k = 2048 (the paper's typical k) and 8192.
+        note("config 2: break-even against a static 32K vocabulary")
         static_idx = torch.arange(32768, dtype=torch.int32, device=dev)
         zs = torch.empty((c.rows, 32768), dtype=torch.float32, device=dev)
         st_us = sorted(timed_replays(capture(
@@ -366,9 +418,11 @@ def main():
         del U, h, idx, z
         torch.cuda.empty_cache()
         result["other_configs"] = other_configs(sv, torch, np, dev, capture, timed_replays)
+        result["indexed_lm_head_microbenchmark"] = indexed_head_microbenchmark(sv, torch, dev, capture, timed_replays)
 
     # ---------------- CPU oracle on a bounded sample of the same steps
     if not args.no_cpu_baseline:
+        note("CPU oracle on a sample of the same steps")
         import oracle
         n_cpu, t_cpu = 0, 0.0
         tc0 = time.perf_counter()

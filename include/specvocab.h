@@ -67,7 +67,8 @@ typedef enum {
     SV_OP_SUBSET_LOGITS = 1,
     SV_OP_DRAFT_TOPK = 2,
     SV_OP_DENSE_LOGITS = 3,
-    SV_OP_DRAFT_STEP = 4
+    SV_OP_DRAFT_STEP = 4,
+    SV_OP_INDEXED_HEAD_NAIVE = 5
 } sv_op;
 
 /* Largest kd the draft top-kd accepts. */
@@ -141,6 +142,18 @@ int specvocab_draft_step(const void* h, int64_t rows, int64_t d, int64_t ldh,
                          const int32_t* idx, int64_t k, int idx_mode, int64_t kd,
                          float* logits_out, int32_t* tok_out, float* prob_out, float* probs_full_out,
                          void* ws, size_t ws_bytes, void* stream);
+
+/* Comparator, not part of the method: the indexed LM head done the naive way the paper's kernel
+ * replaces (Section 3.5 "Custom kernel", Figure 3a): U' = U[idx, :] is first materialised in the
+ * workspace (k rows read and written), then logits_out = U' h is computed over the copy (k rows read
+ * again).  Same arguments and results as specvocab_subset_logits; exists so that the benchmark can
+ * put the fused gather next to the three-times-the-traffic path on the same GPU.
+ * One index set per hidden row or per step; the workspace holds rows x k x d (or k x d) elements. */
+int specvocab_indexed_head_naive(const void* h, int64_t rows, int64_t d, int64_t ldh,
+                                 const void* U, int64_t V, int64_t ldu, int dt,
+                                 const int32_t* idx, int64_t k, int idx_mode,
+                                 float* logits_out,
+                                 void* ws, size_t ws_bytes, void* stream);
 
 /* Section 3.1, the full-vocabulary baseline:  logits_out[r, v] = < U[v, :], h[r, :] >.
  * logits_out: device [rows x V] float32. */

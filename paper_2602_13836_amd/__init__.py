@@ -19,6 +19,7 @@ SV_OK = 0
 SV_F32, SV_BF16 = 0, 1
 SV_IDX_PER_ROW, SV_IDX_PER_STEP = 0, 1
 SV_OP_SELECT, SV_OP_SUBSET_LOGITS, SV_OP_DRAFT_TOPK, SV_OP_DENSE_LOGITS, SV_OP_DRAFT_STEP = 0, 1, 2, 3, 4
+SV_OP_INDEXED_HEAD_NAIVE = 5
 MAX_KD = 64
 
 EXPORTS = (
@@ -29,6 +30,7 @@ EXPORTS = (
     "specvocab_subset_logits",
     "specvocab_draft_topk",
     "specvocab_draft_step",
+    "specvocab_indexed_head_naive",
     "specvocab_dense_logits",
 )
 
@@ -67,6 +69,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.specvocab_subset_logits.restype = ci
     lib.specvocab_subset_logits.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, ci, vp, vp,
                                             ctypes.c_size_t, vp]
+    lib.specvocab_indexed_head_naive.restype = ci
+    lib.specvocab_indexed_head_naive.argtypes = lib.specvocab_subset_logits.argtypes
     lib.specvocab_draft_topk.restype = ci
     lib.specvocab_draft_topk.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.specvocab_draft_step.restype = ci
@@ -194,6 +198,29 @@ def subset_logits(h: torch.Tensor, U: torch.Tensor, idx: torch.Tensor,
                                                   mode, _ptr(out), _ptr(ws),
                                                   0 if ws is None else ws.numel(), _stream(stream)),
            "specvocab_subset_logits")
+    return out
+
+
+def indexed_head_naive(h: torch.Tensor, U: torch.Tensor, idx: torch.Tensor,
+                       out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
+                       stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """specvocab_indexed_head_naive: the comparator that materialises U[idx] and multiplies the copy."""
+    rows, d, ldh = _mat(h, "h")
+    V, d2, ldu = _mat(U, "U")
+    if d2 != d:
+        raise ValueError("U and h disagree on d")
+    dt = _dt(h)
+    if _dt(U) != dt:
+        raise TypeError("h and U must share a dtype")
+    mode, k = _idx(idx, rows)
+    if out is None:
+        out = torch.empty((rows, k), dtype=torch.float32, device=h.device)
+    nbytes = workspace_bytes(SV_OP_INDEXED_HEAD_NAIVE, rows, d, V, k, 0, 0, dt, mode)
+    ws = _workspace(nbytes, h.device, ws)
+    _check(load_library().specvocab_indexed_head_naive(_ptr(h), rows, d, ldh, _ptr(U), V, ldu, dt, _ptr(idx), k,
+                                                       mode, _ptr(out), _ptr(ws),
+                                                       0 if ws is None else ws.numel(), _stream(stream)),
+           "specvocab_indexed_head_naive")
     return out
 
 

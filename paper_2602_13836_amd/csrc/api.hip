@@ -148,6 +148,13 @@ int specvocab_workspace_bytes(int op, int64_t rows, int64_t d, int64_t V, int64_
             if (rows < 1 || rows > kMaxRows || V < 1 || V > kMaxVocab || k < 1 || d < 1) return SV_ERR_SHAPE;
             *bytes_out = gather_ws_bytes(rows, d, V, k, dt, idx_mode);
             return SV_OK;
+        case SV_OP_INDEXED_HEAD_NAIVE: {
+            if (!dtype_ok(dt) || !mode_ok(idx_mode)) return SV_ERR_DTYPE;
+            if (rows < 1 || rows > kMaxRows || k < 1 || d < 1) return SV_ERR_SHAPE;
+            const int64_t sets = idx_mode == SV_IDX_PER_ROW ? rows : 1;
+            *bytes_out = round256((size_t)sets * (size_t)k * (size_t)d * (size_t)esize_of(dt));
+            return SV_OK;
+        }
         case SV_OP_DRAFT_TOPK:
         case SV_OP_DENSE_LOGITS:
             return SV_OK;
@@ -250,6 +257,45 @@ int specvocab_subset_logits(const void* h, int64_t rows, int64_t d, int64_t ldh,
     if (!aligned16(h) || !aligned16(U)) return SV_ERR_ALIGN;
     const sv::GemvArgs g = gather_args(h, rows, d, ldh, U, ldu, dt, idx, k, idx_mode, logits_out);
     return launch_rows_product(dt, g, V, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+int specvocab_indexed_head_naive(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* U, int64_t V,
+                                 int64_t ldu, int dt, const int32_t* idx, int64_t k, int idx_mode,
+                                 float* logits_out, void* ws, size_t ws_bytes, void* stream) {
+    if (!h || !U || !idx || !logits_out) return SV_ERR_NULL;
+    if (!dtype_ok(dt) || !mode_ok(idx_mode)) return SV_ERR_DTYPE;
+    if (rows < 1 || rows > kMaxRows || V < 1 || V > kMaxVocab || k < 1) return SV_ERR_SHAPE;
+    int st = check_row(d, ldh, dt);
+    if (st != SV_OK) return st;
+    st = check_row(d, ldu, dt);
+    if (st != SV_OK) return st;
+    if (!aligned16(h) || !aligned16(U) || !aligned16(ws)) return SV_ERR_ALIGN;
+    const int es = esize_of(dt);
+    const int64_t sets = idx_mode == SV_IDX_PER_ROW ? rows : 1;
+    const size_t need = (size_t)sets * (size_t)k * (size_t)d * (size_t)es;
+    if (!ws || ws_bytes < need) return SV_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int chunks = (int)(d * es / 16);
+    // 1. U' = U[idx, :] written out (Figure 3a: read k rows, write k rows)
+    if (sv::launch_materialize_rows(static_cast<const char*>(U), ldu * es, idx, sets * k, chunks,
+                                    static_cast<char*>(ws), s) != hipSuccess)
+        return SV_ERR_HIP;
+    // 2. logits = U' h over the copy (read k rows again): the dense row kernel, one hidden row at a time
+    for (int64_t r = 0; r < rows; ++r) {
+        sv::GemvArgs g{};
+        g.x = static_cast<const char*>(h) + r * ldh * es;
+        g.x_row_bytes = ldh * es;
+        g.M = static_cast<const char*>(ws) + (idx_mode == SV_IDX_PER_ROW ? (size_t)r * k * d * es : 0);
+        g.m_row_bytes = d * es;
+        g.idx = nullptr;
+        g.n_items = k;
+        g.chunks = chunks;
+        g.rows = 1;
+        g.out_f32 = logits_out + r * k;
+        g.out_row_stride = k;
+        if (sv::launch_gemv(dt, g, s) != hipSuccess) return SV_ERR_HIP;
+    }
+    return SV_OK;
 }
 
 int specvocab_draft_topk(const float* logits, const int32_t* idx, int idx_mode, int64_t rows, int64_t k,

@@ -127,6 +127,20 @@ __global__ __launch_bounds__(256) void gemv_long_rows_kernel(const GemvArgs a) {
     }
 }
 
+// dst[j, :] = M[idx[j], :]: one wavefront per row, 16 bytes per lane and step
+__global__ __launch_bounds__(256) void materialize_rows_kernel(const char* M, int64_t m_row_bytes,
+                                                               const int32_t* idx, int64_t n_rows, int chunks,
+                                                               char* dst) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t step = (int64_t)gridDim.x * 4;
+    for (int64_t j = (int64_t)blockIdx.x * 4 + wave; j < n_rows; j += step) {
+        const u32x4* src = reinterpret_cast<const u32x4*>(M + (int64_t)idx[j] * m_row_bytes);
+        u32x4* out = reinterpret_cast<u32x4*>(dst + j * (int64_t)chunks * 16);
+        for (int ch = lane; ch < chunks; ch += 64) out[ch] = src[ch];
+    }
+}
+
 template <int DT, int NL, int RPI>
 hipError_t launch_rows(const GemvArgs& a, int cus, hipStream_t stream) {
     const int64_t waves = (a.n_items + RPI - 1) / RPI;
@@ -169,6 +183,19 @@ hipError_t launch_dt(const GemvArgs& a, int cus, hipStream_t stream) {
 }
 
 }  // namespace
+
+hipError_t launch_materialize_rows(const char* M, int64_t m_row_bytes, const int32_t* idx, int64_t n_rows,
+                                   int chunks, char* dst, hipStream_t stream) {
+    DeviceInfo di;
+    hipError_t e = device_info(&di);
+    if (e != hipSuccess) return e;
+    int64_t bx = (n_rows + 3) / 4;
+    if (bx > (int64_t)di.cus * 8) bx = (int64_t)di.cus * 8;
+    if (bx < 1) bx = 1;
+    hipLaunchKernelGGL(materialize_rows_kernel, dim3((unsigned)bx), dim3(256), 0, stream, M, m_row_bytes, idx, n_rows,
+                       chunks, dst);
+    return hipGetLastError();
+}
 
 hipError_t launch_gemv(int dt, const GemvArgs& a, hipStream_t stream) {
     DeviceInfo di;

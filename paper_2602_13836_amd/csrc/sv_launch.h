@@ -39,6 +39,10 @@ struct GemvArgs {
 };
 hipError_t launch_gemv(int dt, const GemvArgs& a, hipStream_t stream);
 
+// copies rows M[idx[j], :] (j < n_sets * k) into a dense [n_sets * k x chunks * 16 B] matrix
+hipError_t launch_materialize_rows(const char* M, int64_t m_row_bytes, const int32_t* idx, int64_t n_rows,
+                                   int chunks, char* dst, hipStream_t stream);
+
 // the same product on the matrix cores, for several rows of x sharing one set of rows of M
 bool skinny_mfma_supported(int dt, const GemvArgs& a);
 hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream);

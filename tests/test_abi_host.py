@@ -96,6 +96,11 @@ def test_dense_select_topk_reject_bad_arguments(lib):
     assert s(A, 1, 256, 256, A, 30, A, 1000, 1, 10, A, None, A, 1 << 30, None) == 6         # d' % 8
     assert s(A, 1, 256, 256, A, 32, A, 1000, 4, 10, A, None, A, 1 << 30, None) == 3
 
+    n = lib.specvocab_indexed_head_naive
+    assert n(A, 1, 256, 256, A, 1000, 256, 1, A, 100, 0, A, None, 0, None) == 5          # needs its workspace
+    assert n(A, 1, 256, 256, A, 1000, 256, 1, None, 100, 0, A, A, 1 << 30, None) == 1
+    assert sv.workspace_bytes(sv.SV_OP_INDEXED_HEAD_NAIVE, 2, 4096, 128256, 8192) == 2 * 8192 * 4096 * 2
+
     f = lib.specvocab_draft_step
     assert f(A, 1, 256, 256, A, 1000, 256, 1, A, 100, 0, 10, None, A, A, None, None, 0, None) == 1   # no logits_out
     assert f(A, 1, 256, 256, A, 1000, 256, 1, A, 100, 0, 101, A, A, A, None, None, 0, None) == 2     # kd > k

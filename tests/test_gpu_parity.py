@@ -102,6 +102,26 @@ def test_duplicate_and_unsorted_indices_are_just_gathered():
     assert z[0, 1] == z[0, 2] == z[0, 6] and z[0, 0] == z[0, 4]
 
 
+@pytest.mark.parametrize("dtype,rows,d,V,k,mode", [
+    ("bf16", 1, 2048, 9000, 512, "per_row"), ("bf16", 1, 2560, 7000, 2048, "per_row"),
+    ("bf16", 3, 4096, 5000, 700, "per_row"), ("bf16", 2, 1024, 3000, 333, "per_step"), ("f32", 1, 256, 8192, 512, "per_row"),
+])
+def test_naive_indexed_head_comparator(dtype, rows, d, V, k, mode):
+    """The materialise-then-multiply comparator must give the logits of the fused gather."""
+    say(f"naive indexed head {dtype} rows={rows} d={d} V={V} k={k} {mode}")
+    rng = np.random.default_rng(d + V + k)
+    U = rand(rng, (V, d), 0.02, dtype)
+    h = rand(rng, (rows, d), 1.0, dtype)
+    if mode == "per_step":
+        idx = np.sort(rng.permutation(V)[:k]).astype(np.int32)
+    else:
+        idx = np.stack([np.sort(rng.permutation(V)[:k]) for _ in range(rows)]).astype(np.int32)
+    tU, th, tidx = to_dev(U), to_dev(h), torch.from_numpy(idx).to(DEV)
+    zn = sv.indexed_head_naive(th, tU, tidx).cpu().numpy()
+    assert_logits_close(zn, oracle.subset_logits(h, U, idx), dtype)
+    assert_logits_close(zn, sv.subset_logits(th, tU, tidx).cpu().numpy().astype(np.float64), dtype, "naive vs fused")
+
+
 # ---------------------------------------------------------------- softmax + draft top-kd
 TOPK_SHAPES = [
     # rows, k, kd, mode
