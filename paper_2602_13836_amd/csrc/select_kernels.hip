@@ -31,7 +31,8 @@ namespace {
 constexpr int kHistBits = 12;
 constexpr int kHistBins = 1 << kHistBits;                // 4096
 constexpr int kKeyLowBits = 32 - kHistBits;              // 20
-constexpr int kScoreThreads = 256;                       // scores_hist workgroup
+constexpr int kScoreThreads = 1024;                      // scores_hist workgroup
+constexpr int kScoreWaves = kScoreThreads / 64;
 constexpr int kSelThreads = 1024;                        // collect / resolve / emit workgroup
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kMaxBlocksPerRow = 1024;                   // vocabulary blocks per row in collect / emit
@@ -129,8 +130,8 @@ __global__ __launch_bounds__(kScoreThreads) void scores_hist_kernel(const Scores
     __syncthreads();
 
     const int64_t per_iter = (int64_t)RPW * UNR;
-    const int64_t step = (int64_t)gridDim.x * 4 * per_iter;
-    for (int64_t base = ((int64_t)blockIdx.x * 4 + wave) * per_iter; base < V; base += step) {
+    const int64_t step = (int64_t)gridDim.x * kScoreWaves * per_iter;
+    for (int64_t base = ((int64_t)blockIdx.x * kScoreWaves + wave) * per_iter; base < V; base += step) {
         u32x4 w[UNR];
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
@@ -191,9 +192,9 @@ __global__ __launch_bounds__(kScoreThreads) void hist_kernel(const float* s_all,
 template <int DT, int G>
 hipError_t launch_scores_g(const ScoresArgs& a, uint32_t* scratch, int cus, hipStream_t stream) {
     constexpr int UNR = 8;
-    const int64_t per_block = (int64_t)(64 / G) * UNR * 4;
+    const int64_t per_block = (int64_t)(64 / G) * UNR * kScoreWaves;
     int64_t bx = (a.V + per_block - 1) / per_block;
-    int64_t cap = ((int64_t)cus * 2 + a.rows - 1) / a.rows;     // a few long-lived blocks per CU
+    int64_t cap = ((int64_t)cus + a.rows - 1) / a.rows;         // one long-lived block per CU
     if (cap < 1) cap = 1;
     if (bx > cap) bx = cap;
     hipLaunchKernelGGL((scores_hist_kernel<DT, G, UNR>), dim3((unsigned)bx, (unsigned)a.rows),
