@@ -1,8 +1,8 @@
 // Candidate-vocabulary selection (Section 3.3): approximate logits s = W_vocab h' (Step 1) and
 // k_t = top-k(s_t, k) (Step 2), exact, ids in ascending order, ties to the smaller id.
 //
-// Four launches after the down-projection.  Every step that needs a result of the whole row sits
-// behind a kernel boundary: on this multi-die part a kernel boundary is the cheapest device-wide
+// Three launches after the down-projection (four with many hidden rows).  Every step that needs a
+// result of the whole row sits behind a kernel boundary: on this multi-die part a kernel boundary is the cheapest device-wide
 // synchronisation (a device-scope release fence writes back a whole L2, and atomics on one address
 // serialise at ~50 ns each), so there is no "last block" hand-over and no contended counter.
 //   scores_hist   streams W_vocab once.  A selector row is short (d' = d/16 .. d/8: a few hundred
@@ -15,10 +15,12 @@
 //                 largest score (redundantly: cheaper than one more launch); it then counts its
 //                 scores in bins above B (all selected) and appends (key, id) of its scores in
 //                 bin B to the row's candidate list.
-//   resolve       one block per row: MSB-first radix selection among the candidates over the
-//                 remaining 20 key bits and, only if scores tie exactly, the inverted id bits,
-//                 which yields a 64-bit threshold T with  selected(v) <=> (key(v) << 32 | ~v) >= T ;
-//                 it also turns the per-block counts into output offsets.
+//   resolve       MSB-first radix selection among the candidates over the remaining 20 key bits
+//                 and, only if scores tie exactly, the inverted id bits, which yields a 64-bit
+//                 threshold T with  selected(v) <=> (key(v) << 32 | ~v) >= T ; it also turns the
+//                 per-block counts into output offsets.  With up to 4 hidden rows every emit block
+//                 does this itself (redundant work, one launch less); with more rows it is one
+//                 block per row in a launch of its own.
 //   emit          every block re-evaluates the predicate on its entries in id order and writes the
 //                 selected ids (and scores) at its offset: the output is ascending by construction.
 #include "sv_device.h"
@@ -283,15 +285,18 @@ __global__ __launch_bounds__(kSelThreads) void collect_kernel(const float* s_all
 // ------------------------------------------------------------------------------------------
 // resolve: one block per row
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kSelThreads) void resolve_kernel(int64_t V, int64_t k, uint32_t* scratch, int rows) {
-    __shared__ uint32_t s_hist[2048];
-    __shared__ uint32_t s_w[kSelWaves];
-    __shared__ uint32_t s_out[4];
-    __shared__ uint32_t s_cnt[kMaxBlocksPerRow];
+struct ResolveSmem {
+    uint32_t hist[2048];
+    uint32_t w[kSelWaves];
+    uint32_t out[4];
+    uint32_t cnt[kMaxBlocksPerRow];
+};
+
+// Row-wide part of the selection, run by one whole workgroup: the 64-bit threshold T and, in thread
+// t, the first output slot of vocabulary block t.
+__device__ __forceinline__ void resolve_row(const SelPtrs& p, const SelLayout& L, int64_t k, ResolveSmem& sm,
+                                            uint64_t& T, uint32_t& offset_of_block_tid) {
     const int tid = threadIdx.x;
-    const int64_t r = blockIdx.x;
-    const SelLayout L = sel_layout(V, rows);
-    const SelPtrs p = sel_ptrs(scratch, rows, r, L);
     const uint32_t B = p.binfo[0];
     const uint32_t above = p.binfo[1];
     const uint32_t n = p.state[ST_NCAND];
@@ -305,6 +310,15 @@ __global__ __launch_bounds__(kSelThreads) void resolve_kernel(int64_t V, int64_t
         const uint32_t j = (uint32_t)i * kSelThreads + tid;
         sk[i] = (in_regs && j < n) ? (p.cand[j] & kSubMask) : 0ull;
     }
+    auto for_each_candidate = [&](auto&& f) {
+        if (in_regs) {
+#pragma unroll
+            for (int i = 0; i < kCandPerThread; ++i)
+                if ((uint32_t)i * kSelThreads + tid < n) f(sk[i]);
+        } else {
+            for (uint32_t j = tid; j < n; j += kSelThreads) f(p.cand[j] & kSubMask);
+        }
+    };
 
     uint32_t remain = (uint32_t)k - above;              // 1 <= remain <= n
     uint64_t prefix = 0ull;                             // decided high bits of the threshold sub-key
@@ -315,61 +329,65 @@ __global__ __launch_bounds__(kSelThreads) void resolve_kernel(int64_t V, int64_t
     for (int pass = 0; pass < 5 && !all_of_prefix; ++pass) {
         const int w = widths[pass];
         const int shift = 52 - decided - w;
-        s_hist[tid] = 0u;
-        s_hist[tid + kSelThreads] = 0u;
+        sm.hist[tid] = 0u;
+        sm.hist[tid + kSelThreads] = 0u;
         __syncthreads();
-        auto count = [&](uint64_t x) {
+        for_each_candidate([&](uint64_t x) {
             if (decided == 0 || (x >> (52 - decided)) == (prefix >> (52 - decided)))
-                atomicAdd(&s_hist[(uint32_t)(x >> shift) & ((1u << w) - 1u)], 1u);
-        };
-        if (in_regs) {
-#pragma unroll
-            for (int i = 0; i < kCandPerThread; ++i)
-                if ((uint32_t)i * kSelThreads + tid < n) count(sk[i]);
-        } else {
-            for (uint32_t j = tid; j < n; j += kSelThreads) count(p.cand[j] & kSubMask);
-        }
+                atomicAdd(&sm.hist[(uint32_t)(x >> shift) & ((1u << w) - 1u)], 1u);
+        });
         __syncthreads();
-        const uint32_t c[2] = {s_hist[tid * 2], s_hist[tid * 2 + 1]};
-        locate_bin<2>(c, remain, s_w, s_out);
-        prefix |= (uint64_t)s_out[0] << shift;
-        remain -= s_out[1];
+        const uint32_t c[2] = {sm.hist[tid * 2], sm.hist[tid * 2 + 1]};
+        locate_bin<2>(c, remain, sm.w, sm.out);
+        prefix |= (uint64_t)sm.out[0] << shift;
+        remain -= sm.out[1];
         decided += w;
-        all_of_prefix = (remain == s_out[2]);           // every candidate with this prefix is selected
+        all_of_prefix = (remain == sm.out[2]);          // every candidate with this prefix is selected
         __syncthreads();
     }
     // threshold: selected(v) <=> (key << 32 | ~v) >= T, T = (B << 20 | prefix.hi) << 32 | prefix.lo
-    if (tid == 0) {
-        p.state[ST_T_HI] = (B << kKeyLowBits) | (uint32_t)(prefix >> 32);
-        p.state[ST_T_LO] = (uint32_t)prefix;
-    }
-    // ---- output offsets: selected entries per block = sure + selected candidates, exclusive scan
+    T = ((uint64_t)((B << kKeyLowBits) | (uint32_t)(prefix >> 32)) << 32) | (uint32_t)prefix;
+
+    // output offsets: selected entries per block = sure + selected candidates, exclusive scan
     const int nb = (int)L.nb;
-    s_cnt[tid] = 0u;
+    sm.cnt[tid] = 0u;
     __syncthreads();
-    auto tally = [&](uint64_t x) {
-        if (x >= prefix) atomicAdd(&s_cnt[(uint32_t)(~(uint32_t)x) / (uint32_t)L.chunk], 1u);
-    };
-    if (in_regs) {
-#pragma unroll
-        for (int i = 0; i < kCandPerThread; ++i)
-            if ((uint32_t)i * kSelThreads + tid < n) tally(sk[i]);
-    } else {
-        for (uint32_t j = tid; j < n; j += kSelThreads) tally(p.cand[j] & kSubMask);
+    for_each_candidate([&](uint64_t x) {
+        if (x >= prefix) atomicAdd(&sm.cnt[(uint32_t)(~(uint32_t)x) / (uint32_t)L.chunk], 1u);
+    });
+    __syncthreads();
+    const uint32_t mine = tid < nb ? sm.cnt[tid] + p.sure[tid] : 0u;
+    offset_of_block_tid = block_prefix_exclusive<kSelWaves>(mine, sm.w);
+}
+
+// one block per row (many hidden rows: the result is shared by the row's emit blocks through memory)
+__global__ __launch_bounds__(kSelThreads) void resolve_kernel(int64_t V, int64_t k, uint32_t* scratch, int rows) {
+    __shared__ ResolveSmem sm;
+    const int tid = threadIdx.x;
+    const SelLayout L = sel_layout(V, rows);
+    const SelPtrs p = sel_ptrs(scratch, rows, blockIdx.x, L);
+    uint64_t T;
+    uint32_t off;
+    resolve_row(p, L, k, sm, T, off);
+    if (tid == 0) {
+        p.state[ST_T_HI] = (uint32_t)(T >> 32);
+        p.state[ST_T_LO] = (uint32_t)T;
     }
-    __syncthreads();
-    const uint32_t mine = tid < nb ? s_cnt[tid] + p.sure[tid] : 0u;
-    const uint32_t off = block_prefix_exclusive<kSelWaves>(mine, s_w);
-    if (tid < nb) p.offset[tid] = off;
+    if (tid < (int)L.nb) p.offset[tid] = off;
 }
 
 // ------------------------------------------------------------------------------------------
 // emit
 // ------------------------------------------------------------------------------------------
+// FUSED (few hidden rows): every emit block resolves the row itself instead of reading the result of
+// a separate one-block launch -- redundant work, one launch less on the critical path.
+template <bool FUSED>
 __global__ __launch_bounds__(kSelThreads) void emit_kernel(const float* s_all, int64_t V, int64_t k,
                                                            uint32_t* scratch, int rows, int32_t* idx_out,
                                                            float* scores_out) {
     __shared__ uint32_t s_w[kSelWaves];
+    __shared__ ResolveSmem sm;
+    __shared__ uint32_t s_off;
     const int tid = threadIdx.x;
     const int64_t r = blockIdx.y;
     const SelLayout L = sel_layout(V, rows);
@@ -381,8 +399,18 @@ __global__ __launch_bounds__(kSelThreads) void emit_kernel(const float* s_all, i
     float val[kEpt];
 #pragma unroll
     for (int i = 0; i < kEpt; ++i) val[i] = (v0 + i < V) ? s[v0 + i] : 0.0f;
-    const uint64_t T = ((uint64_t)p.state[ST_T_HI] << 32) | p.state[ST_T_LO];
-    const uint32_t block_off = p.offset[blockIdx.x];
+    uint64_t T;
+    uint32_t block_off;
+    if constexpr (FUSED) {
+        uint32_t off;
+        resolve_row(p, L, k, sm, T, off);
+        if (tid == (int)blockIdx.x) s_off = off;
+        __syncthreads();
+        block_off = s_off;
+    } else {
+        T = ((uint64_t)p.state[ST_T_HI] << 32) | p.state[ST_T_LO];
+        block_off = p.offset[blockIdx.x];
+    }
 
     uint32_t mask = 0u;
 #pragma unroll
@@ -445,8 +473,13 @@ hipError_t launch_topk_of_scores(const RadixArgs& a, hipStream_t stream) {
     const SelLayout L = sel_layout(a.V, a.rows);
     const dim3 grid((unsigned)L.nb, (unsigned)a.rows), block(kSelThreads);
     hipLaunchKernelGGL(collect_kernel, grid, block, 0, stream, a.s, a.V, a.k, a.scratch, a.rows);
+    if (a.rows <= 4) {
+        hipLaunchKernelGGL(emit_kernel<true>, grid, block, 0, stream, a.s, a.V, a.k, a.scratch, a.rows, a.idx_out,
+                           a.scores_out);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(resolve_kernel, dim3((unsigned)a.rows), block, 0, stream, a.V, a.k, a.scratch, a.rows);
-    hipLaunchKernelGGL(emit_kernel, grid, block, 0, stream, a.s, a.V, a.k, a.scratch, a.rows, a.idx_out,
+    hipLaunchKernelGGL(emit_kernel<false>, grid, block, 0, stream, a.s, a.V, a.k, a.scratch, a.rows, a.idx_out,
                        a.scores_out);
     return hipGetLastError();
 }
