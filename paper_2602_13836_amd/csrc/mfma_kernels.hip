@@ -272,7 +272,8 @@ hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream) {
     for (int row0 = 0; row0 < a.rows; row0 += 64) {
         const int nrows = a.rows - row0 < 64 ? a.rows - row0 : 64;
         if (ksplit) e = nrows <= 16 ? launch_ksplit<1>(a, row0, stream) : launch_ksplit<2>(a, row0, stream);
-        else e = wide ? launch_w<8>(a, row0, nrows, stream) : launch_w<2>(a, row0, nrows, stream);
+        else if (!wide) e = launch_w<2>(a, row0, nrows, stream);
+        else e = nrows <= 32 ? launch_w<4>(a, row0, nrows, stream) : launch_w<8>(a, row0, nrows, stream);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
