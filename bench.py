@@ -386,6 +386,15 @@ def main():
                             "step_with_select_us": round(full_us, 2),
                             "speedup_vs_dense": round(result["dense"]["us_per_step"] / full_us, 2)}
         del g_sel, g_full
+        # the wider selector the paper also studies (d'/d = 1/8)
+        Wd8_np, Wv8_np = c.selector(c.d // 8)
+        Wd8, Wv8 = dev_bf16(Wd8_np), dev_bf16(Wv8_np)
+        ws8 = torch.empty(sv.workspace_bytes(sv.SV_OP_SELECT, c.rows, c.d, c.V, c.k, c.d // 8, 0, sv.SV_BF16),
+                          dtype=torch.uint8, device=dev)
+        g_sel8 = capture(lambda t: sv.select(h[t % nd], Wd8, Wv8, c.k, idx_out=sel, ws=ws8), nsel)
+        timed_replays(g_sel8, 2)
+        result["select"]["select_us_d_prime_512"] = round(sorted(timed_replays(g_sel8, 5))[2] * 1e3 / nsel, 2)
+        del g_sel8, Wd8, Wv8, ws8
 
         # ---------------- the paper's break-even (Section 6, Table 4): SpecVocab wins over a static reduced
         # vocabulary V' when V d'/d + k < |V'|.  Static V' = 32K most frequent tokens (the size the

@@ -214,6 +214,53 @@ def test_draft_step_sees_fresh_logits_in_a_reused_buffer():
         assert torch.allclose(prob, prob2, rtol=1e-5, atol=1e-9), t
 
 
+def test_whole_step_replays_from_a_graph():
+    """select -> draft_step captured once into a HIP graph and replayed with eager work and
+    synchronisations in between: every replay must reproduce the eager results."""
+    say("graph capture and replay of select + draft_step")
+    rng = np.random.default_rng(2024)
+    rows, d, dp, V, k, kd = 2, 1024, 64, 30000, 4096, 10
+    U = to_dev(rand(rng, (V, d), 0.02, "bf16"))
+    Wd = to_dev(rand(rng, (dp, d), 0.05, "bf16"))
+    Wv = to_dev(rand(rng, (V, dp), 0.05, "bf16"))
+    hs = [to_dev(rand(rng, (rows, d), 1.0, "bf16")) for _ in range(3)]
+    h = hs[0].clone()
+    ws_sel = torch.empty(sv.workspace_bytes(sv.SV_OP_SELECT, rows, d, V, k, dp, 0, sv.SV_BF16), dtype=torch.uint8,
+                         device=DEV)
+    ws_step = torch.empty(max(1, sv.workspace_bytes(sv.SV_OP_DRAFT_STEP, rows, d, V, k, 0, kd, sv.SV_BF16)),
+                          dtype=torch.uint8, device=DEV)
+    sel = torch.empty((rows, k), dtype=torch.int32, device=DEV)
+    z = torch.empty((rows, k), dtype=torch.float32, device=DEV)
+    tok = torch.empty((rows, kd), dtype=torch.int32, device=DEV)
+    prob = torch.empty((rows, kd), dtype=torch.float32, device=DEV)
+
+    def run():
+        sv.select(h, Wd, Wv, k, idx_out=sel, ws=ws_sel)
+        sv.draft_step(h, U, sel, kd, logits_out=z, tok_out=tok, prob_out=prob, ws=ws_step)
+
+    stream = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        run()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=stream):
+            run()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        h.copy_(hs[rep])                                   # eager work between the replays
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            g.replay()
+        torch.cuda.synchronize()
+        got = (sel.clone(), z.clone(), tok.clone(), prob.clone())
+        sel.zero_(); z.zero_(); tok.zero_(); prob.zero_()
+        torch.cuda.synchronize()
+        run()                                              # eager reference on the default stream
+        torch.cuda.synchronize()
+        assert torch.equal(got[0], sel) and torch.equal(got[1], z) and torch.equal(got[2], tok), rep
+        assert torch.allclose(got[3], prob, rtol=1e-6, atol=0), rep
+
+
 # ---------------------------------------------------------------- select
 SELECT_SHAPES = [
     # dtype, rows, d,   d',  V,     k
