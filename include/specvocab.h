@@ -93,7 +93,7 @@ int specvocab_workspace_bytes(int op, int64_t rows, int64_t d, int64_t V, int64_
  *     idx_out[r, :] = token ids of the k largest s[r, :], in ascending id order
  * h: device [rows x d], row stride ldh.  idx_out: device [rows x k] int32.
  * scores_out: device [rows x k] float32 receiving s[r, idx_out[r, j]], or NULL.
- * Requires 1 <= k <= V < 2^31, 1 <= d_prime, rows >= 1. */
+ * Requires 1 <= k <= V, 1 <= d_prime, rows >= 1; V above 4194304 is SV_ERR_UNSUPPORTED. */
 int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh,
                      const void* W_down, int64_t d_prime,
                      const void* W_vocab, int64_t V,

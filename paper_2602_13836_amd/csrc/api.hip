@@ -327,8 +327,6 @@ int specvocab_draft_step(const void* h, int64_t rows, int64_t d, int64_t ldh, co
                          int64_t ldu, int dt, const int32_t* idx, int64_t k, int idx_mode, int64_t kd,
                          float* logits_out, int32_t* tok_out, float* prob_out, float* probs_full_out, void* ws,
                          size_t ws_bytes, void* stream) {
-    (void)ws;
-    (void)ws_bytes;
     if (!h || !U || !idx || !logits_out || !tok_out || !prob_out) return SV_ERR_NULL;
     if (!dtype_ok(dt) || !mode_ok(idx_mode)) return SV_ERR_DTYPE;
     if (rows < 1 || rows > kMaxRows || V < 1 || V > kMaxVocab || k < 1 || k > kMaxVocab || kd < 1 || kd > k)
@@ -360,8 +358,6 @@ int specvocab_draft_step(const void* h, int64_t rows, int64_t d, int64_t ldh, co
 
 int specvocab_dense_logits(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* U, int64_t V,
                            int64_t ldu, int dt, float* logits_out, void* ws, size_t ws_bytes, void* stream) {
-    (void)ws;
-    (void)ws_bytes;
     if (!h || !U || !logits_out) return SV_ERR_NULL;
     if (!dtype_ok(dt)) return SV_ERR_DTYPE;
     if (rows < 1 || rows > kMaxRows || V < 1 || V > kMaxVocab) return SV_ERR_SHAPE;

@@ -10,12 +10,6 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 enum { DT_F32 = 0, DT_BF16 = 1 };
 
-constexpr int kWave = 64;
-
-template <int DT> struct Elem;
-template <> struct Elem<DT_F32> { static constexpr int size = 4; static constexpr int per16 = 4; };
-template <> struct Elem<DT_BF16> { static constexpr int size = 2; static constexpr int per16 = 8; };
-
 __device__ __forceinline__ u32x4 zero16() { return u32x4{0u, 0u, 0u, 0u}; }
 
 // streaming 16-byte load: the gathered rows are read once per step and need not stay in L2
