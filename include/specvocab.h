@@ -27,7 +27,11 @@
  *           undefined afterwards.  Calls that share a workspace must be ordered on one stream.
  * Errors.   Every entry point returns an sv_status.  Arguments are validated on the host before
  *           anything is enqueued; on any status other than SV_OK nothing has been launched.
- *           Index CONTENTS (range, uniqueness) are the caller's contract and are not checked.
+ *           Index CONTENTS (range, uniqueness) are the caller's contract and are not checked --
+ *           except in the debug mode switched on by the environment variable SPECVOCAB_VALIDATE=1:
+ *           every call that takes an index list then first runs a range check over it, waits for
+ *           the stream (so the call is no longer asynchronous nor capturable), and returns
+ *           SV_ERR_INDEX without launching the operation if an entry lies outside [0, V).
  * Precision.Products of the stored values are accumulated in float32 (order unspecified).
  *           With SV_BF16 storage the intermediate h' of the selector is rounded to bfloat16
  *           (round-to-nearest-even) before the second projection; with SV_F32 it stays float32.
@@ -53,6 +57,7 @@ typedef enum {
     SV_ERR_ALIGN = 4,       /* pointer or stride not 16-byte aligned */
     SV_ERR_WORKSPACE = 5,   /* workspace missing or too small */
     SV_ERR_UNSUPPORTED = 6, /* legal in principle, not handled by this build (see each function) */
+    SV_ERR_INDEX = 7,       /* debug mode only: an index lies outside [0, V) */
     SV_ERR_HIP = 8          /* a HIP runtime call (kernel launch, device query) failed */
 } sv_status;
 

@@ -6,6 +6,9 @@
 #include "sv_device.h"
 #include "sv_launch.h"
 
+#include <stdlib.h>
+#include <string.h>
+
 namespace sv {
 
 hipError_t device_info(DeviceInfo* out) {
@@ -57,6 +60,15 @@ SelectWs select_ws(int64_t rows, int64_t V, int64_t d_prime, int dt) {
     w.radix_off = w.s_off + round256((size_t)rows * (size_t)V * sizeof(float));
     w.total = w.radix_off + round256(sv::select_scratch_words(rows, V) * sizeof(uint32_t));
     return w;
+}
+
+// Debug mode (environment variable SPECVOCAB_VALIDATE=1): range-check an index list before using it.
+int validate_indices(const int32_t* idx, int64_t n, int64_t V, hipStream_t s) {
+    const char* v = getenv("SPECVOCAB_VALIDATE");
+    if (!v || strcmp(v, "1") != 0) return SV_OK;
+    unsigned bad = 0;
+    if (sv::count_bad_indices(idx, n, V, s, &bad) != hipSuccess) return SV_ERR_HIP;
+    return bad ? SV_ERR_INDEX : SV_OK;
 }
 
 // Picks the kernel family for out[r, j] = <M[row(r, j)], x[r]>:
@@ -124,6 +136,7 @@ const char* specvocab_status_string(int status) {
         case SV_ERR_ALIGN: return "pointer or row stride is not 16-byte aligned";
         case SV_ERR_WORKSPACE: return "workspace missing or too small";
         case SV_ERR_UNSUPPORTED: return "shape not supported by this build";
+        case SV_ERR_INDEX: return "an index lies outside [0, V) (debug mode)";
         case SV_ERR_HIP: return "a HIP runtime call failed";
         default: return "unknown status";
     }
@@ -255,6 +268,8 @@ int specvocab_subset_logits(const void* h, int64_t rows, int64_t d, int64_t ldh,
     st = check_row(d, ldu, dt);
     if (st != SV_OK) return st;
     if (!aligned16(h) || !aligned16(U)) return SV_ERR_ALIGN;
+    st = validate_indices(idx, idx_mode == SV_IDX_PER_ROW ? rows * k : k, V, static_cast<hipStream_t>(stream));
+    if (st != SV_OK) return st;
     const sv::GemvArgs g = gather_args(h, rows, d, ldh, U, ldu, dt, idx, k, idx_mode, logits_out);
     return launch_rows_product(dt, g, V, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
@@ -275,6 +290,8 @@ int specvocab_indexed_head_naive(const void* h, int64_t rows, int64_t d, int64_t
     const size_t need = (size_t)sets * (size_t)k * (size_t)d * (size_t)es;
     if (!ws || ws_bytes < need) return SV_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    st = validate_indices(idx, sets * k, V, s);
+    if (st != SV_OK) return st;
     const int chunks = (int)(d * es / 16);
     // 1. U' = U[idx, :] written out (Figure 3a: read k rows, write k rows)
     if (sv::launch_materialize_rows(static_cast<const char*>(U), ldu * es, idx, sets * k, chunks,
@@ -338,6 +355,8 @@ int specvocab_draft_step(const void* h, int64_t rows, int64_t d, int64_t ldh, co
     if (st != SV_OK) return st;
     if (!aligned16(h) || !aligned16(U)) return SV_ERR_ALIGN;
 
+    st = validate_indices(idx, idx_mode == SV_IDX_PER_ROW ? rows * k : k, V, static_cast<hipStream_t>(stream));
+    if (st != SV_OK) return st;
     const sv::GemvArgs g = gather_args(h, rows, d, ldh, U, ldu, dt, idx, k, idx_mode, logits_out);
     sv::TopkArgs t{};
     t.logits = logits_out;

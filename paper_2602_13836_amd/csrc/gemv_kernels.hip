@@ -127,6 +127,18 @@ __global__ __launch_bounds__(256) void gemv_long_rows_kernel(const GemvArgs a) {
     }
 }
 
+// debug aid: counts the entries of idx outside [0, V)
+__device__ unsigned int g_bad_indices;
+
+__global__ __launch_bounds__(256) void check_indices_kernel(const int32_t* idx, int64_t n, int64_t V) {
+    unsigned bad = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t v = idx[i];
+        bad += (v < 0) || (v >= V);
+    }
+    if (bad) atomicAdd(&g_bad_indices, bad);
+}
+
 // dst[j, :] = M[idx[j], :]: one wavefront per row, 16 bytes per lane and step
 __global__ __launch_bounds__(256) void materialize_rows_kernel(const char* M, int64_t m_row_bytes,
                                                                const int32_t* idx, int64_t n_rows, int chunks,
@@ -183,6 +195,23 @@ hipError_t launch_dt(const GemvArgs& a, int cus, hipStream_t stream) {
 }
 
 }  // namespace
+
+hipError_t count_bad_indices(const int32_t* idx, int64_t n, int64_t V, hipStream_t stream, unsigned* bad_out) {
+    const unsigned zero = 0;
+    hipError_t e = hipMemcpyToSymbolAsync(HIP_SYMBOL(g_bad_indices), &zero, sizeof zero, 0, hipMemcpyHostToDevice,
+                                          stream);
+    if (e != hipSuccess) return e;
+    int64_t bx = (n + 255) / 256;
+    if (bx > 1024) bx = 1024;
+    if (bx < 1) bx = 1;
+    hipLaunchKernelGGL(check_indices_kernel, dim3((unsigned)bx), dim3(256), 0, stream, idx, n, V);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = hipMemcpyFromSymbolAsync(bad_out, HIP_SYMBOL(g_bad_indices), sizeof(unsigned), 0, hipMemcpyDeviceToHost,
+                                 stream);
+    if (e != hipSuccess) return e;
+    return hipStreamSynchronize(stream);
+}
 
 hipError_t launch_materialize_rows(const char* M, int64_t m_row_bytes, const int32_t* idx, int64_t n_rows,
                                    int chunks, char* dst, hipStream_t stream) {

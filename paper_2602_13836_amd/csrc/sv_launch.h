@@ -39,6 +39,9 @@ struct GemvArgs {
 };
 hipError_t launch_gemv(int dt, const GemvArgs& a, hipStream_t stream);
 
+// debug aid: number of entries of idx[0..n) outside [0, V); synchronises the stream
+hipError_t count_bad_indices(const int32_t* idx, int64_t n, int64_t V, hipStream_t stream, unsigned* bad_out);
+
 // copies rows M[idx[j], :] (j < n_sets * k) into a dense [n_sets * k x chunks * 16 B] matrix
 hipError_t launch_materialize_rows(const char* M, int64_t m_row_bytes, const int32_t* idx, int64_t n_rows,
                                    int chunks, char* dst, hipStream_t stream);

@@ -122,6 +122,32 @@ def test_naive_indexed_head_comparator(dtype, rows, d, V, k, mode):
     assert_logits_close(zn, sv.subset_logits(th, tU, tidx).cpu().numpy().astype(np.float64), dtype, "naive vs fused")
 
 
+def test_debug_mode_rejects_out_of_range_indices(monkeypatch):
+    """SPECVOCAB_VALIDATE=1: a bad index list is reported on the host and nothing is launched."""
+    say("debug-mode index validation")
+    rng = np.random.default_rng(8)
+    d, V, k = 256, 500, 40
+    U, h = to_dev(rand(rng, (V, d), 0.02, "bf16")), to_dev(rand(rng, (2, d), 1.0, "bf16"))
+    good = torch.from_numpy(np.stack([rng.permutation(V)[:k] for _ in range(2)]).astype(np.int32)).to(DEV)
+    bad = good.clone()
+    bad[1, 7] = V                                        # one past the end
+    neg = good.clone()
+    neg[0, 0] = -1
+    monkeypatch.setenv("SPECVOCAB_VALIDATE", "1")
+    out = torch.full((2, k), 7.0, dtype=torch.float32, device=DEV)
+    for broken in (bad, neg):
+        with pytest.raises(sv.SpecVocabError) as e:
+            sv.subset_logits(h, U, broken, out=out)
+        assert e.value.status == 7
+        with pytest.raises(sv.SpecVocabError):
+            sv.draft_step(h, U, broken, 5)
+    torch.cuda.synchronize()
+    assert bool((out == 7.0).all())                      # untouched: the operation was never enqueued
+    z = sv.subset_logits(h, U, good)                     # a valid list still goes through in debug mode
+    monkeypatch.delenv("SPECVOCAB_VALIDATE")
+    assert torch.equal(z, sv.subset_logits(h, U, good))
+
+
 # ---------------------------------------------------------------- softmax + draft top-kd
 TOPK_SHAPES = [
     # rows, k, kd, mode
