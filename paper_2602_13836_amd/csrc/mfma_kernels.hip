@@ -262,6 +262,7 @@ bool skinny_mfma_supported(int dt, const GemvArgs& a) {
 }
 
 hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream) {
+    if (a.rows > 64) return launch_tile_mfma(a, stream);      // a real contraction: tile both operands
     DeviceInfo di;
     hipError_t e = device_info(&di);
     if (e != hipSuccess) return e;

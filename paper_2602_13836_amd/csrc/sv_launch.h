@@ -49,6 +49,8 @@ hipError_t launch_materialize_rows(const char* M, int64_t m_row_bytes, const int
 // the same product on the matrix cores, for several rows of x sharing one set of rows of M
 bool skinny_mfma_supported(int dt, const GemvArgs& a);
 hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream);
+// more than 64 rows of x: LDS-tiled product (launch_skinny_mfma forwards to it)
+hipError_t launch_tile_mfma(const GemvArgs& a, hipStream_t stream);
 
 // Per-row index sets for several hidden rows (a draft tree): the union of the sets is formed on the
 // device, every row of M in the union is read once and multiplied with all hidden rows on the matrix

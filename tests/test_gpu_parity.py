@@ -52,6 +52,13 @@ LOGIT_SHAPES = [
     ("bf16", 33, 3840, 2500, 2500, "per_row"),   # every row asks for the whole vocabulary
     ("bf16", 64, 1024, 9000, 77, "per_step"),    # 64 rows, one shared set
     ("bf16", 17, 4096, 1500, 1500, "per_step"),
+    ("bf16", 65, 1024, 3000, 700, "per_step"),   # more than 64 rows: LDS-tiled matrix-core kernel, ragged tiles
+    ("bf16", 130, 200, 1111, 1111, "per_step"),  # three row tiles (last one 2 rows), 25 units: ragged last slice
+    ("bf16", 200, 4096, 2000, 129, "per_step"),  # one item tile plus one item
+    ("bf16", 150, 512, 5000, 900, "per_row"),    # union of 150 sets on the tiled kernel
+    ("bf16", 256, 1024, 1500, 1500, "per_step"), # 256 x 256 tiles, hand-ordered main loop
+    ("bf16", 300, 264, 700, 300, "per_step"),    # 128-row tiles with the hand-ordered loop, ragged last slice
+    ("bf16", 500, 1000, 2100, 2100, "per_step"), # two 256-row tiles (last one 244 rows), odd slice count
 ]
 
 
@@ -299,6 +306,7 @@ SELECT_SHAPES = [
     ("bf16", 2, 1024, 512, 6000, 100),        # a full wave per selector row
     ("bf16", 1, 1024, 520, 3000, 64),         # longer than a wave-wide load: generic row kernel
     ("f32", 2, 264, 12, 700, 33),
+    ("bf16", 100, 512, 64, 3000, 500),        # a batch of rows: scores on the tiled matrix-core kernel
 ]
 
 
