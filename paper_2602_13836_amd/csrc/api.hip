@@ -211,7 +211,11 @@ int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh, const 
     g.out_row_stride = d_prime;
     g.zero_ptr = radix;                      // the selection's counters and histogram start at zero
     sv::select_zero_range(rows, V, &g.zero_words);
-    if (sv::launch_gemv(dt, g, s) != hipSuccess) return SV_ERR_HIP;
+    if (sv::ksplit_rows_supported(dt, g)) {           // a batch of rows: W_down read once per 32 of them
+        if (sv::launch_ksplit_rows(g, s) != hipSuccess) return SV_ERR_HIP;
+    } else if (sv::launch_gemv(dt, g, s) != hipSuccess) {
+        return SV_ERR_HIP;
+    }
 
     // Step 1b: s = W_vocab h'.  One hidden row: a bandwidth-bound stream over W_vocab fused with the
     // first histogram pass of the selection.  Several rows: a real matrix product -> matrix cores.

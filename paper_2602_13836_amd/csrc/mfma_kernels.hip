@@ -151,8 +151,11 @@ __global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(const GemvArgs a,
 // wavefront per tile, so the 8 wavefronts of a workgroup share ONE tile and split the reduction:
 // wavefront w takes slices w, w + 8, ... of both operands straight from global memory (x is small and
 // L2-resident), and the partial 16 x 16 N products are summed through LDS at the end.
+// blockIdx.y walks groups of 16 NB hidden rows (a batch of hidden rows against a small M, e.g. the
+// selector's down-projection of Section 3.3 Step 1); output float32 or bf16 (round to nearest even);
+// the launch can also clear scratch words of a later kernel.
 template <int NB>
-__global__ __launch_bounds__(512) void skinny_mfma_ksplit_kernel(const GemvArgs a, const int row0) {
+__global__ __launch_bounds__(512) void skinny_mfma_ksplit_kernel(const GemvArgs a, const int row_base) {
     constexpr int WPB = 8;
     constexpr int N = 16 * NB;
     __shared__ f32x4_t s_part[WPB][NB][64];
@@ -163,10 +166,16 @@ __global__ __launch_bounds__(512) void skinny_mfma_ksplit_kernel(const GemvArgs 
     const int g = lane >> 4;
     const int C = a.chunks;
     const int nslices = (C * 8 + kKC - 1) / kKC;
+    if (a.zero_words) {
+        const size_t step = (size_t)gridDim.x * gridDim.y * blockDim.x;
+        for (size_t z = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + tid; z < a.zero_words; z += step)
+            a.zero_ptr[z] = 0u;
+    }
+    const int row0 = row_base + (int)blockIdx.y * N;
     const int rows_here = min(a.rows - row0, N);
     const int64_t n_items = a.n_items_dev ? (int64_t)*a.n_items_dev : a.n_items;
     const int64_t tile0 = (int64_t)blockIdx.x * 16;
-    if (tile0 >= n_items) return;
+    if (tile0 >= n_items || rows_here <= 0) return;
 
     int64_t item = tile0 + i;
     if (item > n_items - 1) item = n_items - 1;
@@ -213,6 +222,13 @@ __global__ __launch_bounds__(512) void skinny_mfma_ksplit_kernel(const GemvArgs 
     const int r = nb * 16 + i;
     if (r >= rows_here) return;
     const int64_t j0 = tile0 + 4 * g;
+    if (a.out_bf16) {
+        uint16_t* o = a.out_bf16 + (int64_t)(row0 + r) * a.out_row_stride + j0;
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            if (j0 + v < n_items) o[v] = f32_to_bf16_rne(sum[v]);
+        return;
+    }
     float* o = a.out_f32 + (int64_t)(row0 + r) * a.out_row_stride + j0;
     if (j0 + 3 < n_items && ((reinterpret_cast<uintptr_t>(o) & 15u) == 0)) {
         *reinterpret_cast<f32x4_t*>(o) = sum;
@@ -224,9 +240,10 @@ __global__ __launch_bounds__(512) void skinny_mfma_ksplit_kernel(const GemvArgs 
 }
 
 template <int NB>
-hipError_t launch_ksplit(const GemvArgs& a, int row0, hipStream_t stream) {
+hipError_t launch_ksplit(const GemvArgs& a, int row0, int groups, hipStream_t stream) {
     const int64_t bx = (a.n_items + 15) / 16;
-    hipLaunchKernelGGL((skinny_mfma_ksplit_kernel<NB>), dim3((unsigned)bx), dim3(512), 0, stream, a, row0);
+    hipLaunchKernelGGL((skinny_mfma_ksplit_kernel<NB>), dim3((unsigned)bx, (unsigned)groups), dim3(512), 0, stream,
+                       a, row0);
     return hipGetLastError();
 }
 
@@ -261,6 +278,20 @@ bool skinny_mfma_supported(int dt, const GemvArgs& a) {
     return dt == DT_BF16 && a.rows >= 2 && a.idx_row_stride == 0 && a.out_bf16 == nullptr && a.zero_words == 0;
 }
 
+// A batch of hidden rows against few rows of M (a few thousand at most), long reductions: one launch,
+// 32 hidden rows per workgroup row.  Unlike the other matrix-core paths this one also writes bf16
+// and clears scratch, which is what the selector's down-projection needs.
+bool ksplit_rows_supported(int dt, const GemvArgs& a) {
+    DeviceInfo di;
+    if (device_info(&di) != hipSuccess) return false;
+    return dt == DT_BF16 && a.rows >= 16 && a.idx_row_stride == 0 && a.n_items_dev == nullptr &&
+           a.n_items <= (int64_t)di.cus * 16 && a.chunks >= 8 * (kKC / 8);
+}
+
+hipError_t launch_ksplit_rows(const GemvArgs& a, hipStream_t stream) {
+    return launch_ksplit<2>(a, 0, (a.rows + 31) / 32, stream);
+}
+
 hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream) {
     if (a.rows > 64) return launch_tile_mfma(a, stream);      // a real contraction: tile both operands
     DeviceInfo di;
@@ -272,7 +303,7 @@ hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream) {
     const bool ksplit = a.n_items <= (int64_t)di.cus * 64 && a.rows <= 32 && a.chunks >= 8 * (kKC / 8);
     for (int row0 = 0; row0 < a.rows; row0 += 64) {
         const int nrows = a.rows - row0 < 64 ? a.rows - row0 : 64;
-        if (ksplit) e = nrows <= 16 ? launch_ksplit<1>(a, row0, stream) : launch_ksplit<2>(a, row0, stream);
+        if (ksplit) e = nrows <= 16 ? launch_ksplit<1>(a, row0, 1, stream) : launch_ksplit<2>(a, row0, 1, stream);
         else if (!wide) e = launch_w<2>(a, row0, nrows, stream);
         else e = nrows <= 32 ? launch_w<4>(a, row0, nrows, stream) : launch_w<8>(a, row0, nrows, stream);
         if (e != hipSuccess) return e;

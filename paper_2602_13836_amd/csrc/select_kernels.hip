@@ -1,7 +1,7 @@
 // Candidate-vocabulary selection (Section 3.3): approximate logits s = W_vocab h' (Step 1) and
 // k_t = top-k(s_t, k) (Step 2), exact, ids in ascending order, ties to the smaller id.
 //
-// Three launches after the down-projection (four with many hidden rows).  Every step that needs a
+// Three launches after the down-projection (five with more than four hidden rows).  Every step that needs a
 // result of the whole row sits behind a kernel boundary: on this multi-die part a kernel boundary is the cheapest device-wide
 // synchronisation (a device-scope release fence writes back a whole L2, and atomics on one address
 // serialise at ~50 ns each), so there is no "last block" hand-over and no contended counter.
@@ -12,8 +12,9 @@
 //                 order-preserving key: in LDS per block, then merged into one of several global
 //                 replicas of the histogram (replicas keep same-address atomics apart).
 //   collect       every block first sums the replicas and finds the bin B that holds the k-th
-//                 largest score (redundantly: cheaper than one more launch); it then counts its
-//                 scores in bins above B (all selected) and appends (key, id) of its scores in
+//                 largest score (redundantly: cheaper than one more launch -- with more than four
+//                 hidden rows a launch of one block per row does it once instead); it then counts
+//                 its scores in bins above B (all selected) and appends (key, id) of its scores in
 //                 bin B to the row's candidate list.
 //   resolve       MSB-first radix selection among the candidates over the remaining 20 key bits
 //                 and, only if scores tie exactly, the inverted id bits, which yields a 64-bit
@@ -29,6 +30,8 @@
 namespace sv {
 
 namespace {
+
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kHistBits = 12;
 constexpr int kHistBins = 1 << kHistBits;                // 4096
@@ -179,8 +182,31 @@ __global__ __launch_bounds__(kScoreThreads) void hist_kernel(const float* s_all,
     const float* s = s_all + r * V;
     for (int b = tid; b < kHistBins; b += kScoreThreads) lh[b] = 0u;
     __syncthreads();
-    for (int64_t v = (int64_t)blockIdx.x * kScoreThreads + tid; v < V; v += (int64_t)gridDim.x * kScoreThreads)
-        atomicAdd(&lh[f32_to_ord(s[v]) >> kKeyLowBits], 1u);
+    // 16-byte loads, four in flight per thread; the unaligned head and the tail go one by one
+    const int64_t head = min<int64_t>(V, (int64_t)((16u - (reinterpret_cast<uintptr_t>(s) & 15u)) & 15u) / 4);
+    const int64_t nvec = (V - head) / 4;
+    const f32x4_t* sv4 = reinterpret_cast<const f32x4_t*>(s + head);
+    const int64_t stride = (int64_t)gridDim.x * kScoreThreads;
+    constexpr int UNR = 4;
+    for (int64_t q0 = (int64_t)blockIdx.x * kScoreThreads + tid; q0 < nvec; q0 += stride * UNR) {
+        f32x4_t v[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int64_t q = q0 + u * stride;
+            v[u] = q < nvec ? sv4[q] : f32x4_t{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u)
+            if (q0 + u * stride < nvec) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) atomicAdd(&lh[f32_to_ord(v[u][e]) >> kKeyLowBits], 1u);
+            }
+    }
+    if (blockIdx.x == 0) {
+        const int64_t rest = V - head - nvec * 4;        // < 4
+        if (tid < head) atomicAdd(&lh[f32_to_ord(s[tid]) >> kKeyLowBits], 1u);
+        else if (tid - head < rest) atomicAdd(&lh[f32_to_ord(s[head + nvec * 4 + (tid - head)]) >> kKeyLowBits], 1u);
+    }
     __syncthreads();
     const SelLayout L = sel_layout(V, rows);
     const SelPtrs p = sel_ptrs(scratch, rows, r, L);
@@ -219,6 +245,29 @@ __device__ __forceinline__ uint64_t key64(uint32_t key, uint32_t v) {
     return ((uint64_t)key << 32) | (uint32_t)(~v);      // larger score first, then smaller id
 }
 
+// the bin B of the k-th largest score of every row, once per row (many hidden rows: cheaper than having
+// each of the row's collect blocks work it out again)
+__global__ __launch_bounds__(kSelThreads) void locate_kernel(int64_t V, int64_t k, uint32_t* scratch, int rows) {
+    __shared__ uint32_t s_w[kSelWaves];
+    __shared__ uint32_t s_out[4];
+    const int tid = threadIdx.x;
+    const SelLayout L = sel_layout(V, rows);
+    const SelPtrs p = sel_ptrs(scratch, rows, blockIdx.x, L);
+    constexpr int PER = kHistBins / kSelThreads;
+    uint32_t c[PER] = {0u, 0u, 0u, 0u};
+    for (int rep = 0; rep < L.replicas; ++rep) {
+        const u32x4 q = reinterpret_cast<const u32x4*>(p.hist + (size_t)rep * kHistBins)[tid];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) c[i] += q[i];
+    }
+    locate_bin<PER>(c, (uint32_t)k, s_w, s_out);
+    if (tid == 0) {
+        p.binfo[0] = s_out[0];
+        p.binfo[1] = s_out[1];
+    }
+}
+
+// few hidden rows: every block finds the row's bin B itself (one launch less on the critical path)
 __global__ __launch_bounds__(kSelThreads) void collect_kernel(const float* s_all, int64_t V, int64_t k,
                                                               uint32_t* scratch, int rows) {
     __shared__ uint64_t s_list[kSelThreads * kEpt];    // this block's bin-B entries
@@ -280,6 +329,65 @@ __global__ __launch_bounds__(kSelThreads) void collect_kernel(const float* s_all
     __syncthreads();
     const uint32_t gbase = s_gbase;
     for (uint32_t i = tid; i < n_local; i += kSelThreads) p.cand[gbase + i] = s_list[i];
+}
+
+// Many hidden rows: thousands of vocabulary blocks, each a short chain of dependent memory round
+// trips (scores, then one atomic to reserve space in the candidate list).  Small workgroups with
+// many entries per thread keep eight such chains in flight per CU, and B comes from locate_kernel.
+constexpr int kRowThreads = 256;
+constexpr int kRowWaves = kRowThreads / 64;
+constexpr int kRowEpt = kSelThreads * kEpt / kRowThreads;     // 16: the same vocabulary block as above
+static_assert(kRowThreads * kRowEpt == kSelThreads * kEpt, "both forms must cut the vocabulary alike");
+static_assert(kRowThreads * kRowEpt < 65536, "two 16-bit counts are packed into one word");
+
+__global__ __launch_bounds__(kRowThreads) void collect_rows_kernel(const float* s_all, int64_t V,
+                                                                   uint32_t* scratch, int rows) {
+    __shared__ uint32_t s_w[kRowWaves];
+    __shared__ uint32_t s_gbase;
+    const int tid = threadIdx.x;
+    const int64_t r = blockIdx.y;
+    const SelLayout L = sel_layout(V, rows);
+    const SelPtrs p = sel_ptrs(scratch, rows, r, L);
+    const float* s = s_all + r * V;
+    const int64_t base = (int64_t)blockIdx.x * L.chunk;
+    const uint32_t B = p.binfo[0];
+    const bool aligned = (reinterpret_cast<uintptr_t>(s + base) & 15u) == 0;
+    // thread t owns the four-id groups t, t + 256, t + 512, t + 768 of the block (16-byte loads)
+    auto id_of = [&](int i) { return base + 4 * ((int64_t)(i >> 2) * kRowThreads + tid) + (i & 3); };
+    uint32_t key[kRowEpt];
+#pragma unroll
+    for (int j = 0; j < kRowEpt / 4; ++j) {
+        const int64_t v0 = id_of(4 * j);
+        if (aligned && v0 + 3 < V) {
+            const f32x4_t q = *reinterpret_cast<const f32x4_t*>(s + v0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) key[4 * j + e] = f32_to_ord(q[e]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) key[4 * j + e] = (v0 + e < V) ? f32_to_ord(s[v0 + e]) : 0u;
+        }
+    }
+    uint32_t packed = 0u;                                 // candidates (bin B) | sure entries (above B) << 16
+#pragma unroll
+    for (int i = 0; i < kRowEpt; ++i) {
+        const uint32_t bin = key[i] >> kKeyLowBits;
+        if (id_of(i) < V) packed += (bin == B ? 1u : 0u) + (bin > B ? 0x10000u : 0u);
+    }
+    const uint32_t pre = block_prefix_exclusive<kRowWaves>(packed, s_w);
+    if (tid == 0) {
+        uint32_t tot = 0u;
+        for (int w = 0; w < kRowWaves; ++w) tot += s_w[w];
+        p.sure[blockIdx.x] = tot >> 16;
+        const uint32_t n_local = tot & 0xffffu;
+        s_gbase = n_local ? atomicAdd(&p.state[ST_NCAND], n_local) : 0u;
+    }
+    __syncthreads();
+    uint32_t off = s_gbase + (pre & 0xffffu);
+#pragma unroll
+    for (int i = 0; i < kRowEpt; ++i) {
+        const int64_t v = id_of(i);
+        if (v < V && (key[i] >> kKeyLowBits) == B) p.cand[off++] = key64(key[i], (uint32_t)v);
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -379,9 +487,8 @@ __global__ __launch_bounds__(kSelThreads) void resolve_kernel(int64_t V, int64_t
 // ------------------------------------------------------------------------------------------
 // emit
 // ------------------------------------------------------------------------------------------
-// FUSED (few hidden rows): every emit block resolves the row itself instead of reading the result of
-// a separate one-block launch -- redundant work, one launch less on the critical path.
-template <bool FUSED>
+// few hidden rows: every emit block resolves the row itself instead of reading the result of a separate
+// one-block launch -- redundant work, one launch less on the critical path
 __global__ __launch_bounds__(kSelThreads) void emit_kernel(const float* s_all, int64_t V, int64_t k,
                                                            uint32_t* scratch, int rows, int32_t* idx_out,
                                                            float* scores_out) {
@@ -400,17 +507,11 @@ __global__ __launch_bounds__(kSelThreads) void emit_kernel(const float* s_all, i
 #pragma unroll
     for (int i = 0; i < kEpt; ++i) val[i] = (v0 + i < V) ? s[v0 + i] : 0.0f;
     uint64_t T;
-    uint32_t block_off;
-    if constexpr (FUSED) {
-        uint32_t off;
-        resolve_row(p, L, k, sm, T, off);
-        if (tid == (int)blockIdx.x) s_off = off;
-        __syncthreads();
-        block_off = s_off;
-    } else {
-        T = ((uint64_t)p.state[ST_T_HI] << 32) | p.state[ST_T_LO];
-        block_off = p.offset[blockIdx.x];
-    }
+    uint32_t off;
+    resolve_row(p, L, k, sm, T, off);
+    if (tid == (int)blockIdx.x) s_off = off;
+    __syncthreads();
+    const uint32_t block_off = s_off;
 
     uint32_t mask = 0u;
 #pragma unroll
@@ -428,6 +529,81 @@ __global__ __launch_bounds__(kSelThreads) void emit_kernel(const float* s_all, i
                 if (scores_out) scores_out[r * k + pos] = val[i];
             }
             ++pos;
+        }
+    }
+}
+
+// Many hidden rows (threshold and block offsets come from resolve_kernel): small workgroups as in
+// collect_rows_kernel.  Thread t owns the four-id groups t, t + 256, t + 512, t + 768 of the
+// vocabulary block (16-byte loads, consecutive lanes on consecutive groups), so ascending id order
+// is (group round j, thread, element): one packed prefix sum per two rounds places every id.
+__global__ __launch_bounds__(kRowThreads) void emit_rows_kernel(const float* s_all, int64_t V, int64_t k,
+                                                                uint32_t* scratch, int rows, int32_t* idx_out,
+                                                                float* scores_out) {
+    constexpr int kRounds = kRowEpt / 4;                  // 4
+    static_assert(kRounds == 4, "two packed scans cover four rounds");
+    __shared__ uint32_t s_w[kRowWaves];
+    const int tid = threadIdx.x;
+    const int64_t r = blockIdx.y;
+    const SelLayout L = sel_layout(V, rows);
+    const SelPtrs p = sel_ptrs(scratch, rows, r, L);
+    const float* s = s_all + r * V;
+    const int64_t base = (int64_t)blockIdx.x * L.chunk;
+    const bool aligned = (reinterpret_cast<uintptr_t>(s + base) & 15u) == 0;
+
+    float val[kRounds][4];
+#pragma unroll
+    for (int j = 0; j < kRounds; ++j) {
+        const int64_t v0 = base + 4 * ((int64_t)j * kRowThreads + tid);
+        if (aligned && v0 + 3 < V) {
+            const f32x4_t q = *reinterpret_cast<const f32x4_t*>(s + v0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) val[j][e] = q[e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) val[j][e] = (v0 + e < V) ? s[v0 + e] : 0.0f;
+        }
+    }
+    const uint64_t T = ((uint64_t)p.state[ST_T_HI] << 32) | p.state[ST_T_LO];
+    const uint32_t block_off = p.offset[blockIdx.x];
+
+    uint32_t mask[kRounds];
+#pragma unroll
+    for (int j = 0; j < kRounds; ++j) {
+        const int64_t v0 = base + 4 * ((int64_t)j * kRowThreads + tid);
+        mask[j] = 0u;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (v0 + e < V && key64(f32_to_ord(val[j][e]), (uint32_t)(v0 + e)) >= T) mask[j] |= 1u << e;
+    }
+    const uint32_t c01 = (uint32_t)__popc(mask[0]) | ((uint32_t)__popc(mask[1]) << 16);
+    const uint32_t c23 = (uint32_t)__popc(mask[2]) | ((uint32_t)__popc(mask[3]) << 16);
+    const uint32_t pre01 = block_prefix_exclusive<kRowWaves>(c01, s_w);
+    uint32_t tot01 = 0u;
+    for (int w = 0; w < kRowWaves; ++w) tot01 += s_w[w];
+    const uint32_t pre23 = block_prefix_exclusive<kRowWaves>(c23, s_w);      // its first barrier: all have read s_w
+    uint32_t tot23 = 0u;
+    for (int w = 0; w < kRowWaves; ++w) tot23 += s_w[w];
+    uint32_t pos[kRounds];
+    pos[0] = block_off + (pre01 & 0xffffu);
+    pos[1] = block_off + (tot01 & 0xffffu) + (pre01 >> 16);
+    pos[2] = block_off + (tot01 & 0xffffu) + (tot01 >> 16) + (pre23 & 0xffffu);
+    pos[3] = block_off + (tot01 & 0xffffu) + (tot01 >> 16) + (tot23 & 0xffffu) + (pre23 >> 16);
+
+    int32_t* out = idx_out + r * k;
+#pragma unroll
+    for (int j = 0; j < kRounds; ++j) {
+        const int64_t v0 = base + 4 * ((int64_t)j * kRowThreads + tid);
+        uint32_t q = pos[j];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (mask[j] & (1u << e)) {
+                if (q < (uint32_t)k) {                    // always true for a consistent threshold
+                    out[q] = (int32_t)(v0 + e);
+                    if (scores_out) scores_out[r * k + q] = val[j][e];
+                }
+                ++q;
+            }
         }
     }
 }
@@ -460,7 +636,7 @@ hipError_t launch_hist(const float* s, int64_t V, int64_t k, int rows, uint32_t*
     DeviceInfo di;
     hipError_t e = device_info(&di);
     if (e != hipSuccess) return e;
-    int64_t bx = (V + kScoreThreads * 4 - 1) / (kScoreThreads * 4);
+    int64_t bx = (V + kScoreThreads * 16 - 1) / (kScoreThreads * 16);
     int64_t cap = ((int64_t)di.cus * 2 + rows - 1) / rows;
     if (cap < 1) cap = 1;
     if (bx > cap) bx = cap;
@@ -471,16 +647,20 @@ hipError_t launch_hist(const float* s, int64_t V, int64_t k, int rows, uint32_t*
 
 hipError_t launch_topk_of_scores(const RadixArgs& a, hipStream_t stream) {
     const SelLayout L = sel_layout(a.V, a.rows);
-    const dim3 grid((unsigned)L.nb, (unsigned)a.rows), block(kSelThreads);
-    hipLaunchKernelGGL(collect_kernel, grid, block, 0, stream, a.s, a.V, a.k, a.scratch, a.rows);
+    const dim3 grid((unsigned)L.nb, (unsigned)a.rows);
     if (a.rows <= 4) {
-        hipLaunchKernelGGL(emit_kernel<true>, grid, block, 0, stream, a.s, a.V, a.k, a.scratch, a.rows, a.idx_out,
-                           a.scores_out);
+        hipLaunchKernelGGL(collect_kernel, grid, dim3(kSelThreads), 0, stream, a.s, a.V, a.k, a.scratch, a.rows);
+        hipLaunchKernelGGL(emit_kernel, grid, dim3(kSelThreads), 0, stream, a.s, a.V, a.k, a.scratch, a.rows,
+                           a.idx_out, a.scores_out);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(resolve_kernel, dim3((unsigned)a.rows), block, 0, stream, a.V, a.k, a.scratch, a.rows);
-    hipLaunchKernelGGL(emit_kernel<false>, grid, block, 0, stream, a.s, a.V, a.k, a.scratch, a.rows, a.idx_out,
-                       a.scores_out);
+    hipLaunchKernelGGL(locate_kernel, dim3((unsigned)a.rows), dim3(kSelThreads), 0, stream, a.V, a.k, a.scratch,
+                       a.rows);
+    hipLaunchKernelGGL(collect_rows_kernel, grid, dim3(kRowThreads), 0, stream, a.s, a.V, a.scratch, a.rows);
+    hipLaunchKernelGGL(resolve_kernel, dim3((unsigned)a.rows), dim3(kSelThreads), 0, stream, a.V, a.k, a.scratch,
+                       a.rows);
+    hipLaunchKernelGGL(emit_rows_kernel, grid, dim3(kRowThreads), 0, stream, a.s, a.V, a.k, a.scratch, a.rows,
+                       a.idx_out, a.scores_out);
     return hipGetLastError();
 }
 

@@ -49,6 +49,10 @@ hipError_t launch_materialize_rows(const char* M, int64_t m_row_bytes, const int
 // the same product on the matrix cores, for several rows of x sharing one set of rows of M
 bool skinny_mfma_supported(int dt, const GemvArgs& a);
 hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream);
+// a batch of rows of x against few rows of M: reduction split over the wavefronts of a workgroup;
+// also supports out_bf16 and zero_ptr
+bool ksplit_rows_supported(int dt, const GemvArgs& a);
+hipError_t launch_ksplit_rows(const GemvArgs& a, hipStream_t stream);
 // more than 64 rows of x: LDS-tiled product (launch_skinny_mfma forwards to it)
 hipError_t launch_tile_mfma(const GemvArgs& a, hipStream_t stream);
 
