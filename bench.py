@@ -48,7 +48,40 @@ def parse_args():
     p.add_argument("--counter-run", action="store_true",
                    help="for rocprofv3 --pmc: a few eager (ungraphed) steps plus 1 GiB reference copies, "
                         "no timing, no JSON line")
+    p.add_argument("--trace-config5", action="store_true",
+                   help="for rocprofv3 --kernel-trace: three eager passes of config 5 (select, draft step, dense), "
+                        "no timing, no JSON line")
     return p.parse_args()
+
+
+def config5_setup(sv, torch, np, dev):
+    """Config 5 (512 hidden rows, selector d' = 256, k = 8192, top-10) resident on the device; returns the
+    config and closures for its three stages plus the buffer the selection writes."""
+    from workloads import CONFIGS
+
+    def dev_bf16(a):
+        return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+
+    c = CONFIGS[5]
+    U = dev_bf16(c.weights())
+    Wd_np, Wv_np = c.selector()
+    Wd, Wv = dev_bf16(Wd_np), dev_bf16(Wv_np)
+    h = dev_bf16(c.hidden(1)[0])
+    ws = torch.empty(sv.workspace_bytes(sv.SV_OP_SELECT, c.rows, c.d, c.V, c.k, c.d_prime, 0, sv.SV_BF16),
+                     dtype=torch.uint8, device=dev)
+    ws2 = torch.empty(max(1, sv.workspace_bytes(sv.SV_OP_DRAFT_STEP, c.rows, c.d, c.V, c.k, 0, c.kd, sv.SV_BF16)),
+                      dtype=torch.uint8, device=dev)
+    sel = torch.empty((c.rows, c.k), dtype=torch.int32, device=dev)
+    z = torch.empty((c.rows, c.k), dtype=torch.float32, device=dev)
+    tok = torch.empty((c.rows, c.kd), dtype=torch.int32, device=dev)
+    prob = torch.empty((c.rows, c.kd), dtype=torch.float32, device=dev)
+    zd = torch.empty((c.rows, c.V), dtype=torch.float32, device=dev)
+    run_select = lambda: sv.select(h, Wd, Wv, c.k, idx_out=sel, ws=ws)
+    run_step = lambda: sv.draft_step(h, U, sel, c.kd, logits_out=z, tok_out=tok, prob_out=prob, ws=ws2)
+    run_dense = lambda: sv.dense_logits(h, U, out=zd)
+    run_select()                                   # sel holds valid ids before anything gathers with it
+    torch.cuda.synchronize()
+    return c, run_select, run_step, run_dense, sel
 
 
 def other_configs(sv, torch, np, dev, capture, timed_replays):
@@ -120,24 +153,19 @@ def other_configs(sv, torch, np, dev, capture, timed_replays):
 
     # ---- config 5: 512 rows, selector d'=256, k=8192, top-10: select -> logits -> softmax/top-10
     note("config 5: 512 rows with selection")
-    c = CONFIGS[5]
-    U = dev_bf16(c.weights())
-    Wd_np, Wv_np = c.selector()
-    Wd, Wv = dev_bf16(Wd_np), dev_bf16(Wv_np)
-    h = dev_bf16(c.hidden(1)[0])
-    ws = torch.empty(sv.workspace_bytes(sv.SV_OP_SELECT, c.rows, c.d, c.V, c.k, c.d_prime, 0, sv.SV_BF16),
-                     dtype=torch.uint8, device=dev)
-    sel = torch.empty((c.rows, c.k), dtype=torch.int32, device=dev)
-    z = torch.empty((c.rows, c.k), dtype=torch.float32, device=dev)
-    tok = torch.empty((c.rows, c.kd), dtype=torch.int32, device=dev)
-    prob = torch.empty((c.rows, c.kd), dtype=torch.float32, device=dev)
-    zd = torch.empty((c.rows, c.V), dtype=torch.float32, device=dev)
-    sel_us = med_us(lambda t: sv.select(h, Wd, Wv, c.k, idx_out=sel, ws=ws), 3, reps=3)
-    step_us = med_us(lambda t: sv.draft_step(h, U, sel, c.kd, logits_out=z, tok_out=tok, prob_out=prob), 3, reps=3)
-    dense_us = med_us(lambda t: sv.dense_logits(h, U, out=zd), 3, reps=3)
+    c, run_select, run_step, run_dense, sel = config5_setup(sv, torch, np, dev)
+    sel_us = med_us(lambda t: run_select(), 3, reps=3)
+    step_us = med_us(lambda t: run_step(), 3, reps=3)
+    dense_us = med_us(lambda t: run_dense(), 3, reps=3)
+    flops = 2.0 * c.rows * c.V * c.d
     out["config5_qwen3_select"] = {"rows": c.rows, "k": c.k, "d_prime": c.d_prime, "select_us": round(sel_us, 1),
                                    "logits_softmax_topk_us": round(step_us, 1),
-                                   "end_to_end_us": round(sel_us + step_us, 1), "dense_us": round(dense_us, 1)}
+                                   "end_to_end_us": round(sel_us + step_us, 1), "dense_us": round(dense_us, 1),
+                                   "dense_tflops": round(flops / dense_us / 1e6, 1),
+                                   "dense_frac_mfma_peak": round(flops / (dense_us * 1e-6) / 2.5e15, 3),
+                                   "union_of_selected_sets": int(torch.unique(sel).numel()),
+                                   "note": "random-init selector: the 512 selected sets are unrelated, their union "
+                                           "is (nearly) the whole vocabulary, so the subset logits cost a dense pass"}
     return out
 
 
@@ -251,6 +279,16 @@ def main():
                 e1.synchronize()
                 out.append(e0.elapsed_time(e1))
         return out
+
+    if args.trace_config5:
+        _, run_select, run_step, run_dense, _ = config5_setup(sv, torch, np, dev)
+        for _ in range(3):
+            run_select()
+            run_step()
+            run_dense()
+        torch.cuda.synchronize()
+        print("config 5 trace run done: 3 x (select, draft step, dense)", flush=True)
+        return
 
     if args.counter_run:
         # hardware counters are read per dispatch; a plain copy of known size calibrates them

@@ -256,8 +256,8 @@ def draft_step(h: torch.Tensor, U: torch.Tensor, idx: torch.Tensor, kd: int,
                prob_out: Optional[torch.Tensor] = None, probs_full_out: Optional[torch.Tensor] = None,
                want_probs: bool = False, ws: Optional[torch.Tensor] = None,
                stream: Optional[torch.cuda.Stream] = None):
-    """specvocab_draft_step: subset logits, subset softmax and top-kd tokens of every row, in one
-    launch where the shape allows. Returns (logits [rows x k], tok [rows x kd], prob [rows x kd],
+    """specvocab_draft_step: subset logits, then subset softmax and top-kd tokens of every row,
+    enqueued back to back. Returns (logits [rows x k], tok [rows x kd], prob [rows x kd],
     q_K [rows x k] or None)."""
     rows, d, ldh = _mat(h, "h")
     V, d2, ldu = _mat(U, "U")
