@@ -297,18 +297,19 @@ hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream) {
     DeviceInfo di;
     hipError_t e = device_info(&di);
     if (e != hipSuccess) return e;
-    // wide workgroups share one x slice among more rows of M; small problems need more workgroups
-    const bool wide = a.n_items >= (int64_t)di.cus * 2 * 128;
-    // few items and at most 32 hidden rows: split the reduction over the wavefronts of a workgroup
-    const bool ksplit = a.n_items <= (int64_t)di.cus * 64 && a.rows <= 32 && a.chunks >= 8 * (kKC / 8);
-    for (int row0 = 0; row0 < a.rows; row0 += 64) {
-        const int nrows = a.rows - row0 < 64 ? a.rows - row0 : 64;
-        if (ksplit) e = nrows <= 16 ? launch_ksplit<1>(a, row0, 1, stream) : launch_ksplit<2>(a, row0, 1, stream);
-        else if (!wide) e = launch_w<2>(a, row0, nrows, stream);
-        else e = nrows <= 32 ? launch_w<4>(a, row0, nrows, stream) : launch_w<8>(a, row0, nrows, stream);
-        if (e != hipSuccess) return e;
+    // few items: split the reduction over the wavefronts of a workgroup, 32 hidden rows per workgroup row
+    // (every workgroup reads its hidden rows from L2 itself, so two row groups pay off for fewer items)
+    if (a.n_items <= (int64_t)di.cus * (a.rows > 32 ? 32 : 64) && a.chunks >= 8 * (kKC / 8)) {
+        if (a.rows <= 16) return launch_ksplit<1>(a, 0, 1, stream);
+        return launch_ksplit<2>(a, 0, (a.rows + 31) / 32, stream);
     }
-    return hipSuccess;
+    // Wide workgroups share one x slice among more rows of M; small problems need more workgroups.
+    // But only a workgroup with at least 128 threads per 16 hidden rows stages the x slice behind the
+    // multiplications (four 16-byte pieces per thread), and that matters more than the workgroup count.
+    const bool wide = a.n_items >= (int64_t)di.cus * 2 * 128;
+    if (a.rows > 32) return launch_w<8>(a, 0, a.rows, stream);
+    if (a.rows > 16 || wide) return launch_w<4>(a, 0, a.rows, stream);
+    return launch_w<2>(a, 0, a.rows, stream);
 }
 
 }  // namespace sv

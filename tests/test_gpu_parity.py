@@ -52,6 +52,8 @@ LOGIT_SHAPES = [
     ("bf16", 33, 3840, 2500, 2500, "per_row"),   # every row asks for the whole vocabulary
     ("bf16", 64, 1024, 9000, 77, "per_step"),    # 64 rows, one shared set
     ("bf16", 17, 4096, 1500, 1500, "per_step"),
+    ("bf16", 60, 2048, 20000, 9000, "per_step"), # 60 rows, few items, long rows: reduction split, two row groups
+    ("bf16", 40, 2048, 40000, 20000, "per_step"),# mid-size shared set: widest skinny workgroups
     ("bf16", 65, 1024, 3000, 700, "per_step"),   # more than 64 rows: LDS-tiled matrix-core kernel, ragged tiles
     ("bf16", 130, 200, 1111, 1111, "per_step"),  # three row tiles (last one 2 rows), 25 units: ragged last slice
     ("bf16", 200, 4096, 2000, 129, "per_step"),  # one item tile plus one item
