@@ -160,6 +160,17 @@ int specvocab_indexed_head_naive(const void* h, int64_t rows, int64_t d, int64_t
                                  float* logits_out,
                                  void* ws, size_t ws_bytes, void* stream);
 
+/* Static-vocabulary mode (the fixed sub-vocabularies the paper compares against: Section 2 "Static
+ * sub-vocabularies", the 32K-token baselines of Section 4): packs U' = U[idx, :] into a dense matrix
+ * once, when the static vocabulary is chosen,
+ *     U_packed[j, :] = U[idx[j], :]            j < k
+ * after which every draft step is specvocab_dense_logits over U_packed (V = k) followed by
+ * specvocab_draft_topk with the same idx as the token ids (SV_IDX_PER_STEP).
+ * idx: device [k] int32, entries in [0, V) (caller's contract).  U_packed: device [k x d] in `dt`, row
+ * stride d, 16-byte aligned, written completely; it must not overlap U. */
+int specvocab_pack_rows(const void* U, int64_t V, int64_t d, int64_t ldu, int dt,
+                        const int32_t* idx, int64_t k, void* U_packed, void* stream);
+
 /* Section 3.1, the full-vocabulary baseline:  logits_out[r, v] = < U[v, :], h[r, :] >.
  * logits_out: device [rows x V] float32. */
 int specvocab_dense_logits(const void* h, int64_t rows, int64_t d, int64_t ldh,

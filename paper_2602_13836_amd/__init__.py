@@ -31,6 +31,7 @@ EXPORTS = (
     "specvocab_draft_topk",
     "specvocab_draft_step",
     "specvocab_indexed_head_naive",
+    "specvocab_pack_rows",
     "specvocab_dense_logits",
 )
 
@@ -71,6 +72,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
                                             ctypes.c_size_t, vp]
     lib.specvocab_indexed_head_naive.restype = ci
     lib.specvocab_indexed_head_naive.argtypes = lib.specvocab_subset_logits.argtypes
+    lib.specvocab_pack_rows.restype = ci
+    lib.specvocab_pack_rows.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp, vp]
     lib.specvocab_draft_topk.restype = ci
     lib.specvocab_draft_topk.argtypes = [vp, vp, ci, i64, i64, i64, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.specvocab_draft_step.restype = ci
@@ -221,6 +224,23 @@ def indexed_head_naive(h: torch.Tensor, U: torch.Tensor, idx: torch.Tensor,
                                                        mode, _ptr(out), _ptr(ws),
                                                        0 if ws is None else ws.numel(), _stream(stream)),
            "specvocab_indexed_head_naive")
+    return out
+
+
+def pack_rows(U: torch.Tensor, idx: torch.Tensor, out: Optional[torch.Tensor] = None,
+              stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """specvocab_pack_rows: U' = U[idx, :] as a dense [k x d] matrix (static-vocabulary mode)."""
+    V, d, ldu = _mat(U, "U")
+    dt = _dt(U)
+    if not idx.is_cuda or idx.dtype != torch.int32 or idx.dim() != 1 or not idx.is_contiguous():
+        raise ValueError("idx must be a contiguous [k] int32 GPU tensor")
+    k = idx.shape[0]
+    if out is None:
+        out = torch.empty((k, d), dtype=U.dtype, device=U.device)
+    elif out.shape != (k, d) or out.dtype != U.dtype or not out.is_contiguous() or not out.is_cuda:
+        raise ValueError("out must be a contiguous [k x d] GPU tensor of U's dtype")
+    _check(load_library().specvocab_pack_rows(_ptr(U), V, d, ldu, dt, _ptr(idx), k, _ptr(out), _stream(stream)),
+           "specvocab_pack_rows")
     return out
 
 

@@ -319,6 +319,24 @@ int specvocab_indexed_head_naive(const void* h, int64_t rows, int64_t d, int64_t
     return SV_OK;
 }
 
+int specvocab_pack_rows(const void* U, int64_t V, int64_t d, int64_t ldu, int dt, const int32_t* idx, int64_t k,
+                        void* U_packed, void* stream) {
+    if (!U || !idx || !U_packed) return SV_ERR_NULL;
+    if (!dtype_ok(dt)) return SV_ERR_DTYPE;
+    if (V < 1 || V > kMaxVocab || k < 1 || k > kMaxVocab) return SV_ERR_SHAPE;
+    int st = check_row(d, ldu, dt);
+    if (st != SV_OK) return st;
+    if (!aligned16(U) || !aligned16(U_packed)) return SV_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    st = validate_indices(idx, k, V, s);
+    if (st != SV_OK) return st;
+    const int es = esize_of(dt);
+    if (sv::launch_materialize_rows(static_cast<const char*>(U), ldu * es, idx, k, (int)(d * es / 16),
+                                    static_cast<char*>(U_packed), s) != hipSuccess)
+        return SV_ERR_HIP;
+    return SV_OK;
+}
+
 int specvocab_draft_topk(const float* logits, const int32_t* idx, int idx_mode, int64_t rows, int64_t k,
                          int64_t kd, int32_t* tok_out, float* prob_out, float* probs_full_out, void* ws,
                          size_t ws_bytes, void* stream) {

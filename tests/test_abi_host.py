@@ -101,6 +101,13 @@ def test_dense_select_topk_reject_bad_arguments(lib):
     assert n(A, 1, 256, 256, A, 1000, 256, 1, None, 100, 0, A, A, 1 << 30, None) == 1
     assert sv.workspace_bytes(sv.SV_OP_INDEXED_HEAD_NAIVE, 2, 4096, 128256, 8192) == 2 * 8192 * 4096 * 2
 
+    pk = lib.specvocab_pack_rows
+    assert pk(A, 1000, 256, 256, 1, None, 10, A, None) == 1
+    assert pk(A, 1000, 256, 256, 1, A, 0, A, None) == 2
+    assert pk(A, 1000, 256, 256, 7, A, 10, A, None) == 3
+    assert pk(A, 1000, 252, 256, 1, A, 10, A, None) == 6                                   # d % 8
+    assert pk(A, 1000, 256, 256, 1, A, 10, MIS, None) == 4
+
     f = lib.specvocab_draft_step
     assert f(A, 1, 256, 256, A, 1000, 256, 1, A, 100, 0, 10, None, A, A, None, None, 0, None) == 1   # no logits_out
     assert f(A, 1, 256, 256, A, 1000, 256, 1, A, 100, 0, 101, A, A, A, None, None, 0, None) == 2     # kd > k

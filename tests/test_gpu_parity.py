@@ -131,6 +131,25 @@ def test_naive_indexed_head_comparator(dtype, rows, d, V, k, mode):
     assert_logits_close(zn, sv.subset_logits(th, tU, tidx).cpu().numpy().astype(np.float64), dtype, "naive vs fused")
 
 
+@pytest.mark.parametrize("dtype,d,V,k", [("bf16", 1024, 5000, 1300), ("f32", 264, 900, 77), ("bf16", 8200, 300, 300)])
+def test_static_vocabulary_mode(dtype, d, V, k):
+    """pack_rows once, then dense logits over the packed matrix + top-kd with the static ids: the same
+    tokens and probabilities as the gathered path over the same set."""
+    say(f"static vocabulary {dtype} d={d} V={V} k={k}")
+    rng = np.random.default_rng(d + k)
+    U, h = rand(rng, (V, d), 0.02, dtype), rand(rng, (3, d), 1.0, dtype)
+    idx = np.sort(rng.permutation(V)[:k]).astype(np.int32)
+    tU, th, tidx = to_dev(U), to_dev(h), torch.from_numpy(idx).to(DEV)
+    Up = sv.pack_rows(tU, tidx)
+    assert torch.equal(Up, tU[tidx.long()])                  # a byte-exact copy of the chosen rows
+    z = sv.dense_logits(th, Up)
+    assert_logits_close(z.cpu().numpy(), oracle.subset_logits(h, U, idx), dtype, "logits over the packed matrix")
+    tok, prob, _ = sv.draft_topk(z, tidx, 10)
+    tok_ref, prob_ref = oracle.softmax_topk(z.cpu().numpy(), idx, 10)
+    assert np.array_equal(tok.cpu().numpy(), tok_ref)
+    np.testing.assert_allclose(prob.cpu().numpy(), prob_ref, rtol=2e-5, atol=1e-9)
+
+
 def test_debug_mode_rejects_out_of_range_indices(monkeypatch):
     """SPECVOCAB_VALIDATE=1: a bad index list is reported on the host and nothing is launched."""
     say("debug-mode index validation")
