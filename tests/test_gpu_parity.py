@@ -374,6 +374,33 @@ def test_select_ties_go_to_smaller_ids(rows):
     assert np.array_equal(idx.cpu().numpy(), np.tile(np.arange(4321, dtype=np.int32), (rows, 1)))
 
 
+def test_k_varies_from_step_to_step():
+    """Section 3.3 Step 2 allows k to change per decoding step: k is a call argument, and buffers and
+    workspace sized once for the largest k serve every step."""
+    say("k varies per step")
+    rng = np.random.default_rng(79)
+    d, dp, V, kmax = 512, 64, 6000, 2048
+    U, Wd, Wv = rand(rng, (V, d), 0.02, "bf16"), rand(rng, (dp, d), 0.05, "bf16"), rand(rng, (V, dp), 0.05, "bf16")
+    tU, tWd, tWv = to_dev(U), to_dev(Wd), to_dev(Wv)
+    ws = torch.empty(sv.workspace_bytes(sv.SV_OP_SELECT, 1, d, V, kmax, dp, 0, sv.SV_BF16), dtype=torch.uint8,
+                     device=DEV)
+    sel_buf = torch.empty(kmax, dtype=torch.int32, device=DEV)
+    z_buf = torch.empty(kmax, dtype=torch.float32, device=DEV)
+    for step, k in enumerate((2048, 300, 1, 1024, 17)):
+        h = rand(rng, (1, d), 1.0, "bf16")
+        th = to_dev(h)
+        sel, z = sel_buf[:k].view(1, k), z_buf[:k].view(1, k)
+        sv.select(th, tWd, tWv, k, idx_out=sel, ws=ws)
+        _, tok, prob, _ = sv.draft_step(th, tU, sel, min(10, k), logits_out=z)
+        ref_idx, _, s_ref, _ = oracle.select(h, Wd, Wv, k, full=True)
+        check_selected_set(sel.cpu().numpy()[0], s_ref[0], ref_idx[0], k, "bf16")
+        z_ref = oracle.subset_logits(h, U, sel.cpu().numpy())
+        assert_logits_close(z.cpu().numpy(), z_ref, "bf16", f"step {step} k={k}")
+        tok_ref, prob_ref = oracle.softmax_topk(z.cpu().numpy(), sel.cpu().numpy(), min(10, k))
+        assert np.array_equal(tok.cpu().numpy(), tok_ref)
+        np.testing.assert_allclose(prob.cpu().numpy(), prob_ref, rtol=2e-5, atol=1e-9)
+
+
 def test_exact_selector_reduces_to_dense_topk():
     """d' = d, W_down = I, W_vocab = U: select must return the top-k of the true logits."""
     say("select with the exact selector")
