@@ -95,6 +95,7 @@ def test_dense_select_topk_reject_bad_arguments(lib):
     assert s(A, 1, 256, 256, A, 32, A, 1000, 1, 10, A, None, A, 16, None) == 5              # too small
     assert s(A, 1, 256, 256, A, 30, A, 1000, 1, 10, A, None, A, 1 << 30, None) == 6         # d' % 8
     assert s(A, 1, 256, 256, A, 32, A, 1000, 4, 10, A, None, A, 1 << 30, None) == 3
+    assert s(A, 1, 256, 256, A, 32, A, 4194305, 1, 10, A, None, A, 1 << 40, None) == 6      # V above the limit
 
     n = lib.specvocab_indexed_head_naive
     assert n(A, 1, 256, 256, A, 1000, 256, 1, A, 100, 0, A, None, 0, None) == 5          # needs its workspace

@@ -374,6 +374,22 @@ def test_select_ties_go_to_smaller_ids(rows):
     assert np.array_equal(idx.cpu().numpy(), np.tile(np.arange(4321, dtype=np.int32), (rows, 1)))
 
 
+@pytest.mark.parametrize("rows", [1, 5])
+def test_select_at_the_largest_vocabulary(rows):
+    """V = 4194304, the most specvocab_select accepts: 1024 vocabulary blocks per row, both forms of the
+    tail kernels."""
+    say(f"select V=4194304 rows={rows}")
+    rng = np.random.default_rng(80 + rows)
+    d, dp, V, k = 16, 8, 4194304, 1000
+    h, Wd, Wv = rand(rng, (rows, d), 1.0, "bf16"), rand(rng, (dp, d), 0.3, "bf16"), rand(rng, (V, dp), 0.3, "bf16")
+    idx, sc = sv.select(to_dev(h), to_dev(Wd), to_dev(Wv), k, want_scores=True)
+    idx, sc = idx.cpu().numpy(), sc.cpu().numpy()
+    ref_idx, _, s_ref, _ = oracle.select(h, Wd, Wv, k, full=True)
+    for r in range(rows):
+        check_selected_set(idx[r], s_ref[r], ref_idx[r], k, "bf16")
+        assert_logits_close(sc[r], s_ref[r, idx[r]], "bf16", "scores at the selected ids")
+
+
 def test_k_varies_from_step_to_step():
     """Section 3.3 Step 2 allows k to change per decoding step: k is a call argument, and buffers and
     workspace sized once for the largest k serve every step."""
