@@ -393,11 +393,23 @@ def main():
         timed_replays(g_coldg, 1)
         cgr = sorted(timed_replays(g_coldg, 5))
         coldg_us = cgr[len(cgr) // 2] * 1e3 / K
+        # the same number of bytes as ONE contiguous block of k rows (no index list, the same kernel), cold:
+        # what a burst of this size can reach on this machine at all
+        nwin = c.V // c.k
+        zc = torch.empty((c.rows, c.k), dtype=torch.float32, device=dev)
+        g_coldc = capture(lambda t: sv.dense_logits(
+            h[t % nd], copies[t % ncopy][((t // ncopy) % nwin) * c.k:((t // ncopy) % nwin + 1) * c.k], out=zc), K)
+        timed_replays(g_coldc, 1)
+        ccr = sorted(timed_replays(g_coldc, 5))
+        coldc_us = ccr[len(ccr) // 2] * 1e3 / K
         result["cold"] = {"copies_of_U": ncopy, "us_per_step": round(cold_us, 3),
                           "gather_kernel_us": round(coldg_us, 3),
                           "gather_GBps": round(gather_bytes / (coldg_us * 1e-6) / 1e9, 1),
-                          "gather_frac_hbm_peak": round(gather_bytes / (coldg_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
-        del g_cold, g_coldg, copies
+                          "gather_frac_hbm_peak": round(gather_bytes / (coldg_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                          "contiguous_block_of_k_rows_us": round(coldc_us, 3),
+                          "note": "contiguous_block_of_k_rows_us: the same kernel streaming k consecutive rows "
+                                  "(no index list), also cold -- the ceiling for a burst of this size"}
+        del g_cold, g_coldg, g_coldc, copies
         torch.cuda.empty_cache()
 
         # ---------------- the selector at the same shape, and the whole step including it
