@@ -1,10 +1,13 @@
 // Candidate-vocabulary selection (Section 3.3): approximate logits s = W_vocab h' (Step 1) and
 // k_t = top-k(s_t, k) (Step 2), exact, ids in ascending order, ties to the smaller id.
 //
-// Three launches after the down-projection (five with more than four hidden rows).  Every step that needs a
-// result of the whole row sits behind a kernel boundary: on this multi-die part a kernel boundary is the cheapest device-wide
-// synchronisation (a device-scope release fence writes back a whole L2, and atomics on one address
-// serialise at ~50 ns each), so there is no "last block" hand-over and no contended counter.
+// Three launches after the down-projection (with more than four hidden rows: a histogram pass over
+// scores that a matrix-core kernel produced, then four).  Every step that needs a result of the whole
+// row sits behind a kernel boundary: on this multi-die part a kernel boundary is the cheapest
+// device-wide synchronisation (a device-scope release fence writes back a whole L2, and atomics on one
+// address serialise at ~50 ns each), so there is no "last block" hand-over and no contended counter.
+// Up to four hidden rows the kernels are shaped for latency (few launches, redundant work per block);
+// beyond that for throughput (small workgroups, 16-byte loads, the row-wide results computed once).
 //   scores_hist   streams W_vocab once.  A selector row is short (d' = d/16 .. d/8: a few hundred
 //                 bytes), so a wavefront is split into groups of G lanes, one row per group, and
 //                 every load instruction still covers 1 KiB of consecutive memory.  Each score is
