@@ -58,6 +58,8 @@ LOGIT_SHAPES = [
     ("bf16", 130, 200, 1111, 1111, "per_step"),  # three row tiles (last one 2 rows), 25 units: ragged last slice
     ("bf16", 200, 4096, 2000, 129, "per_step"),  # one item tile plus one item
     ("bf16", 150, 512, 5000, 900, "per_row"),    # union of 150 sets on the tiled kernel
+    ("bf16", 70, 8, 300, 300, "per_step"),       # one 16-byte unit per row: a single, ragged reduction slice
+    ("bf16", 300, 64, 100, 1, "per_step"),       # one item, three row tiles
     ("bf16", 256, 1024, 1500, 1500, "per_step"), # 256 x 256 tiles, hand-ordered main loop
     ("bf16", 300, 264, 700, 300, "per_step"),    # 128-row tiles with the hand-ordered loop, ragged last slice
     ("bf16", 500, 1000, 2100, 2100, "per_step"), # two 256-row tiles (last one 244 rows), odd slice count
