@@ -145,7 +145,6 @@ const char* specvocab_status_string(int status) {
 int specvocab_workspace_bytes(int op, int64_t rows, int64_t d, int64_t V, int64_t k, int64_t d_prime,
                               int64_t kd, int dt, int idx_mode, size_t* bytes_out) {
     (void)kd;
-    (void)idx_mode;
     if (!bytes_out) return SV_ERR_NULL;
     *bytes_out = 0;
     switch (op) {

@@ -272,6 +272,7 @@ hipError_t launch_tile(const GemvArgs& a, hipStream_t stream) {
     const int64_t IT = (a.n_items + TN - 1) / TN;
     const int64_t groups = (IT + kXcds - 1) / kXcds;            // item tiles per XCD, rounded up
     const int64_t bx = groups * RT * kXcds;
+    if (bx > 0x7fffffffLL) return hipErrorInvalidValue;         // more tiles than a grid dimension holds
     const size_t lds = (size_t)2 * (TM + TN) * kRowB;
     static bool configured = false;                             // more than 64 KiB of LDS needs an explicit opt-in
     if (!configured && lds > 64 * 1024) {
