@@ -36,6 +36,8 @@
  *           With SV_BF16 storage the intermediate h' of the selector is rounded to bfloat16
  *           (round-to-nearest-even) before the second projection; with SV_F32 it stays float32.
  * Ties.     Wherever "largest" decides, equal values are ordered by smaller token id first.
+ * Threads.  Entry points may be called from several host threads; the library keeps no per-call
+ *           state on the host (only idempotent per-process caches of device attributes).
  */
 #ifndef SPECVOCAB_H
 #define SPECVOCAB_H
