@@ -270,12 +270,16 @@ def test_draft_step_sees_fresh_logits_in_a_reused_buffer():
         assert torch.allclose(prob, prob2, rtol=1e-5, atol=1e-9), t
 
 
-def test_whole_step_replays_from_a_graph():
+@pytest.mark.parametrize("rows,d,dp,V,k", [
+    (2, 1024, 64, 30000, 4096),      # the latency-shaped kernels of a chain step
+    (72, 2048, 64, 9000, 600),       # a batch: matrix-core down-projection and scores, many-row tail, union path
+])
+def test_whole_step_replays_from_a_graph(rows, d, dp, V, k):
     """select -> draft_step captured once into a HIP graph and replayed with eager work and
     synchronisations in between: every replay must reproduce the eager results."""
-    say("graph capture and replay of select + draft_step")
+    say(f"graph capture and replay of select + draft_step, rows={rows}")
     rng = np.random.default_rng(2024)
-    rows, d, dp, V, k, kd = 2, 1024, 64, 30000, 4096, 10
+    kd = 10
     U = to_dev(rand(rng, (V, d), 0.02, "bf16"))
     Wd = to_dev(rand(rng, (dp, d), 0.05, "bf16"))
     Wv = to_dev(rand(rng, (V, dp), 0.05, "bf16"))
