@@ -44,7 +44,7 @@ def _load():
         lib = ctypes.CDLL(_LIB)
         lib.svo_mac_count.restype = ctypes.c_uint64
         lib.svo_reset_mac_count.restype = None
-        for name in ("svo_dense_logits", "svo_subset_logits", "svo_select", "svo_softmax_topk"):
+        for name in ("svo_dense_logits", "svo_subset_logits", "svo_select", "svo_softmax_topk", "svo_log_softmax"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -203,3 +203,22 @@ def softmax_topk(logits: np.ndarray, idx: np.ndarray, kd: int, full: bool = Fals
     if full:
         return tok, prob, q
     return tok, prob
+
+
+def log_softmax(s: np.ndarray) -> np.ndarray:
+    """Section 3.4: log q_aux = log softmax(s) over the whole vocabulary, row by row, in float64."""
+    s = np.ascontiguousarray(np.atleast_2d(np.asarray(s, dtype=np.float64)))
+    rows, V = s.shape
+    out = np.empty((rows, V), dtype=np.float64)
+    rc = _load().svo_log_softmax(_ptr(s), ctypes.c_int64(rows), ctypes.c_int64(V), _ptr(out))
+    _check(rc, "log_softmax")
+    return out
+
+
+def aux_log_softmax(h: np.ndarray, W_down: np.ndarray, W_vocab: np.ndarray,
+                    hprime_round: Optional[bool] = None, acc: str = "f32") -> np.ndarray:
+    """Section 3.4: log q_aux(x_t | x_<t) = log softmax(W_vocab (W_down h_t)), [rows x V] float64.
+    The scores are those of Section 3.3 Step 1 (same rounding of h' as select)."""
+    _, _, s_full, _ = select(h, W_down, W_vocab, 1, hprime_round=hprime_round, acc=acc, full=True)
+    return log_softmax(s_full)
+

@@ -15,6 +15,8 @@
  *   svo_softmax_topk   Section 3.3: q_K = softmax(z'); draft tokens = the
  *                      top-kd entries of q_K (Appendix, inference
  *                      hyperparameters: Top-k = 10)
+ *   svo_log_softmax    Section 3.4 (training): q_aux = softmax(s_t) over the
+ *                      entire vocabulary, as natural-log probabilities
  *
  * Precision.  The paper does not fix storage or accumulation precision.
  * Inputs are float32 or bfloat16 (bit patterns, widened exactly to float32).
@@ -231,5 +233,24 @@ int svo_softmax_topk(const float* logits, const int32_t* idx, int idx_mode,
         }
     }
     free(order);
+    return SVO_OK;
+}
+
+/* Section 3.4: the vocabulary speculator's own distribution q_aux = softmax(s) over the whole
+ * vocabulary, returned as log-probabilities:
+ *   out[r, v] = s[r, v] - m_r - log( sum_u exp(s[r, u] - m_r) ),  m_r = max_u s[r, u]
+ * s, out: [rows x V] double (s as produced by svo_select's s_full_out). */
+int svo_log_softmax(const double* s, int64_t rows, int64_t V, double* out) {
+    if (!s || !out || rows < 1 || V < 1) return SVO_ERR_ARG;
+    for (int64_t r = 0; r < rows; ++r) {
+        const double* x = s + r * V;
+        double m = x[0];
+        for (int64_t v = 1; v < V; ++v)
+            if (x[v] > m) m = x[v];
+        double denom = 0.0;
+        for (int64_t v = 0; v < V; ++v) denom += exp(x[v] - m);
+        const double lse = m + log(denom);
+        for (int64_t v = 0; v < V; ++v) out[r * V + v] = x[v] - lse;
+    }
     return SVO_OK;
 }

@@ -436,3 +436,66 @@ def test_error_paths():
         oracle.dense_logits(h, U.astype(np.float64))
     with pytest.raises(TypeError):
         oracle.dense_logits(h, np.zeros((6, 4), np.uint16))
+
+
+# --------------------------------------------------------------------------
+# Section 3.4: q_aux = softmax(s) over the entire vocabulary, as log-probabilities
+# --------------------------------------------------------------------------
+def test_log_softmax_closed_form():
+    """s = (0, ln 2, ln 3)  =>  q_aux = (1/6, 2/6, 3/6)."""
+    out = oracle.log_softmax(np.array([[0.0, math.log(2.0), math.log(3.0)]]))
+    want = np.log(np.array([[1.0, 2.0, 3.0]]) / 6.0)
+    np.testing.assert_allclose(out, want, rtol=0, atol=1e-15)
+    # equal scores: the uniform distribution, also where exp(s) itself would overflow
+    out = oracle.log_softmax(np.full((2, 5), 1000.0))
+    np.testing.assert_allclose(out, np.full((2, 5), -math.log(5.0)), rtol=0, atol=1e-12)
+
+
+def test_log_softmax_against_scipy_and_invariants():
+    from scipy.special import log_softmax as scipy_log_softmax, logsumexp
+    rng = np.random.default_rng(34)
+    s = rng.normal(0.0, 3.0, size=(4, 1000))
+    out = oracle.log_softmax(s)
+    np.testing.assert_allclose(out, scipy_log_softmax(s, axis=1), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(logsumexp(out, axis=1), 0.0, atol=1e-12)          # probabilities sum to one
+    np.testing.assert_allclose(oracle.log_softmax(s + 7.25), out, atol=1e-12)     # shift invariance
+    assert np.array_equal(out.argmax(axis=1), s.argmax(axis=1))
+    # differences of log-probabilities are differences of scores
+    np.testing.assert_allclose(out[:, 1:] - out[:, :-1], s[:, 1:] - s[:, :-1], atol=1e-12)
+
+
+def test_q_aux_restricted_to_a_subset_is_the_subset_softmax():
+    """Renormalising q_aux over a subset K gives softmax(s[K]) -- the same function the subset softmax of
+    Section 3.3 computes on logits."""
+    rng = np.random.default_rng(35)
+    s = rng.normal(0.0, 2.0, size=(2, 300)).astype(np.float32)
+    K = np.sort(rng.permutation(300)[:40]).astype(np.int32)
+    logq = oracle.log_softmax(s.astype(np.float64))
+    q_sub = np.exp(logq[:, K])
+    q_sub /= q_sub.sum(axis=1, keepdims=True)
+    _, _, q_K = oracle.softmax_topk(s[:, K], K, 5, full=True)
+    np.testing.assert_allclose(q_sub, q_K, rtol=1e-12, atol=0)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_aux_log_softmax_composes_the_selector_scores(dtype):
+    """log q_aux = log softmax(W_vocab (W_down h)): against numpy float64 on the widened inputs, with h'
+    rounded through bf16 exactly where select rounds it."""
+    rng = np.random.default_rng(36)
+    d, dp, V = 64, 16, 200
+    def draw(shape, scale):
+        a = rng.normal(0.0, scale, size=shape).astype(np.float32)
+        return f32_to_bf16_bits(a) if dtype == "bf16" else a
+    def wide(a):
+        return bf16_bits_to_f32(a).astype(np.float64) if dtype == "bf16" else a.astype(np.float64)
+    h, Wd, Wv = draw((3, d), 1.0), draw((dp, d), 0.2), draw((V, dp), 0.2)
+    hp = wide(h) @ wide(Wd).T
+    if dtype == "bf16":
+        hp = bf16_bits_to_f32(f32_to_bf16_bits(hp.astype(np.float32))).astype(np.float64)
+    s = hp @ wide(Wv).T
+    want = s - s.max(axis=1, keepdims=True)
+    want = want - np.log(np.exp(want).sum(axis=1, keepdims=True))
+    got = oracle.aux_log_softmax(h, Wd, Wv, acc="f64")
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-9)
+    # the float32-accumulated variant stays within accumulation noise of it
+    np.testing.assert_allclose(oracle.aux_log_softmax(h, Wd, Wv), want, rtol=0, atol=2e-5 if dtype == "f32" else 2e-2)
