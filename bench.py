@@ -447,6 +447,14 @@ def main():
         timed_replays(g_sel8, 2)
         result["select"]["select_us_d_prime_512"] = round(sorted(timed_replays(g_sel8, 5))[2] * 1e3 / nsel, 2)
         del g_sel8, Wd8, Wv8, ws8
+        # the training-side distribution of the vocabulary speculator (Section 3.4): log q_aux over all V
+        logq = torch.empty((c.rows, c.V), dtype=torch.float32, device=dev)
+        ws_aux = torch.empty(sv.workspace_bytes(sv.SV_OP_AUX_LOG_SOFTMAX, c.rows, c.d, c.V, 0, c.d_prime, 0,
+                                                sv.SV_BF16), dtype=torch.uint8, device=dev)
+        g_aux = capture(lambda t: sv.aux_log_softmax(h[t % nd], Wd, Wv, out=logq, ws=ws_aux), nsel)
+        timed_replays(g_aux, 2)
+        result["aux_log_softmax_us"] = round(sorted(timed_replays(g_aux, 5))[2] * 1e3 / nsel, 2)
+        del g_aux, logq, ws_aux
 
         # ---------------- the paper's break-even (Section 6, Table 4): SpecVocab wins over a static reduced
         # vocabulary V' when V d'/d + k < |V'|.  Static V' = 32K most frequent tokens (the size the

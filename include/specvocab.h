@@ -75,7 +75,8 @@ typedef enum {
     SV_OP_DRAFT_TOPK = 2,
     SV_OP_DENSE_LOGITS = 3,
     SV_OP_DRAFT_STEP = 4,
-    SV_OP_INDEXED_HEAD_NAIVE = 5
+    SV_OP_INDEXED_HEAD_NAIVE = 5,
+    SV_OP_AUX_LOG_SOFTMAX = 6
 } sv_op;
 
 /* Largest kd the draft top-kd accepts. */
@@ -172,6 +173,17 @@ int specvocab_indexed_head_naive(const void* h, int64_t rows, int64_t d, int64_t
  * stride d, 16-byte aligned, written completely; it must not overlap U. */
 int specvocab_pack_rows(const void* U, int64_t V, int64_t d, int64_t ldu, int dt,
                         const int32_t* idx, int64_t k, void* U_packed, void* stream);
+
+/* Section 3.4 (training side, forward only): the vocabulary speculator's own output distribution over
+ * the ENTIRE vocabulary, q_aux = softmax(s) with s = W_vocab (W_down h) as in specvocab_select, returned
+ * as natural-log probabilities (what a cross-entropy style distillation loss consumes):
+ *     logq_out[r, v] = s[r, v] - log sum_u exp(s[r, u])
+ * Arguments as in specvocab_select; logq_out: device [rows x V] float32.  No limit on V beyond int32. */
+int specvocab_aux_log_softmax(const void* h, int64_t rows, int64_t d, int64_t ldh,
+                              const void* W_down, int64_t d_prime,
+                              const void* W_vocab, int64_t V, int dt,
+                              float* logq_out,
+                              void* ws, size_t ws_bytes, void* stream);
 
 /* Section 3.1, the full-vocabulary baseline:  logits_out[r, v] = < U[v, :], h[r, :] >.
  * logits_out: device [rows x V] float32. */

@@ -20,6 +20,7 @@ SV_F32, SV_BF16 = 0, 1
 SV_IDX_PER_ROW, SV_IDX_PER_STEP = 0, 1
 SV_OP_SELECT, SV_OP_SUBSET_LOGITS, SV_OP_DRAFT_TOPK, SV_OP_DENSE_LOGITS, SV_OP_DRAFT_STEP = 0, 1, 2, 3, 4
 SV_OP_INDEXED_HEAD_NAIVE = 5
+SV_OP_AUX_LOG_SOFTMAX = 6
 MAX_KD = 64
 
 EXPORTS = (
@@ -32,6 +33,7 @@ EXPORTS = (
     "specvocab_draft_step",
     "specvocab_indexed_head_naive",
     "specvocab_pack_rows",
+    "specvocab_aux_log_softmax",
     "specvocab_dense_logits",
 )
 
@@ -72,6 +74,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
                                             ctypes.c_size_t, vp]
     lib.specvocab_indexed_head_naive.restype = ci
     lib.specvocab_indexed_head_naive.argtypes = lib.specvocab_subset_logits.argtypes
+    lib.specvocab_aux_log_softmax.restype = ci
+    lib.specvocab_aux_log_softmax.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, ci, vp, vp, ctypes.c_size_t, vp]
     lib.specvocab_pack_rows.restype = ci
     lib.specvocab_pack_rows.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp, vp]
     lib.specvocab_draft_topk.restype = ci
@@ -224,6 +228,32 @@ def indexed_head_naive(h: torch.Tensor, U: torch.Tensor, idx: torch.Tensor,
                                                        mode, _ptr(out), _ptr(ws),
                                                        0 if ws is None else ws.numel(), _stream(stream)),
            "specvocab_indexed_head_naive")
+    return out
+
+
+def aux_log_softmax(h: torch.Tensor, W_down: torch.Tensor, W_vocab: torch.Tensor,
+                    out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
+                    stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """specvocab_aux_log_softmax: log q_aux = log softmax(W_vocab (W_down h)) over the whole vocabulary,
+    [rows x V] float32."""
+    rows, d, ldh = _mat(h, "h")
+    dp, d2, ldd = _mat(W_down, "W_down")
+    V, dp2, ldv = _mat(W_vocab, "W_vocab")
+    if d2 != d or dp2 != dp or ldd != d or ldv != dp:
+        raise ValueError("W_down must be a dense [d' x d] and W_vocab a dense [V x d']")
+    dt = _dt(h)
+    if _dt(W_down) != dt or _dt(W_vocab) != dt:
+        raise TypeError("h, W_down and W_vocab must share a dtype")
+    if out is None:
+        out = torch.empty((rows, V), dtype=torch.float32, device=h.device)
+    elif out.shape != (rows, V) or out.dtype != torch.float32 or not out.is_contiguous() or not out.is_cuda:
+        raise ValueError("out must be a contiguous [rows x V] float32 GPU tensor")
+    nbytes = workspace_bytes(SV_OP_AUX_LOG_SOFTMAX, rows, d, V, 0, dp, 0, dt)
+    ws = _workspace(nbytes, h.device, ws)
+    _check(load_library().specvocab_aux_log_softmax(_ptr(h), rows, d, ldh, _ptr(W_down), dp, _ptr(W_vocab), V, dt,
+                                                    _ptr(out), _ptr(ws), 0 if ws is None else ws.numel(),
+                                                    _stream(stream)),
+           "specvocab_aux_log_softmax")
     return out
 
 

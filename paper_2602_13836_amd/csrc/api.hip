@@ -110,6 +110,32 @@ size_t gather_ws_bytes(int64_t rows, int64_t d, int64_t V, int64_t k, int dt, in
     return sv::union_path_wanted(dt, g) ? sv::union_ws_bytes(rows, V, k) : 0;
 }
 
+// h'[r, :] = W_down h[r, :] into hp ([rows x d_prime] in the storage dtype; bf16: round to nearest even);
+// optionally clears zero_words words at zero_ptr in the same launch
+int launch_down_projection(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* W_down,
+                           int64_t d_prime, int dt, char* hp, uint32_t* zero_ptr, size_t zero_words,
+                           hipStream_t s) {
+    const int es = esize_of(dt);
+    sv::GemvArgs g{};
+    g.x = static_cast<const char*>(h);
+    g.x_row_bytes = ldh * es;
+    g.M = static_cast<const char*>(W_down);
+    g.m_row_bytes = d * es;
+    g.idx = nullptr;
+    g.idx_row_stride = 0;
+    g.n_items = d_prime;
+    g.chunks = (int)(d * es / 16);
+    g.rows = (int)rows;
+    g.out_f32 = dt == SV_BF16 ? nullptr : reinterpret_cast<float*>(hp);
+    g.out_bf16 = dt == SV_BF16 ? reinterpret_cast<uint16_t*>(hp) : nullptr;
+    g.out_row_stride = d_prime;
+    g.zero_ptr = zero_ptr;
+    g.zero_words = zero_words;
+    if (sv::ksplit_rows_supported(dt, g))              // a batch of rows: W_down read once per 32 of them
+        return sv::launch_ksplit_rows(g, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
+    return sv::launch_gemv(dt, g, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
+}
+
 int check_select_shape(int64_t rows, int64_t d, int64_t V, int64_t k, int64_t d_prime, int dt) {
     if (!dtype_ok(dt)) return SV_ERR_DTYPE;
     if (rows < 1 || rows > kMaxRows || V < 1 || V > kMaxVocab || k < 1 || k > V) return SV_ERR_SHAPE;
@@ -119,6 +145,28 @@ int check_select_shape(int64_t rows, int64_t d, int64_t V, int64_t k, int64_t d_
     if (st != SV_OK) return st;
     if (d > (1 << 24) || d_prime > (1 << 24) || V > sv::select_max_vocab()) return SV_ERR_UNSUPPORTED;
     return SV_OK;
+}
+
+int check_aux_shape(int64_t rows, int64_t d, int64_t V, int64_t d_prime, int dt) {
+    if (!dtype_ok(dt)) return SV_ERR_DTYPE;
+    if (rows < 1 || rows > kMaxRows || V < 1 || V > kMaxVocab) return SV_ERR_SHAPE;
+    int st = check_row(d, d, dt);
+    if (st != SV_OK) return st;
+    st = check_row(d_prime, d_prime, dt);
+    if (st != SV_OK) return st;
+    if (d > (1 << 24) || d_prime > (1 << 24)) return SV_ERR_UNSUPPORTED;
+    return SV_OK;
+}
+
+struct AuxWs {
+    size_t hp_off, partial_off, total;
+};
+AuxWs aux_ws(int64_t rows, int64_t V, int64_t d_prime, int dt) {
+    AuxWs w;
+    w.hp_off = 0;
+    w.partial_off = round256((size_t)rows * (size_t)d_prime * (size_t)esize_of(dt));
+    w.total = w.partial_off + round256(sv::log_softmax_ws_floats(rows, V) * sizeof(float));
+    return w;
 }
 
 }  // namespace
@@ -167,6 +215,12 @@ int specvocab_workspace_bytes(int op, int64_t rows, int64_t d, int64_t V, int64_
             *bytes_out = round256((size_t)sets * (size_t)k * (size_t)d * (size_t)esize_of(dt));
             return SV_OK;
         }
+        case SV_OP_AUX_LOG_SOFTMAX: {
+            const int st = check_aux_shape(rows, d, V, d_prime, dt);
+            if (st != SV_OK) return st;
+            *bytes_out = aux_ws(rows, V, d_prime, dt).total;
+            return SV_OK;
+        }
         case SV_OP_DRAFT_TOPK:
         case SV_OP_DENSE_LOGITS:
             return SV_OK;
@@ -194,27 +248,12 @@ int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh, const 
     float* scores = reinterpret_cast<float*>(base + w.s_off);
     uint32_t* radix = reinterpret_cast<uint32_t*>(base + w.radix_off);
 
-    // Step 1a: h' = W_down h, stored in the storage dtype (bf16: rounded to nearest even)
-    sv::GemvArgs g{};
-    g.x = static_cast<const char*>(h);
-    g.x_row_bytes = ldh * es;
-    g.M = static_cast<const char*>(W_down);
-    g.m_row_bytes = d * es;
-    g.idx = nullptr;
-    g.idx_row_stride = 0;
-    g.n_items = d_prime;
-    g.chunks = (int)(d * es / 16);
-    g.rows = (int)rows;
-    g.out_f32 = dt == SV_BF16 ? nullptr : reinterpret_cast<float*>(hp);
-    g.out_bf16 = dt == SV_BF16 ? reinterpret_cast<uint16_t*>(hp) : nullptr;
-    g.out_row_stride = d_prime;
-    g.zero_ptr = radix;                      // the selection's counters and histogram start at zero
-    sv::select_zero_range(rows, V, &g.zero_words);
-    if (sv::ksplit_rows_supported(dt, g)) {           // a batch of rows: W_down read once per 32 of them
-        if (sv::launch_ksplit_rows(g, s) != hipSuccess) return SV_ERR_HIP;
-    } else if (sv::launch_gemv(dt, g, s) != hipSuccess) {
+    // Step 1a: h' = W_down h, stored in the storage dtype (bf16: rounded to nearest even); the same launch
+    // clears the selection's counters and histogram
+    size_t zero_words = 0;
+    sv::select_zero_range(rows, V, &zero_words);
+    if (launch_down_projection(h, rows, d, ldh, W_down, d_prime, dt, hp, radix, zero_words, s) != SV_OK)
         return SV_ERR_HIP;
-    }
 
     // Step 1b: s = W_vocab h'.  One hidden row: a bandwidth-bound stream over W_vocab fused with the
     // first histogram pass of the selection.  Several rows: a real matrix product -> matrix cores.
@@ -257,6 +296,41 @@ int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh, const 
     ra.scores_out = scores_out;
     ra.scratch = radix;
     if (sv::launch_topk_of_scores(ra, s) != hipSuccess) return SV_ERR_HIP;
+    return SV_OK;
+}
+
+int specvocab_aux_log_softmax(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* W_down,
+                              int64_t d_prime, const void* W_vocab, int64_t V, int dt, float* logq_out, void* ws,
+                              size_t ws_bytes, void* stream) {
+    if (!h || !W_down || !W_vocab || !logq_out) return SV_ERR_NULL;
+    int st = check_aux_shape(rows, d, V, d_prime, dt);
+    if (st != SV_OK) return st;
+    st = check_row(d, ldh, dt);
+    if (st != SV_OK) return st;
+    if (!aligned16(h) || !aligned16(W_down) || !aligned16(W_vocab) || !aligned16(ws)) return SV_ERR_ALIGN;
+    const AuxWs w = aux_ws(rows, V, d_prime, dt);
+    if (!ws || ws_bytes < w.total) return SV_ERR_WORKSPACE;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int es = esize_of(dt);
+    char* hp = static_cast<char*>(ws) + w.hp_off;
+    float* partial = reinterpret_cast<float*>(static_cast<char*>(ws) + w.partial_off);
+    st = launch_down_projection(h, rows, d, ldh, W_down, d_prime, dt, hp, nullptr, 0, s);
+    if (st != SV_OK) return st;
+    // s = W_vocab h' straight into the output, then normalised in place
+    sv::GemvArgs g{};
+    g.x = hp;
+    g.x_row_bytes = d_prime * es;
+    g.M = static_cast<const char*>(W_vocab);
+    g.m_row_bytes = d_prime * es;
+    g.n_items = V;
+    g.chunks = (int)(d_prime * es / 16);
+    g.rows = (int)rows;
+    g.out_f32 = logq_out;
+    g.out_row_stride = V;
+    st = launch_rows_product(dt, g, V, nullptr, 0, s);
+    if (st != SV_OK) return st;
+    if (sv::launch_log_softmax_rows(logq_out, V, (int)rows, partial, s) != hipSuccess) return SV_ERR_HIP;
     return SV_OK;
 }
 

@@ -56,6 +56,10 @@ hipError_t launch_ksplit_rows(const GemvArgs& a, hipStream_t stream);
 // more than 64 rows of x: LDS-tiled product (launch_skinny_mfma forwards to it)
 hipError_t launch_tile_mfma(const GemvArgs& a, hipStream_t stream);
 
+// in place: s[r, :] <- log softmax(s[r, :]) for rows of V float32 scores; partial: log_softmax_ws_floats floats
+size_t log_softmax_ws_floats(int64_t rows, int64_t V);
+hipError_t launch_log_softmax_rows(float* s, int64_t V, int rows, float* partial, hipStream_t stream);
+
 // Per-row index sets for several hidden rows (a draft tree): the union of the sets is formed on the
 // device, every row of M in the union is read once and multiplied with all hidden rows on the matrix
 // cores, and each (row, j) picks its logit out of that product.

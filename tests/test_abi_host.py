@@ -102,6 +102,13 @@ def test_dense_select_topk_reject_bad_arguments(lib):
     assert n(A, 1, 256, 256, A, 1000, 256, 1, None, 100, 0, A, A, 1 << 30, None) == 1
     assert sv.workspace_bytes(sv.SV_OP_INDEXED_HEAD_NAIVE, 2, 4096, 128256, 8192) == 2 * 8192 * 4096 * 2
 
+    q = lib.specvocab_aux_log_softmax
+    assert q(A, 1, 256, 256, A, 32, A, 1000, 1, None, A, 1 << 30, None) == 1
+    assert q(A, 1, 256, 256, A, 32, A, 1000, 1, A, None, 0, None) == 5
+    assert q(A, 1, 256, 256, A, 30, A, 1000, 1, A, A, 1 << 30, None) == 6
+    assert q(A, 0, 256, 256, A, 32, A, 1000, 1, A, A, 1 << 30, None) == 2
+    assert sv.workspace_bytes(sv.SV_OP_AUX_LOG_SOFTMAX, 2, 4096, 128256, 0, 256) > 2 * 256 * 2
+
     pk = lib.specvocab_pack_rows
     assert pk(A, 1000, 256, 256, 1, None, 10, A, None) == 1
     assert pk(A, 1000, 256, 256, 1, A, 0, A, None) == 2

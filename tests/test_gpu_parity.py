@@ -396,6 +396,32 @@ def test_select_at_the_largest_vocabulary(rows):
         assert_logits_close(sc[r], s_ref[r, idx[r]], "bf16", "scores at the selected ids")
 
 
+AUX_SHAPES = [
+    # dtype, rows, d,   d',  V
+    ("f32", 1, 256, 32, 8192),
+    ("bf16", 1, 1024, 256, 20000),       # one hidden row: row kernel over 512-byte selector rows
+    ("bf16", 3, 512, 64, 4099),          # rows of the output not 16-byte aligned, two vocabulary blocks
+    ("bf16", 20, 2048, 128, 9000),       # matrix-core projections
+    ("bf16", 80, 512, 64, 5000),         # tiled matrix-core scores
+    ("bf16", 2, 256, 8, 1),              # V = 1: log q = 0
+]
+
+
+@pytest.mark.parametrize("dtype,rows,d,dp,V", AUX_SHAPES)
+def test_aux_log_softmax(dtype, rows, d, dp, V):
+    """log q_aux over the whole vocabulary (Section 3.4) against the oracle: the scores carry the logit
+    tolerance, the normaliser is common to a row."""
+    say(f"aux log-softmax {dtype} rows={rows} d={d} d'={dp} V={V}")
+    rng = np.random.default_rng(V + dp + rows)
+    h, Wd, Wv = rand(rng, (rows, d), 1.0, dtype), rand(rng, (dp, d), 0.05, dtype), rand(rng, (V, dp), 0.05, dtype)
+    got = sv.aux_log_softmax(to_dev(h), to_dev(Wd), to_dev(Wv)).cpu().numpy()
+    ref = oracle.aux_log_softmax(h, Wd, Wv)
+    assert_logits_close(got, ref, dtype, "log q_aux")
+    # each row is a normalised distribution, to float32 accuracy
+    lse = np.log(np.exp(got.astype(np.float64)).sum(axis=1))
+    assert np.abs(lse).max() < 5e-5, lse
+
+
 def test_k_varies_from_step_to_step():
     """Section 3.3 Step 2 allows k to change per decoding step: k is a call argument, and buffers and
     workspace sized once for the largest k serve every step."""
