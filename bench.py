@@ -13,7 +13,15 @@ Prints ONE JSON line.  Besides the contract fields it carries
   dense         the full-vocabulary projection on the same GPU and the resulting speed-up
   cold          the same step with U rotated over 8 copies, so that no row can be served from the
                 256 MB last-level cache (the one-U numbers are what a drafter really sees)
+                also: the same kernel over one contiguous block of k rows, cold -- the ceiling of a burst
   select        the selector (W_down, W_vocab, top-k) at the same shape, and the step with it
+  aux_log_softmax_us   log q_aux over the whole vocabulary (Section 3.4) at the same shape
+  break_even    the paper's Section 6 / Table 4 comparison: full vocabulary, a static 32K vocabulary
+                (gathered and pre-packed), SpecVocab with k = 2048 and 8192, whole steps
+  other_configs tree rows (config 3), the 262144-token head with a k sweep (config 4), 512 hidden
+                rows with selection (config 5), each next to the dense projection
+  indexed_lm_head_microbenchmark   fused gather against materialise-then-multiply at four model
+                shapes, k from 512 to 32768 (the paper's kernel microbenchmark in kind)
 """
 from __future__ import annotations
 
