@@ -214,6 +214,20 @@ def test_draft_topk_matches_oracle_on_identical_logits(rows, k, kd, mode, ties):
 
 
 # ---------------------------------------------------------------- draft step in one call
+def test_signed_zeros_tie():
+    """-0.0 and +0.0 are equal logits: the tie goes to the smaller token id, as in the oracle."""
+    say("draft top-kd with signed zeros")
+    rng = np.random.default_rng(5)
+    k, kd = 3000, 12
+    z = np.where(rng.random((2, k)) < 0.5, -0.0, 0.0).astype(np.float32)
+    z[0, 100:110] = -1.0                                     # and something smaller in the way
+    idx = np.stack([rng.permutation(50000)[:k] for _ in range(2)]).astype(np.int32)
+    tok, prob, _ = sv.draft_topk(torch.from_numpy(z).to(DEV), torch.from_numpy(idx).to(DEV), kd)
+    tok_ref, prob_ref = oracle.softmax_topk(z, idx, kd)
+    assert np.array_equal(tok.cpu().numpy(), tok_ref)
+    np.testing.assert_allclose(prob.cpu().numpy(), prob_ref, rtol=2e-5)
+
+
 STEP_SHAPES = [
     # dtype, rows, d,   V,    k,    kd, mode
     ("f32", 1, 256, 8192, 512, 8, "per_row"),         # config 1
