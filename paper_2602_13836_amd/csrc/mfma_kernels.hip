@@ -49,29 +49,28 @@ __global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(const GemvArgs a,
     int64_t item = tile0 + i;
     if (item > n_items - 1) item = n_items - 1;                   // tail rows are computed, never stored
     const int64_t mrow = a.idx ? (int64_t)a.idx[item] : item;
-    const u32x4* mp = reinterpret_cast<const u32x4*>(a.M + mrow * a.m_row_bytes) + g;
+    const u32x4* mrow_p = reinterpret_cast<const u32x4*>(a.M + mrow * a.m_row_bytes);
 
+    // Units past the end of a row are read as the row's last unit instead of being skipped: their
+    // factors in the x slice are zeros and the loaded values are finite, and loads with no condition
+    // around them need no branches.
     auto load_a = [&](int slice, u32x4 (&dst)[kSteps]) {
 #pragma unroll
-        for (int s = 0; s < kSteps; ++s) {
-            const int unit = slice * (kKC / 8) + s * 4 + g;       // 16-byte unit within the row
-            dst[s] = unit < C ? mp[slice * (kKC / 8) + s * 4] : zero16();
-        }
+        for (int s = 0; s < kSteps; ++s) dst[s] = mrow_p[min(slice * (kKC / 8) + s * 4 + g, C - 1)];
     };
     // the x slice goes global -> registers -> LDS in two steps, so that its latency hides behind the
     // multiplications of the current slice
     constexpr int kXAll = (kPieces + kThreads - 1) / kThreads;     // 16-byte pieces per thread
     constexpr bool kSplit = kXAll <= 4;                            // else: too many registers, stage in one go
     constexpr int kXPer = kSplit ? kXAll : 1;
-    auto load_x = [&](int slice, u32x4 (&dst)[kXPer]) {
+    static_assert(!kSplit || kPieces % kThreads == 0, "split staging: every thread moves the same number of pieces");
+    auto load_x = [&](int slice, u32x4 (&dst)[kXPer]) {            // unconditional: row and unit clamped
 #pragma unroll
         for (int q = 0; q < kXPer; ++q) {
             const int p = q * kThreads + tid;
-            const int r = p / (kKC / 8), u = p % (kKC / 8);
-            const int unit = slice * (kKC / 8) + u;
-            dst[q] = zero16();
-            if (p < kPieces && r < rows_here && unit < C)
-                dst[q] = reinterpret_cast<const u32x4*>(a.x + (int64_t)(row0 + r) * a.x_row_bytes)[unit];
+            const int r = min(p / (kKC / 8), rows_here - 1), u = p % (kKC / 8);
+            const int unit = min(slice * (kKC / 8) + u, C - 1);
+            dst[q] = reinterpret_cast<const u32x4*>(a.x + (int64_t)(row0 + r) * a.x_row_bytes)[unit];
         }
     };
     auto stage_x = [&](int slice, int buf) {                       // one step: load and store at once
@@ -85,13 +84,14 @@ __global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(const GemvArgs a,
             *reinterpret_cast<u32x4*>(base + (size_t)r * kXRowBytes + u * 16) = v;
         }
     };
-    auto store_x = [&](const u32x4 (&src)[kXPer], int buf) {
-        unsigned char* base = smem + (size_t)buf * N * kXRowBytes;
+    auto store_x = [&](int slice, const u32x4 (&src)[kXPer]) {     // slice -> buffer slice % 2; zeros past the row
+        unsigned char* base = smem + (size_t)(slice & 1) * N * kXRowBytes;
 #pragma unroll
         for (int q = 0; q < kXPer; ++q) {
             const int p = q * kThreads + tid;
             const int r = p / (kKC / 8), u = p % (kKC / 8);
-            if (p < kPieces) *reinterpret_cast<u32x4*>(base + (size_t)r * kXRowBytes + u * 16) = src[q];
+            const bool past = slice * (kKC / 8) + u >= C;
+            *reinterpret_cast<u32x4*>(base + (size_t)r * kXRowBytes + u * 16) = past ? zero16() : src[q];
         }
     };
 
@@ -124,7 +124,7 @@ __global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(const GemvArgs a,
             }
         }
         if constexpr (kSplit)
-            if (more) store_x(xr, buf ^ 1);       // the other buffer: nobody reads it during this slice
+            if (more) store_x(slice + 1, xr);     // the other buffer: nobody reads it during this slice
         __syncthreads();                          // everyone is done with buf; buf^1 is complete
 #pragma unroll
         for (int s = 0; s < kSteps; ++s) cur[s] = nxt[s];
