@@ -193,16 +193,30 @@ __global__ __launch_bounds__(512) void skinny_mfma_ksplit_kernel(const GemvArgs 
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    for (int slice = wave; slice < nslices; slice += WPB) {
-        u32x4 av[kSteps], bv[NB][kSteps];
+    // whole slices are loaded without conditions (no branches between the loads); only a ragged last
+    // slice masks its units
+    const int nwhole = C / (kKC / 8);
+    auto load_slice = [&](int slice, u32x4 (&av)[kSteps], u32x4 (&bv)[NB][kSteps]) {
+        if (slice < nwhole) {
 #pragma unroll
-        for (int s = 0; s < kSteps; ++s) {
-            const int off = slice * (kKC / 8) + s * 4;
-            const bool ok = off + g < C;
-            av[s] = ok ? mp[off] : zero16();
+            for (int s = 0; s < kSteps; ++s) {
+                const int off = slice * (kKC / 8) + s * 4;
+                av[s] = mp[off];
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) bv[nb][s] = ok ? xp[nb][off] : zero16();
+                for (int nb = 0; nb < NB; ++nb) bv[nb][s] = xp[nb][off];
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < kSteps; ++s) {
+                const int off = slice * (kKC / 8) + s * 4;
+                const bool ok = off + g < C;
+                av[s] = ok ? mp[off] : zero16();
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) bv[nb][s] = ok ? xp[nb][off] : zero16();
+            }
         }
+    };
+    auto multiply = [&](const u32x4 (&av)[kSteps], const u32x4 (&bv)[NB][kSteps]) {
 #pragma unroll
         for (int s = 0; s < kSteps; ++s)
 #pragma unroll
@@ -210,6 +224,22 @@ __global__ __launch_bounds__(512) void skinny_mfma_ksplit_kernel(const GemvArgs 
                 acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av[s]),
                                                                   __builtin_bit_cast(bf16x8_t, bv[nb][s]), acc[nb],
                                                                   0, 0, 0);
+    };
+    int slice = wave;
+    if constexpr (NB == 1) {
+        // registers allow two slices per wavefront in flight: one memory latency instead of two
+        for (; slice + WPB < nwhole; slice += 2 * WPB) {
+            u32x4 av0[kSteps], bv0[NB][kSteps], av1[kSteps], bv1[NB][kSteps];
+            load_slice(slice, av0, bv0);
+            load_slice(slice + WPB, av1, bv1);
+            multiply(av0, bv0);
+            multiply(av1, bv1);
+        }
+    }
+    for (; slice < nslices; slice += WPB) {
+        u32x4 av[kSteps], bv[NB][kSteps];
+        load_slice(slice, av, bv);
+        multiply(av, bv);
     }
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) s_part[wave][nb][lane] = acc[nb];
