@@ -151,10 +151,12 @@ def subset_logits(h: np.ndarray, U: np.ndarray, idx: np.ndarray, acc: str = "f32
 
 
 def select(h: np.ndarray, W_down: np.ndarray, W_vocab: np.ndarray, k: int,
-           hprime_round: Optional[bool] = None, acc: str = "f32", full: bool = False):
+           hprime_round: Optional[bool] = None, acc: str = "f32", full: bool = False,
+           tau: Optional[float] = None):
     """Steps 1-2 of Section 3.3. Returns (idx [rows x k] int32 ascending, scores [rows x k]) and,
     with full=True, also (s [rows x V], h' [rows x d']).  hprime_round defaults to True for bf16
-    storage and False for float32."""
+    storage and False for float32.  With tau, selected tokens scoring below tau become padding
+    slots (id -1, score -inf) in place."""
     h = _c2(h)
     W_down, W_vocab = np.ascontiguousarray(_c2(W_down)), np.ascontiguousarray(_c2(W_vocab))
     dt = _same_dtype(h, W_down, W_vocab)
@@ -172,6 +174,7 @@ def select(h: np.ndarray, W_down: np.ndarray, W_vocab: np.ndarray, k: int,
     rc = _load().svo_select(_ptr(h), ctypes.c_int64(rows), ctypes.c_int64(d), ctypes.c_int64(_ld(h)),
                             _ptr(W_down), ctypes.c_int64(d_prime), _ptr(W_vocab), ctypes.c_int64(V),
                             dt, int(bool(hprime_round)), _acc_code(acc), ctypes.c_int64(k),
+                            ctypes.c_double(-np.inf if tau is None else float(tau)),
                             _ptr(idx), _ptr(scores), _ptr(s_full), _ptr(hp))
     _check(rc, "select")
     if full:

@@ -100,7 +100,9 @@ int svo_dense_logits(const void* h, int64_t rows, int64_t d, int64_t ldh,
 }
 
 /* Section 3.3 Step 3: z'[r, j] = sum_i U[idx(r, j), i] h[r, i]    out: [rows x k]
- * idx is [rows x k] (per row) or [k] (one set for the whole step). */
+ * idx is [rows x k] (per row) or [k] (one set for the whole step).
+ * Variable subset sizes inside fixed-size lists (Section 3.3 Step 2 lets k vary): an entry -1 is a
+ * padding slot, it names no token and its logit is -inf. */
 int svo_subset_logits(const void* h, int64_t rows, int64_t d, int64_t ldh,
                       const void* U, int64_t V, int64_t ldu, int dtype,
                       const int32_t* idx, int64_t k, int idx_mode, int acc, double* out) {
@@ -110,6 +112,10 @@ int svo_subset_logits(const void* h, int64_t rows, int64_t d, int64_t ldh,
         const int32_t* row_idx = (idx_mode == SVO_IDX_PER_STEP) ? idx : idx + r * k;
         for (int64_t j = 0; j < k; ++j) {
             int64_t tok = row_idx[j];
+            if (tok == -1) {                      /* padding slot: no token, logit -inf */
+                out[r * k + j] = -INFINITY;
+                continue;
+            }
             if (tok < 0 || tok >= V) return SVO_ERR_INDEX;
             out[r * k + j] = dot_stored(U, tok * ldu, h, r * ldh, dtype, d, acc);
         }
@@ -142,11 +148,13 @@ static int by_int32(const void* pa, const void* pb) {
  *   h'[r, j] = sum_i W_down[j, i] h[r, i]            (W_down is [d' x d])
  *   s[r, v]  = sum_j W_vocab[v, j] h'[r, j]          (W_vocab is [V x d'])
  *   idx_out[r, :] = ids of the k largest s[r, :], ascending id order
+ * With a finite tau the selected tokens scoring below tau are replaced by padding slots (-1, score
+ * -inf) in place, so the list keeps its length and its id order.
  * Optional outputs (may be NULL): scores_out [rows x k] = s at idx_out;
  * s_full_out [rows x V]; hprime_out [rows x d'] (the values fed to the second projection). */
 int svo_select(const void* h, int64_t rows, int64_t d, int64_t ldh,
                const void* W_down, int64_t d_prime, const void* W_vocab, int64_t V,
-               int dtype, int hprime_round, int acc, int64_t k,
+               int dtype, int hprime_round, int acc, int64_t k, double tau,
                int32_t* idx_out, double* scores_out, double* s_full_out, double* hprime_out) {
     if (!h || !W_down || !W_vocab || !idx_out || rows < 1 || d < 1 || d_prime < 1 || V < 1 ||
         k < 1 || k > V || ldh < d)
@@ -193,8 +201,14 @@ int svo_select(const void* h, int64_t rows, int64_t d, int64_t ldh,
         int32_t* dst = idx_out + r * k;
         for (int64_t j = 0; j < k; ++j) dst[j] = order[j].tok;
         qsort(dst, (size_t)k, sizeof(int32_t), by_int32);
-        if (scores_out)
-            for (int64_t j = 0; j < k; ++j) scores_out[r * k + j] = s[dst[j]];
+        /* variable subset size: of the k best, only those scoring at least tau stay; the others
+         * become padding slots (tau = -inf keeps all k) */
+        for (int64_t j = 0; j < k; ++j) {
+            const double sc = s[dst[j]];
+            const int keep = sc >= tau;
+            if (scores_out) scores_out[r * k + j] = keep ? sc : -INFINITY;
+            if (!keep) dst[j] = -1;
+        }
     }
     free(hp); free(s); free(order);
     return SVO_OK;
@@ -219,17 +233,19 @@ int svo_softmax_topk(const float* logits, const int32_t* idx, int idx_mode,
         double m = (double)z[0];
         for (int64_t j = 1; j < k; ++j)
             if ((double)z[j] > m) m = (double)z[j];
+        /* padding slots carry -inf: probability 0; a row of nothing but padding has all probabilities 0 */
+        const int empty = isinf(m) && m < 0;
         double denom = 0.0;
-        for (int64_t j = 0; j < k; ++j) denom += exp((double)z[j] - m);
+        for (int64_t j = 0; j < k; ++j) denom += empty ? 0.0 : exp((double)z[j] - m);
         for (int64_t j = 0; j < k; ++j) {
             order[j].score = (double)z[j];
             order[j].tok = row_idx[j];
-            if (probs_full_out) probs_full_out[r * k + j] = exp((double)z[j] - m) / denom;
+            if (probs_full_out) probs_full_out[r * k + j] = empty ? 0.0 : exp((double)z[j] - m) / denom;
         }
         qsort(order, (size_t)k, sizeof(scored_t), by_score_then_id);
         for (int64_t t = 0; t < kd; ++t) {
             tok_out[r * kd + t] = order[t].tok;
-            prob_out[r * kd + t] = exp(order[t].score - m) / denom;
+            prob_out[r * kd + t] = empty ? 0.0 : exp(order[t].score - m) / denom;
         }
     }
     free(order);

@@ -429,7 +429,7 @@ def test_error_paths():
     with pytest.raises(RuntimeError):
         oracle.subset_logits(h, U, np.array([[0, 6]], np.int32))
     with pytest.raises(RuntimeError):
-        oracle.subset_logits(h, U, np.array([[-1]], np.int32))
+        oracle.subset_logits(h, U, np.array([[-2]], np.int32))      # -1 alone is the padding slot
     with pytest.raises(RuntimeError):
         oracle.select(h, np.zeros((2, 4), np.float32), np.zeros((6, 2), np.float32), 7)
     with pytest.raises(TypeError):
@@ -499,3 +499,62 @@ def test_aux_log_softmax_composes_the_selector_scores(dtype):
     np.testing.assert_allclose(got, want, rtol=0, atol=1e-9)
     # the float32-accumulated variant stays within accumulation noise of it
     np.testing.assert_allclose(oracle.aux_log_softmax(h, Wd, Wv), want, rtol=0, atol=2e-5 if dtype == "f32" else 2e-2)
+
+
+# --------------------------------------------------------------------------
+# Variable subset sizes inside fixed-size lists: padding slots (-1) and a score threshold.
+# Section 3.3 Step 2 only says that k may vary; the encoding is this implementation's, so the pins
+# are its defining properties: padding changes nothing for the real entries, and a padded list
+# behaves as the compacted list of its real entries.
+# --------------------------------------------------------------------------
+def test_padding_slots_in_subset_logits_and_softmax():
+    rng = np.random.default_rng(41)
+    d, V, k, kd = 32, 200, 30, 6
+    h = rng.normal(size=(2, d)).astype(np.float32)
+    U = rng.normal(scale=0.3, size=(V, d)).astype(np.float32)
+    idx = np.stack([rng.permutation(V)[:k] for _ in range(2)]).astype(np.int32)
+    pad = idx.copy()
+    holes = [np.array([0, 7, 8, 29]), np.array([3, 4, 5, 6, 20])]
+    for r in range(2):
+        pad[r, holes[r]] = -1
+    z, zp = oracle.subset_logits(h, U, idx), oracle.subset_logits(h, U, pad)
+    for r in range(2):
+        real = np.setdiff1d(np.arange(k), holes[r])
+        assert np.array_equal(zp[r, real], z[r, real])                  # real entries untouched
+        assert np.all(np.isneginf(zp[r, holes[r]]))                     # padding: logit -inf
+        # the padded list behaves as the compacted list of its real entries
+        tok_p, prob_p, q_p = oracle.softmax_topk(zp[r:r + 1], pad[r:r + 1], kd, full=True)
+        tok_c, prob_c, q_c = oracle.softmax_topk(z[r:r + 1, real], idx[r:r + 1, real], kd, full=True)
+        assert np.array_equal(tok_p, tok_c)
+        np.testing.assert_allclose(prob_p, prob_c, rtol=1e-14)
+        np.testing.assert_allclose(q_p[0, real], q_c[0], rtol=1e-14)
+        assert np.all(q_p[0, holes[r]] == 0.0)
+
+
+def test_fewer_real_entries_than_draft_tokens_and_empty_rows():
+    z = np.array([[1.0, -np.inf, 0.0, -np.inf], [-np.inf] * 4], dtype=np.float32)
+    idx = np.array([[5, -1, 9, -1], [-1, -1, -1, -1]], dtype=np.int32)
+    tok, prob, q = oracle.softmax_topk(z, idx, 3, full=True)
+    e = math.exp(-1.0)
+    assert tok[0].tolist() == [5, 9, -1]
+    np.testing.assert_allclose(prob[0], [1 / (1 + e), e / (1 + e), 0.0], rtol=1e-15)
+    assert tok[1].tolist() == [-1, -1, -1] and np.all(prob[1] == 0.0) and np.all(q[1] == 0.0)
+
+
+def test_score_threshold_pads_the_selected_list_in_place():
+    rng = np.random.default_rng(42)
+    d, dp, V, k = 24, 8, 300, 40
+    h = rng.normal(size=(3, d)).astype(np.float32)
+    Wd = rng.normal(scale=0.3, size=(dp, d)).astype(np.float32)
+    Wv = rng.normal(scale=0.3, size=(V, dp)).astype(np.float32)
+    idx, sc = oracle.select(h, Wd, Wv, k)
+    tau = float(np.median(sc))                                          # keeps about half of each list
+    idx_t, sc_t = oracle.select(h, Wd, Wv, k, tau=tau)
+    keep = sc >= tau
+    assert np.array_equal(idx_t, np.where(keep, idx, -1))
+    assert np.array_equal(sc_t, np.where(keep, sc, -np.inf))
+    assert 0 < keep.sum() < keep.size
+    # tau = -inf is the plain selection; tau above every score empties the lists
+    assert np.array_equal(oracle.select(h, Wd, Wv, k, tau=-np.inf)[0], idx)
+    assert np.all(oracle.select(h, Wd, Wv, k, tau=1e30)[0] == -1)
+
