@@ -69,6 +69,16 @@ typedef enum { SV_F32 = 0, SV_BF16 = 1 } sv_dtype;
  * SV_IDX_PER_STEP: idx is [k], one set shared by every row of the step. */
 typedef enum { SV_IDX_PER_ROW = 0, SV_IDX_PER_STEP = 1 } sv_idx_mode;
 
+/* Subset sizes that differ from row to row inside fixed-size lists (Section 3.3 Step 2 lets k vary).
+ * OR this flag into idx_mode to say that the index list may hold PADDING SLOTS: entries equal to -1
+ * name no token.  A padding slot reads no row of U, its logit is -inf and its probability 0; the real
+ * entries of the row are computed exactly as without padding, and the draft top-kd behaves as on the
+ * compacted list of real entries (if a row has fewer than kd of them, the remaining tok_out entries
+ * are -1 with probability 0; a row of padding only gets all probabilities 0).  The gathering calls
+ * need extra workspace for a padded list (specvocab_workspace_bytes with the flagged idx_mode) and
+ * two small extra launches; lists without the flag must not contain -1. */
+#define SV_IDX_PADDED 4
+
 typedef enum {
     SV_OP_SELECT = 0,
     SV_OP_SUBSET_LOGITS = 1,
@@ -109,12 +119,25 @@ int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh,
                      int32_t* idx_out, float* scores_out,
                      void* ws, size_t ws_bytes, void* stream);
 
+/* specvocab_select with a score threshold: of the k best tokens of a row only those with
+ * s[r, v] >= tau stay; the others become padding slots in place (idx_out = -1, scores_out = -inf),
+ * so that the list keeps its length k and its ascending id order and can be passed on with
+ * SV_IDX_PADDED.  tau = -INFINITY is specvocab_select; NaN is SV_ERR_SHAPE.  Workspace as for
+ * SV_OP_SELECT. */
+int specvocab_select_threshold(const void* h, int64_t rows, int64_t d, int64_t ldh,
+                               const void* W_down, int64_t d_prime,
+                               const void* W_vocab, int64_t V,
+                               int dt, int64_t k, float tau,
+                               int32_t* idx_out, float* scores_out,
+                               void* ws, size_t ws_bytes, void* stream);
+
 /* Section 3.3, Step 3 (the fused indexed LM head of Section 3.5, "Custom kernel"):
  *     logits_out[r, j] = < U[idx(r, j), :], h[r, :] >
  * without materialising U[idx, :]; each needed row of U is read from memory once per use.
  * h: device [rows x d] stride ldh.  U: device [V x d] stride ldu.
  * idx: device int32, [rows x k] (SV_IDX_PER_ROW) or [k] (SV_IDX_PER_STEP), any order; every
- * entry must lie in [0, V) (caller's contract, unchecked).  Duplicates just repeat the value.
+ * entry must lie in [0, V) (caller's contract, unchecked) or, with SV_IDX_PADDED, be -1.
+ * Duplicates just repeat the value.
  * logits_out: device [rows x k] float32.
  * With several hidden rows and one set per row (a draft tree) the union of the sets is formed in
  * the workspace and each needed row of U is read once per step rather than once per asking row;

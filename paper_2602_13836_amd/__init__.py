@@ -21,6 +21,7 @@ SV_IDX_PER_ROW, SV_IDX_PER_STEP = 0, 1
 SV_OP_SELECT, SV_OP_SUBSET_LOGITS, SV_OP_DRAFT_TOPK, SV_OP_DENSE_LOGITS, SV_OP_DRAFT_STEP = 0, 1, 2, 3, 4
 SV_OP_INDEXED_HEAD_NAIVE = 5
 SV_OP_AUX_LOG_SOFTMAX = 6
+SV_IDX_PADDED = 4        # OR into idx_mode: the list may hold padding slots (-1)
 MAX_KD = 64
 
 EXPORTS = (
@@ -28,6 +29,7 @@ EXPORTS = (
     "specvocab_status_string",
     "specvocab_workspace_bytes",
     "specvocab_select",
+    "specvocab_select_threshold",
     "specvocab_subset_logits",
     "specvocab_draft_topk",
     "specvocab_draft_step",
@@ -69,6 +71,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.specvocab_select.restype = ci
     lib.specvocab_select.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, ci, i64, vp, vp, vp,
                                      ctypes.c_size_t, vp]
+    lib.specvocab_select_threshold.restype = ci
+    lib.specvocab_select_threshold.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, ci, i64, ctypes.c_float, vp, vp,
+                                               vp, ctypes.c_size_t, vp]
     lib.specvocab_subset_logits.restype = ci
     lib.specvocab_subset_logits.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, ci, vp, vp,
                                             ctypes.c_size_t, vp]
@@ -161,9 +166,10 @@ def _workspace(nbytes: int, device, ws: Optional[torch.Tensor]) -> Optional[torc
 def select(h: torch.Tensor, W_down: torch.Tensor, W_vocab: torch.Tensor, k: int,
            idx_out: Optional[torch.Tensor] = None, scores_out: Optional[torch.Tensor] = None,
            want_scores: bool = False, ws: Optional[torch.Tensor] = None,
-           stream: Optional[torch.cuda.Stream] = None):
+           stream: Optional[torch.cuda.Stream] = None, tau: Optional[float] = None):
     """specvocab_select: ids of the k largest approximate logits per row, ascending.
-    Returns (idx [rows x k] int32, scores [rows x k] float32 or None)."""
+    Returns (idx [rows x k] int32, scores [rows x k] float32 or None).
+    tau: specvocab_select_threshold -- selected tokens scoring below tau become padding slots (-1)."""
     rows, d, ldh = _mat(h, "h")
     dp, d2, ldd = _mat(W_down, "W_down")
     V, dp2, ldv = _mat(W_vocab, "W_vocab")
@@ -178,17 +184,25 @@ def select(h: torch.Tensor, W_down: torch.Tensor, W_vocab: torch.Tensor, k: int,
         scores_out = torch.empty((rows, k), dtype=torch.float32, device=h.device)
     nbytes = workspace_bytes(SV_OP_SELECT, rows, d, V, k, dp, 0, dt)
     ws = _workspace(nbytes, h.device, ws)
-    _check(load_library().specvocab_select(_ptr(h), rows, d, ldh, _ptr(W_down), dp, _ptr(W_vocab), V, dt, k,
-                                           _ptr(idx_out), _ptr(scores_out), _ptr(ws),
-                                           0 if ws is None else ws.numel(), _stream(stream)),
-           "specvocab_select")
+    if tau is None:
+        _check(load_library().specvocab_select(_ptr(h), rows, d, ldh, _ptr(W_down), dp, _ptr(W_vocab), V, dt, k,
+                                               _ptr(idx_out), _ptr(scores_out), _ptr(ws),
+                                               0 if ws is None else ws.numel(), _stream(stream)),
+               "specvocab_select")
+    else:
+        _check(load_library().specvocab_select_threshold(_ptr(h), rows, d, ldh, _ptr(W_down), dp, _ptr(W_vocab), V,
+                                                         dt, k, ctypes.c_float(tau), _ptr(idx_out),
+                                                         _ptr(scores_out), _ptr(ws),
+                                                         0 if ws is None else ws.numel(), _stream(stream)),
+               "specvocab_select_threshold")
     return idx_out, scores_out
 
 
 def subset_logits(h: torch.Tensor, U: torch.Tensor, idx: torch.Tensor,
                   out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
-                  stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
-    """specvocab_subset_logits: out[r, j] = <U[idx(r, j)], h_r>, [rows x k] float32."""
+                  stream: Optional[torch.cuda.Stream] = None, padded: bool = False) -> torch.Tensor:
+    """specvocab_subset_logits: out[r, j] = <U[idx(r, j)], h_r>, [rows x k] float32.
+    padded=True: idx may hold padding slots (-1), whose logit is -inf."""
     rows, d, ldh = _mat(h, "h")
     V, d2, ldu = _mat(U, "U")
     if d2 != d:
@@ -197,6 +211,8 @@ def subset_logits(h: torch.Tensor, U: torch.Tensor, idx: torch.Tensor,
     if _dt(U) != dt:
         raise TypeError("h and U must share a dtype")
     mode, k = _idx(idx, rows)
+    if padded:
+        mode |= SV_IDX_PADDED
     if out is None:
         out = torch.empty((rows, k), dtype=torch.float32, device=h.device)
     nbytes = workspace_bytes(SV_OP_SUBSET_LOGITS, rows, d, V, k, 0, 0, dt, mode)
@@ -305,7 +321,7 @@ def draft_step(h: torch.Tensor, U: torch.Tensor, idx: torch.Tensor, kd: int,
                logits_out: Optional[torch.Tensor] = None, tok_out: Optional[torch.Tensor] = None,
                prob_out: Optional[torch.Tensor] = None, probs_full_out: Optional[torch.Tensor] = None,
                want_probs: bool = False, ws: Optional[torch.Tensor] = None,
-               stream: Optional[torch.cuda.Stream] = None):
+               stream: Optional[torch.cuda.Stream] = None, padded: bool = False):
     """specvocab_draft_step: subset logits, then subset softmax and top-kd tokens of every row,
     enqueued back to back. Returns (logits [rows x k], tok [rows x kd], prob [rows x kd],
     q_K [rows x k] or None)."""
@@ -317,6 +333,8 @@ def draft_step(h: torch.Tensor, U: torch.Tensor, idx: torch.Tensor, kd: int,
     if _dt(U) != dt:
         raise TypeError("h and U must share a dtype")
     mode, k = _idx(idx, rows)
+    if padded:
+        mode |= SV_IDX_PADDED
     dev = h.device
     if logits_out is None:
         logits_out = torch.empty((rows, k), dtype=torch.float32, device=dev)

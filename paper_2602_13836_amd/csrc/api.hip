@@ -39,7 +39,9 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline size_t round256(size_t n) { return (n + 255u) & ~static_cast<size_t>(255u); }
 inline int esize_of(int dt) { return dt == SV_BF16 ? 2 : 4; }
 inline bool dtype_ok(int dt) { return dt == SV_F32 || dt == SV_BF16; }
-inline bool mode_ok(int m) { return m == SV_IDX_PER_ROW || m == SV_IDX_PER_STEP; }
+inline bool mode_ok(int m) { return (m & ~SV_IDX_PADDED) == SV_IDX_PER_ROW || (m & ~SV_IDX_PADDED) == SV_IDX_PER_STEP; }
+inline bool is_padded(int m) { return (m & SV_IDX_PADDED) != 0; }
+inline int base_mode(int m) { return m & ~SV_IDX_PADDED; }
 
 // a row of `n` elements must be a whole number of 16-byte units, and so must its stride
 inline int check_row(int64_t n, int64_t ld, int dt) {
@@ -63,11 +65,11 @@ SelectWs select_ws(int64_t rows, int64_t V, int64_t d_prime, int dt) {
 }
 
 // Debug mode (environment variable SPECVOCAB_VALIDATE=1): range-check an index list before using it.
-int validate_indices(const int32_t* idx, int64_t n, int64_t V, hipStream_t s) {
+int validate_indices(const int32_t* idx, int64_t n, int64_t V, hipStream_t s, bool padded = false) {
     const char* v = getenv("SPECVOCAB_VALIDATE");
     if (!v || strcmp(v, "1") != 0) return SV_OK;
     unsigned bad = 0;
-    if (sv::count_bad_indices(idx, n, V, s, &bad) != hipSuccess) return SV_ERR_HIP;
+    if (sv::count_bad_indices(idx, n, V, padded, s, &bad) != hipSuccess) return SV_ERR_HIP;
     return bad ? SV_ERR_INDEX : SV_OK;
 }
 
@@ -95,7 +97,7 @@ sv::GemvArgs gather_args(const void* h, int64_t rows, int64_t d, int64_t ldh, co
     g.M = static_cast<const char*>(U);
     g.m_row_bytes = ldu * es;
     g.idx = idx;
-    g.idx_row_stride = idx_mode == SV_IDX_PER_ROW ? k : 0;
+    g.idx_row_stride = base_mode(idx_mode) == SV_IDX_PER_ROW ? k : 0;
     g.n_items = k;
     g.chunks = (int)(d * es / 16);
     g.rows = (int)rows;
@@ -104,10 +106,47 @@ sv::GemvArgs gather_args(const void* h, int64_t rows, int64_t d, int64_t ldh, co
     return g;
 }
 
+// bytes of the clean copy of a padded index list (0 if the list is not padded)
+size_t pad_ws_bytes(int64_t rows, int64_t k, int idx_mode) {
+    if (!is_padded(idx_mode)) return 0;
+    const int64_t sets = base_mode(idx_mode) == SV_IDX_PER_ROW ? rows : 1;
+    return round256((size_t)sets * (size_t)k * sizeof(int32_t));
+}
+
 size_t gather_ws_bytes(int64_t rows, int64_t d, int64_t V, int64_t k, int dt, int idx_mode) {
     sv::GemvArgs g = gather_args(nullptr, rows, d, d, nullptr, d, dt, reinterpret_cast<const int32_t*>(16), k,
                                  idx_mode, nullptr);
-    return sv::union_path_wanted(dt, g) ? sv::union_ws_bytes(rows, V, k) : 0;
+    return pad_ws_bytes(rows, k, idx_mode) + (sv::union_path_wanted(dt, g) ? sv::union_ws_bytes(rows, V, k) : 0);
+}
+
+// Gathered logits for an index list that may carry padding slots (SV_IDX_PADDED): the kernels run on
+// a clean copy of the list (padding -> token 0) and the padding slots get -inf afterwards, so the
+// paths for plain lists stay exactly as they are.
+int launch_gather(int dt, const void* h, int64_t rows, int64_t d, int64_t ldh, const void* U, int64_t V,
+                  int64_t ldu, const int32_t* idx, int64_t k, int idx_mode, float* logits_out, void* ws,
+                  size_t ws_bytes, hipStream_t s) {
+    const bool padded = is_padded(idx_mode);
+    const int64_t sets = base_mode(idx_mode) == SV_IDX_PER_ROW ? rows : 1;
+    int st = validate_indices(idx, sets * k, V, s, padded);
+    if (st != SV_OK) return st;
+    const int32_t* use = idx;
+    char* rest = static_cast<char*>(ws);
+    size_t rest_bytes = ws_bytes;
+    if (padded) {
+        const size_t pb = pad_ws_bytes(rows, k, idx_mode);
+        if (!ws || ws_bytes < pb) return SV_ERR_WORKSPACE;
+        if (!aligned16(ws)) return SV_ERR_ALIGN;
+        if (sv::launch_pad_clean(idx, sets * k, reinterpret_cast<int32_t*>(ws), s) != hipSuccess) return SV_ERR_HIP;
+        use = reinterpret_cast<const int32_t*>(ws);
+        rest += pb;
+        rest_bytes -= pb;
+    }
+    const sv::GemvArgs g = gather_args(h, rows, d, ldh, U, ldu, dt, use, k, idx_mode, logits_out);
+    st = launch_rows_product(dt, g, V, rest_bytes ? rest : nullptr, rest_bytes, s);
+    if (st != SV_OK) return st;
+    if (padded && sv::launch_pad_mask(idx, g.idx_row_stride, (int)rows, k, logits_out, s) != hipSuccess)
+        return SV_ERR_HIP;
+    return SV_OK;
 }
 
 // h'[r, :] = W_down h[r, :] into hp ([rows x d_prime] in the storage dtype; bf16: round to nearest even);
@@ -211,6 +250,7 @@ int specvocab_workspace_bytes(int op, int64_t rows, int64_t d, int64_t V, int64_
         case SV_OP_INDEXED_HEAD_NAIVE: {
             if (!dtype_ok(dt) || !mode_ok(idx_mode)) return SV_ERR_DTYPE;
             if (rows < 1 || rows > kMaxRows || k < 1 || d < 1) return SV_ERR_SHAPE;
+            if (is_padded(idx_mode)) return SV_ERR_UNSUPPORTED;
             const int64_t sets = idx_mode == SV_IDX_PER_ROW ? rows : 1;
             *bytes_out = round256((size_t)sets * (size_t)k * (size_t)d * (size_t)esize_of(dt));
             return SV_OK;
@@ -229,9 +269,9 @@ int specvocab_workspace_bytes(int op, int64_t rows, int64_t d, int64_t V, int64_
     }
 }
 
-int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* W_down,
-                     int64_t d_prime, const void* W_vocab, int64_t V, int dt, int64_t k,
-                     int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream) {
+static int select_impl(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* W_down, int64_t d_prime,
+                       const void* W_vocab, int64_t V, int dt, int64_t k, float tau, int32_t* idx_out,
+                       float* scores_out, void* ws, size_t ws_bytes, void* stream) {
     if (!h || !W_down || !W_vocab || !idx_out) return SV_ERR_NULL;
     int st = check_select_shape(rows, d, V, k, d_prime, dt);
     if (st != SV_OK) return st;
@@ -294,9 +334,25 @@ int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh, const 
     ra.k = k;
     ra.idx_out = idx_out;
     ra.scores_out = scores_out;
+    ra.tau = tau;
     ra.scratch = radix;
     if (sv::launch_topk_of_scores(ra, s) != hipSuccess) return SV_ERR_HIP;
     return SV_OK;
+}
+
+int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* W_down,
+                     int64_t d_prime, const void* W_vocab, int64_t V, int dt, int64_t k,
+                     int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream) {
+    return select_impl(h, rows, d, ldh, W_down, d_prime, W_vocab, V, dt, k, -INFINITY, idx_out, scores_out, ws,
+                       ws_bytes, stream);
+}
+
+int specvocab_select_threshold(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* W_down,
+                               int64_t d_prime, const void* W_vocab, int64_t V, int dt, int64_t k, float tau,
+                               int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream) {
+    if (tau != tau) return SV_ERR_SHAPE;                        // NaN orders nothing
+    return select_impl(h, rows, d, ldh, W_down, d_prime, W_vocab, V, dt, k, tau, idx_out, scores_out, ws,
+                       ws_bytes, stream);
 }
 
 int specvocab_aux_log_softmax(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* W_down,
@@ -345,10 +401,8 @@ int specvocab_subset_logits(const void* h, int64_t rows, int64_t d, int64_t ldh,
     st = check_row(d, ldu, dt);
     if (st != SV_OK) return st;
     if (!aligned16(h) || !aligned16(U)) return SV_ERR_ALIGN;
-    st = validate_indices(idx, idx_mode == SV_IDX_PER_ROW ? rows * k : k, V, static_cast<hipStream_t>(stream));
-    if (st != SV_OK) return st;
-    const sv::GemvArgs g = gather_args(h, rows, d, ldh, U, ldu, dt, idx, k, idx_mode, logits_out);
-    return launch_rows_product(dt, g, V, ws, ws_bytes, static_cast<hipStream_t>(stream));
+    return launch_gather(dt, h, rows, d, ldh, U, V, ldu, idx, k, idx_mode, logits_out, ws, ws_bytes,
+                         static_cast<hipStream_t>(stream));
 }
 
 int specvocab_indexed_head_naive(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* U, int64_t V,
@@ -356,6 +410,7 @@ int specvocab_indexed_head_naive(const void* h, int64_t rows, int64_t d, int64_t
                                  float* logits_out, void* ws, size_t ws_bytes, void* stream) {
     if (!h || !U || !idx || !logits_out) return SV_ERR_NULL;
     if (!dtype_ok(dt) || !mode_ok(idx_mode)) return SV_ERR_DTYPE;
+    if (is_padded(idx_mode)) return SV_ERR_UNSUPPORTED;        // the comparator takes plain lists only
     if (rows < 1 || rows > kMaxRows || V < 1 || V > kMaxVocab || k < 1) return SV_ERR_SHAPE;
     int st = check_row(d, ldh, dt);
     if (st != SV_OK) return st;
@@ -424,7 +479,7 @@ int specvocab_draft_topk(const float* logits, const int32_t* idx, int idx_mode, 
     sv::TopkArgs t{};
     t.logits = logits;
     t.idx = idx;
-    t.idx_row_stride = idx_mode == SV_IDX_PER_ROW ? k : 0;
+    t.idx_row_stride = base_mode(idx_mode) == SV_IDX_PER_ROW ? k : 0;
     t.rows = (int)rows;
     t.k = k;
     t.kd = (int)kd;
@@ -450,13 +505,10 @@ int specvocab_draft_step(const void* h, int64_t rows, int64_t d, int64_t ldh, co
     if (st != SV_OK) return st;
     if (!aligned16(h) || !aligned16(U)) return SV_ERR_ALIGN;
 
-    st = validate_indices(idx, idx_mode == SV_IDX_PER_ROW ? rows * k : k, V, static_cast<hipStream_t>(stream));
-    if (st != SV_OK) return st;
-    const sv::GemvArgs g = gather_args(h, rows, d, ldh, U, ldu, dt, idx, k, idx_mode, logits_out);
     sv::TopkArgs t{};
     t.logits = logits_out;
     t.idx = idx;
-    t.idx_row_stride = g.idx_row_stride;
+    t.idx_row_stride = base_mode(idx_mode) == SV_IDX_PER_ROW ? k : 0;
     t.rows = (int)rows;
     t.k = k;
     t.kd = (int)kd;
@@ -464,7 +516,7 @@ int specvocab_draft_step(const void* h, int64_t rows, int64_t d, int64_t ldh, co
     t.prob_out = prob_out;
     t.probs_full_out = probs_full_out;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    st = launch_rows_product(dt, g, V, ws, ws_bytes, s);
+    st = launch_gather(dt, h, rows, d, ldh, U, V, ldu, idx, k, idx_mode, logits_out, ws, ws_bytes, s);
     if (st != SV_OK) return st;
     if (sv::launch_softmax_topk(t, s) != hipSuccess) return SV_ERR_HIP;
     return SV_OK;

@@ -130,13 +130,30 @@ __global__ __launch_bounds__(256) void gemv_long_rows_kernel(const GemvArgs a) {
 // debug aid: counts the entries of idx outside [0, V)
 __device__ unsigned int g_bad_indices;
 
-__global__ __launch_bounds__(256) void check_indices_kernel(const int32_t* idx, int64_t n, int64_t V) {
+__global__ __launch_bounds__(256) void check_indices_kernel(const int32_t* idx, int64_t n, int64_t V,
+                                                            int64_t lowest) {
     unsigned bad = 0;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
         const int64_t v = idx[i];
-        bad += (v < 0) || (v >= V);
+        bad += (v < lowest) || (v >= V);
     }
     if (bad) atomicAdd(&g_bad_indices, bad);
+}
+
+// index lists with padding slots (-1 = no token): a clean copy for the kernels that follow addresses ...
+__global__ __launch_bounds__(256) void pad_clean_kernel(const int32_t* idx, int64_t n, int32_t* clean) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const int32_t v = idx[i];
+        clean[i] = v < 0 ? 0 : v;
+    }
+}
+// ... and -inf for the logits of the padding slots afterwards
+__global__ __launch_bounds__(256) void pad_mask_kernel(const int32_t* idx, int64_t idx_row_stride, int64_t k,
+                                                       int64_t pairs, float* logits) {
+    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < pairs; p += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = p / k, j = p - r * k;
+        if (idx[r * idx_row_stride + j] < 0) logits[p] = -INFINITY;
+    }
 }
 
 // dst[j, :] = M[idx[j], :]: one wavefront per row, 16 bytes per lane and step
@@ -196,7 +213,27 @@ hipError_t launch_dt(const GemvArgs& a, int cus, hipStream_t stream) {
 
 }  // namespace
 
-hipError_t count_bad_indices(const int32_t* idx, int64_t n, int64_t V, hipStream_t stream, unsigned* bad_out) {
+hipError_t launch_pad_clean(const int32_t* idx, int64_t n, int32_t* clean, hipStream_t stream) {
+    int64_t bx = (n + 1023) / 1024;
+    if (bx > 2048) bx = 2048;
+    if (bx < 1) bx = 1;
+    hipLaunchKernelGGL(pad_clean_kernel, dim3((unsigned)bx), dim3(256), 0, stream, idx, n, clean);
+    return hipGetLastError();
+}
+
+hipError_t launch_pad_mask(const int32_t* idx, int64_t idx_row_stride, int rows, int64_t k, float* logits,
+                           hipStream_t stream) {
+    const int64_t pairs = (int64_t)rows * k;
+    int64_t bx = (pairs + 1023) / 1024;
+    if (bx > 2048) bx = 2048;
+    if (bx < 1) bx = 1;
+    hipLaunchKernelGGL(pad_mask_kernel, dim3((unsigned)bx), dim3(256), 0, stream, idx, idx_row_stride, k, pairs,
+                       logits);
+    return hipGetLastError();
+}
+
+hipError_t count_bad_indices(const int32_t* idx, int64_t n, int64_t V, bool padded, hipStream_t stream,
+                             unsigned* bad_out) {
     const unsigned zero = 0;
     hipError_t e = hipMemcpyToSymbolAsync(HIP_SYMBOL(g_bad_indices), &zero, sizeof zero, 0, hipMemcpyHostToDevice,
                                           stream);
@@ -204,7 +241,8 @@ hipError_t count_bad_indices(const int32_t* idx, int64_t n, int64_t V, hipStream
     int64_t bx = (n + 255) / 256;
     if (bx > 1024) bx = 1024;
     if (bx < 1) bx = 1;
-    hipLaunchKernelGGL(check_indices_kernel, dim3((unsigned)bx), dim3(256), 0, stream, idx, n, V);
+    hipLaunchKernelGGL(check_indices_kernel, dim3((unsigned)bx), dim3(256), 0, stream, idx, n, V,
+                       (int64_t)(padded ? -1 : 0));
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     e = hipMemcpyFromSymbolAsync(bad_out, HIP_SYMBOL(g_bad_indices), sizeof(unsigned), 0, hipMemcpyDeviceToHost,

@@ -494,7 +494,7 @@ __global__ __launch_bounds__(kSelThreads) void resolve_kernel(int64_t V, int64_t
 // one-block launch -- redundant work, one launch less on the critical path
 __global__ __launch_bounds__(kSelThreads) void emit_kernel(const float* s_all, int64_t V, int64_t k,
                                                            uint32_t* scratch, int rows, int32_t* idx_out,
-                                                           float* scores_out) {
+                                                           float* scores_out, float tau) {
     __shared__ uint32_t s_w[kSelWaves];
     __shared__ ResolveSmem sm;
     __shared__ uint32_t s_off;
@@ -528,8 +528,9 @@ __global__ __launch_bounds__(kSelThreads) void emit_kernel(const float* s_all, i
     for (int i = 0; i < kEpt; ++i) {
         if (mask & (1u << i)) {
             if (pos < (uint32_t)k) {                      // always true for a consistent threshold
-                out[pos] = (int32_t)(v0 + i);
-                if (scores_out) scores_out[r * k + pos] = val[i];
+                const bool keep = val[i] >= tau;          // below the threshold: a padding slot
+                out[pos] = keep ? (int32_t)(v0 + i) : -1;
+                if (scores_out) scores_out[r * k + pos] = keep ? val[i] : -INFINITY;
             }
             ++pos;
         }
@@ -542,7 +543,7 @@ __global__ __launch_bounds__(kSelThreads) void emit_kernel(const float* s_all, i
 // is (group round j, thread, element): one packed prefix sum per two rounds places every id.
 __global__ __launch_bounds__(kRowThreads) void emit_rows_kernel(const float* s_all, int64_t V, int64_t k,
                                                                 uint32_t* scratch, int rows, int32_t* idx_out,
-                                                                float* scores_out) {
+                                                                float* scores_out, float tau) {
     constexpr int kRounds = kRowEpt / 4;                  // 4
     static_assert(kRounds == 4, "two packed scans cover four rounds");
     __shared__ uint32_t s_w[kRowWaves];
@@ -602,8 +603,9 @@ __global__ __launch_bounds__(kRowThreads) void emit_rows_kernel(const float* s_a
         for (int e = 0; e < 4; ++e) {
             if (mask[j] & (1u << e)) {
                 if (q < (uint32_t)k) {                    // always true for a consistent threshold
-                    out[q] = (int32_t)(v0 + e);
-                    if (scores_out) scores_out[r * k + q] = val[j][e];
+                    const bool keep = val[j][e] >= tau;   // below the threshold: a padding slot
+                    out[q] = keep ? (int32_t)(v0 + e) : -1;
+                    if (scores_out) scores_out[r * k + q] = keep ? val[j][e] : -INFINITY;
                 }
                 ++q;
             }
@@ -654,7 +656,7 @@ hipError_t launch_topk_of_scores(const RadixArgs& a, hipStream_t stream) {
     if (a.rows <= 4) {
         hipLaunchKernelGGL(collect_kernel, grid, dim3(kSelThreads), 0, stream, a.s, a.V, a.k, a.scratch, a.rows);
         hipLaunchKernelGGL(emit_kernel, grid, dim3(kSelThreads), 0, stream, a.s, a.V, a.k, a.scratch, a.rows,
-                           a.idx_out, a.scores_out);
+                           a.idx_out, a.scores_out, a.tau);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(locate_kernel, dim3((unsigned)a.rows), dim3(kSelThreads), 0, stream, a.V, a.k, a.scratch,
@@ -663,7 +665,7 @@ hipError_t launch_topk_of_scores(const RadixArgs& a, hipStream_t stream) {
     hipLaunchKernelGGL(resolve_kernel, dim3((unsigned)a.rows), dim3(kSelThreads), 0, stream, a.V, a.k, a.scratch,
                        a.rows);
     hipLaunchKernelGGL(emit_rows_kernel, grid, dim3(kRowThreads), 0, stream, a.s, a.V, a.k, a.scratch, a.rows,
-                       a.idx_out, a.scores_out);
+                       a.idx_out, a.scores_out, a.tau);
     return hipGetLastError();
 }
 

@@ -39,8 +39,9 @@ struct GemvArgs {
 };
 hipError_t launch_gemv(int dt, const GemvArgs& a, hipStream_t stream);
 
-// debug aid: number of entries of idx[0..n) outside [0, V); synchronises the stream
-hipError_t count_bad_indices(const int32_t* idx, int64_t n, int64_t V, hipStream_t stream, unsigned* bad_out);
+// debug aid: number of entries of idx[0..n) outside [0, V) (padded: -1 is allowed); synchronises the stream
+hipError_t count_bad_indices(const int32_t* idx, int64_t n, int64_t V, bool padded, hipStream_t stream,
+                             unsigned* bad_out);
 
 // copies rows M[idx[j], :] (j < n_sets * k) into a dense [n_sets * k x chunks * 16 B] matrix
 hipError_t launch_materialize_rows(const char* M, int64_t m_row_bytes, const int32_t* idx, int64_t n_rows,
@@ -59,6 +60,12 @@ hipError_t launch_tile_mfma(const GemvArgs& a, hipStream_t stream);
 // in place: s[r, :] <- log softmax(s[r, :]) for rows of V float32 scores; partial: log_softmax_ws_floats floats
 size_t log_softmax_ws_floats(int64_t rows, int64_t V);
 hipError_t launch_log_softmax_rows(float* s, int64_t V, int rows, float* partial, hipStream_t stream);
+
+// Index lists with padding slots (-1): clean[p] = max(idx[p], 0), and afterwards
+// logits[r, j] = -inf wherever idx(r, j) < 0 (idx_row_stride 0: one list for every row)
+hipError_t launch_pad_clean(const int32_t* idx, int64_t n, int32_t* clean, hipStream_t stream);
+hipError_t launch_pad_mask(const int32_t* idx, int64_t idx_row_stride, int rows, int64_t k, float* logits,
+                           hipStream_t stream);
 
 // Per-row index sets for several hidden rows (a draft tree): the union of the sets is formed on the
 // device, every row of M in the union is read once and multiplied with all hidden rows on the matrix
@@ -91,6 +98,7 @@ struct RadixArgs {
     int64_t k;
     int32_t* idx_out;      // [rows x k]
     float* scores_out;     // [rows x k] or nullptr
+    float tau;             // selected entries scoring below tau are emitted as padding (-1, -inf); -inf: none
     uint32_t* scratch;     // select_scratch_words(rows, V) uint32 words; the first
                            // select_zero_range() words must be zero before the histogram pass
 };

@@ -110,7 +110,10 @@ __device__ __forceinline__ void softmax_topk_block(const TopkArgs& a, const int6
     const int src = __ffsll((long long)pick) - 1;
     uint32_t L = (uint32_t)__builtin_amdgcn_readlane((int)mytag, src) & ~63u;
     if (L == 0u) L = 1u;                                      // never admit the "no element" key
-    const float zmax = ord_to_f32(zmaxkey);
+    // padding slots carry -inf (probability 0); a row of nothing else has all probabilities 0
+    constexpr uint32_t kNegInfKey = 0x007FFFFFu;              // f32_to_ord(-inf)
+    const bool empty = zmaxkey <= kNegInfKey;
+    const float zmax = empty ? 0.0f : ord_to_f32(zmaxkey);
 
     // ---- 3. candidates >= L into LDS; softmax denominator over everything
     float part = 0.0f;
@@ -135,8 +138,11 @@ __device__ __forceinline__ void softmax_topk_block(const TopkArgs& a, const int6
     float tot = 0.0f;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) tot += s_part[w];
-    const float inv = 1.0f / tot;
+    const float inv = empty ? 0.0f : 1.0f / tot;
     const uint32_t n = s_count;
+    auto prob_of = [&](uint64_t k64) {                        // keys at or below -inf: padding or no entry at all
+        return (uint32_t)(k64 >> 32) <= kNegInfKey ? 0.0f : __expf(key_value(k64) - zmax) * inv;
+    };
 
     if (n <= (uint32_t)kCap) {
         // ---- 4. rank the candidates by counting; ranks are unique (position breaks exact ties)
@@ -150,7 +156,7 @@ __device__ __forceinline__ void softmax_topk_block(const TopkArgs& a, const int6
             }
             if ((uint32_t)lane < n && rank < (uint32_t)kd) {
                 a.tok_out[r * kd + rank] = key_token(mine);
-                a.prob_out[r * kd + rank] = __expf(key_value(mine) - zmax) * inv;
+                a.prob_out[r * kd + rank] = prob_of(mine);
             }
         } else if (wave == 0) {
             for (uint32_t i = lane; i < n; i += 64) {
@@ -162,7 +168,7 @@ __device__ __forceinline__ void softmax_topk_block(const TopkArgs& a, const int6
                 }
                 if (rank < (uint32_t)kd) {
                     a.tok_out[r * kd + rank] = key_token(mine);
-                    a.prob_out[r * kd + rank] = __expf(key_value(mine) - zmax) * inv;
+                    a.prob_out[r * kd + rank] = prob_of(mine);
                 }
             }
         }
@@ -191,7 +197,7 @@ __device__ __forceinline__ void softmax_topk_block(const TopkArgs& a, const int6
             __syncthreads();
             if (tid == 0) {
                 a.tok_out[r * kd + t] = key_token(best);
-                a.prob_out[r * kd + t] = __expf(key_value(best) - zmax) * inv;
+                a.prob_out[r * kd + t] = prob_of(best);
             }
             prev = best;
         }

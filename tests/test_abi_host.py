@@ -74,7 +74,7 @@ def test_subset_logits_rejects_bad_arguments(lib):
     assert call(h=None) == 1 and call(U=None) == 1 and call(idx=None) == 1 and call(out=None) == 1
     assert call(rows=0) == 2 and call(k=0) == 2 and call(V=0) == 2
     assert call(ldh=128) == 2 and call(ldu=255) == 2
-    assert call(dt=7) == 3 and call(mode=5) == 3
+    assert call(dt=7) == 3 and call(mode=2) == 3 and call(mode=9) == 3      # 4 and 5 are the padded modes
     assert call(d=252, ldh=252, ldu=252) == 6             # row not a whole number of 16-byte units
     assert call(ldu=260) == 4                              # stride not 16-byte aligned
     assert call(h=MIS) == 4 and call(U=MIS) == 4
@@ -101,6 +101,16 @@ def test_dense_select_topk_reject_bad_arguments(lib):
     assert n(A, 1, 256, 256, A, 1000, 256, 1, A, 100, 0, A, None, 0, None) == 5          # needs its workspace
     assert n(A, 1, 256, 256, A, 1000, 256, 1, None, 100, 0, A, A, 1 << 30, None) == 1
     assert sv.workspace_bytes(sv.SV_OP_INDEXED_HEAD_NAIVE, 2, 4096, 128256, 8192) == 2 * 8192 * 4096 * 2
+
+    st = lib.specvocab_select_threshold
+    assert st(A, 1, 256, 256, A, 32, A, 1000, 1, 10, float("nan"), A, None, A, 1 << 30, None) == 2
+    assert st(A, 1, 256, 256, A, 32, A, 1000, 1, 10, 0.5, None, None, A, 1 << 30, None) == 1
+    # a padded list needs room for its clean copy; the comparator takes plain lists only
+    plain = sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 1, 4096, 128256, 8192)
+    assert sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 1, 4096, 128256, 8192, idx_mode=sv.SV_IDX_PADDED) == plain + 8192 * 4
+    assert lib.specvocab_subset_logits(A, 1, 256, 256, A, 1000, 256, 1, A, 100, 4, A, None, 0, None) == 5
+    assert lib.specvocab_indexed_head_naive(A, 1, 256, 256, A, 1000, 256, 1, A, 100, 4, A, A, 1 << 30, None) == 6
+    assert lib.specvocab_subset_logits(A, 1, 256, 256, A, 1000, 256, 1, A, 100, 2, A, None, 0, None) == 3
 
     q = lib.specvocab_aux_log_softmax
     assert q(A, 1, 256, 256, A, 32, A, 1000, 1, None, A, 1 << 30, None) == 1

@@ -436,6 +436,92 @@ def test_aux_log_softmax(dtype, rows, d, dp, V):
     assert np.abs(lse).max() < 5e-5, lse
 
 
+PADDED_SHAPES = [
+    # dtype, rows, d, V, k, mode          (which kernel family the clean copy goes through)
+    ("bf16", 1, 1024, 9000, 2048, "per_row"),     # row gather
+    ("f32", 2, 264, 900, 100, "per_row"),
+    ("bf16", 6, 1024, 5000, 700, "per_step"),     # matrix cores, one shared padded list
+    ("bf16", 20, 512, 6000, 1100, "per_row"),     # union of sets
+    ("bf16", 70, 256, 3000, 300, "per_step"),     # tiled matrix-core kernel
+]
+
+
+@pytest.mark.parametrize("dtype,rows,d,V,k,mode", PADDED_SHAPES)
+def test_padded_index_lists(dtype, rows, d, V, k, mode):
+    """SV_IDX_PADDED: padding slots (-1) give -inf logits and probability 0; the real entries and the
+    draft tokens are those of the oracle on the same padded list."""
+    say(f"padded lists {dtype} rows={rows} d={d} V={V} k={k} {mode}")
+    rng = np.random.default_rng(rows * 31 + k)
+    U, h = rand(rng, (V, d), 0.02, dtype), rand(rng, (rows, d), 1.0, dtype)
+    shape = (k,) if mode == "per_step" else (rows, k)
+    idx = (rng.permutation(V)[:k] if mode == "per_step"
+           else np.stack([rng.permutation(V)[:k] for _ in range(rows)])).astype(np.int32)
+    idx = np.where(rng.random(shape) < 0.3, -1, idx).astype(np.int32)       # 30 % padding
+    if mode == "per_row":
+        idx[0, :] = -1
+        idx[0, k // 2] = 17                                                   # a row with a single real entry
+    tU, th, tidx = to_dev(U), to_dev(h), torch.from_numpy(idx).to(DEV)
+    z = sv.subset_logits(th, tU, tidx, padded=True).cpu().numpy()
+    z_ref = oracle.subset_logits(h, U, idx)
+    pad = np.broadcast_to(idx < 0, z.shape)
+    assert np.all(np.isneginf(z[pad])) and np.all(np.isneginf(z_ref[pad]))
+    assert_logits_close(z[~pad], z_ref[~pad], dtype, "logits of the real entries")
+    kd = 5
+    zz, tok, prob, q = sv.draft_step(th, tU, tidx, kd, want_probs=True, padded=True)
+    assert np.array_equal(np.isneginf(zz.cpu().numpy()), pad)
+    tok_ref, prob_ref, q_ref = oracle.softmax_topk(zz.cpu().numpy(), idx, kd, full=True)
+    assert np.array_equal(tok.cpu().numpy(), tok_ref)
+    np.testing.assert_allclose(prob.cpu().numpy(), prob_ref, rtol=2e-5, atol=1e-9)
+    np.testing.assert_allclose(q.cpu().numpy(), q_ref, rtol=2e-5, atol=1e-9)
+    if mode == "per_row":                                                     # one real entry, kd = 5
+        assert tok_ref[0].tolist() == [17, -1, -1, -1, -1] and prob_ref[0, 0] == 1.0
+
+
+def test_empty_rows_and_draft_topk_on_padding():
+    """A row of padding only: all probabilities 0, tokens -1 (through the slow exact path as well)."""
+    say("draft top-kd on rows of padding")
+    k, kd = 3000, 8
+    z = np.full((3, k), -np.inf, dtype=np.float32)
+    idx = np.full((3, k), -1, dtype=np.int32)
+    z[1, 5], idx[1, 5] = 2.0, 40                    # one real entry among 2999 padding slots
+    z[2, :4], idx[2, :4] = [0.5, 0.25, 0.5, -1.0], [9, 8, 7, 6]
+    tok, prob, q = sv.draft_topk(torch.from_numpy(z).to(DEV), torch.from_numpy(idx).to(DEV), kd, want_probs=True)
+    tok_ref, prob_ref, q_ref = oracle.softmax_topk(z, idx, kd, full=True)
+    assert np.array_equal(tok.cpu().numpy(), tok_ref)
+    np.testing.assert_allclose(prob.cpu().numpy(), prob_ref, rtol=2e-5, atol=0)
+    np.testing.assert_allclose(q.cpu().numpy(), q_ref, rtol=2e-5, atol=0)
+    assert tok_ref[0].tolist() == [-1] * kd and tok_ref[2].tolist()[:4] == [7, 9, 8, 6]
+
+
+@pytest.mark.parametrize("rows", [1, 7])
+def test_select_threshold_pads_in_place(rows):
+    """specvocab_select_threshold: the plain selection with the entries scoring below tau turned into
+    padding slots, then usable as a padded list."""
+    say(f"select with a score threshold rows={rows}")
+    rng = np.random.default_rng(90 + rows)
+    d, dp, V, k = 512, 64, 7000, 900
+    h, Wd, Wv = rand(rng, (rows, d), 1.0, "bf16"), rand(rng, (dp, d), 0.05, "bf16"), rand(rng, (V, dp), 0.05, "bf16")
+    U = rand(rng, (V, d), 0.02, "bf16")
+    th, tWd, tWv = to_dev(h), to_dev(Wd), to_dev(Wv)
+    idx, sc = sv.select(th, tWd, tWv, k, want_scores=True)
+    tau = float(np.median(sc.cpu().numpy()))
+    idx_t, sc_t = sv.select(th, tWd, tWv, k, want_scores=True, tau=tau)
+    keep = sc >= tau
+    assert torch.equal(idx_t, torch.where(keep, idx, torch.full_like(idx, -1)))
+    assert torch.equal(sc_t, torch.where(keep, sc, torch.full_like(sc, -float("inf"))))
+    assert 0 < int(keep.sum()) < keep.numel()
+    # and the oracle agrees on what stays (scores within tolerance of tau may fall on either side)
+    ref_idx, ref_sc = oracle.select(h, Wd, Wv, k, tau=tau)
+    got, want = idx_t.cpu().numpy(), ref_idx
+    differ = (got != want)
+    s_ref = oracle.select(h, Wd, Wv, k, full=True)[2]
+    for r, j in zip(*np.nonzero(differ)):
+        v = got[r, j] if got[r, j] >= 0 else want[r, j]
+        assert v >= 0 and abs(s_ref[r, v] - tau) < 2e-2, (r, j, got[r, j], want[r, j])
+    z = sv.subset_logits(th, to_dev(U), idx_t, padded=True)
+    assert torch.equal(torch.isneginf(z), idx_t < 0)
+
+
 def test_k_varies_from_step_to_step():
     """Section 3.3 Step 2 allows k to change per decoding step: k is a call argument, and buffers and
     workspace sized once for the largest k serve every step."""
