@@ -174,6 +174,16 @@ def test_debug_mode_rejects_out_of_range_indices(monkeypatch):
     torch.cuda.synchronize()
     assert bool((out == 7.0).all())                      # untouched: the operation was never enqueued
     z = sv.subset_logits(h, U, good)                     # a valid list still goes through in debug mode
+    # -1 is legal exactly when the list is declared padded; anything below never is
+    with pytest.raises(sv.SpecVocabError):
+        sv.subset_logits(h, U, neg)
+    zp = sv.subset_logits(h, U, neg, padded=True)
+    assert bool(torch.isneginf(zp[0, 0])) and torch.equal(zp[1], z[1])
+    neg2 = good.clone()
+    neg2[1, 3] = -2
+    with pytest.raises(sv.SpecVocabError) as e:
+        sv.subset_logits(h, U, neg2, padded=True)
+    assert e.value.status == 7
     monkeypatch.delenv("SPECVOCAB_VALIDATE")
     assert torch.equal(z, sv.subset_logits(h, U, good))
 
