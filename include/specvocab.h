@@ -31,7 +31,8 @@
  *           except in the debug mode switched on by the environment variable SPECVOCAB_VALIDATE=1:
  *           every call that takes an index list then first runs a range check over it, waits for
  *           the stream (so the call is no longer asynchronous nor capturable), and returns
- *           SV_ERR_INDEX without launching the operation if an entry lies outside [0, V).
+ *           SV_ERR_INDEX without launching the operation if an entry lies outside [0, V) (a padding
+ *           slot, -1, is accepted in lists passed with SV_IDX_PADDED).
  * Precision.Products of the stored values are accumulated in float32 (order unspecified).
  *           With SV_BF16 storage the intermediate h' of the selector is rounded to bfloat16
  *           (round-to-nearest-even) before the second projection; with SV_F32 it stays float32.
