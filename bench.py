@@ -178,7 +178,7 @@ def other_configs(sv, torch, np, dev, capture, timed_replays):
 
 
 def indexed_head_microbenchmark(sv, torch, dev, capture, timed_replays):
-    """The paper's kernel microbenchmark in kind (Section 6, "Our kernel achieves ..."): synthetic
+    """The paper's kernel microbenchmark in kind (Section 6, the paragraph on the kernel's speed-up): synthetic
     activations and weights at model dimensions, one hidden row, graph replay; the fused row gather
     against the indexed LM head done the naive way of Figure 3a (materialise U[idx] in memory, then a
     matrix-vector product over the copy), both from this library.  Dimensions are those of public

@@ -1,7 +1,7 @@
 """Seeded synthetic workloads shaped like the paper's draft-step microbenchmark.
 
 The paper benchmarks its subset-logits kernel on synthetic activations and
-weights at each model's dimensions (Section 6, "Our kernel achieves ...").  The
+weights at each model's dimensions (Section 6, the paragraph on the kernel's speed-up).  The
 same is done here: weights ~ N(0, 0.02^2), hidden states ~ N(0, 1), and index
 sets biased towards frequent tokens (Zipf, exponent 1.1) because the candidate
 vocabulary of a language model is dominated by frequent tokens (Section 1).
