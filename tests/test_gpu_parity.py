@@ -44,6 +44,7 @@ LOGIT_SHAPES = [
     ("f32", 2, 260, 500, 64, "per_row"),
     ("f32", 1, 4096, 700, 100, "per_step"),      # 16 loads per lane, float32
     ("f32", 2, 4100, 300, 33, "per_row"),        # long-row path, float32
+    ("f32", 70, 260, 500, 64, "per_row"),        # float32 has no matrix-core path: one launch row by row
     ("bf16", 7, 1024, 5000, 1000, "per_row"),
     ("bf16", 4, 8192, 30000, 13000, "per_row"),  # few rows, enough gathered bytes for the union-of-sets path
     ("bf16", 16, 1024, 6000, 1100, "per_row"),   # 16 rows: union-of-sets path
@@ -87,11 +88,15 @@ def test_subset_and_dense_logits(dtype, rows, d, V, k, mode):
     assert_logits_close(z, oracle.subset_logits(h, U, idx, acc="f64"), dtype, "subset logits vs f64")
 
 
-def test_strided_rows():
+@pytest.mark.parametrize("rows,d,V,k", [
+    (3, 512, 700, 200),          # row kernel
+    (24, 2048, 3000, 800),       # skinny matrix-core kernels (shared set: reduction split; dense: streamed)
+    (90, 512, 1500, 400),        # tiled matrix-core kernel
+])
+def test_strided_rows(rows, d, V, k):
     """h and U taken as column slices of wider matrices (row stride > d)."""
-    say("strided rows")
+    say(f"strided rows rows={rows}")
     rng = np.random.default_rng(5)
-    rows, d, V, k = 3, 512, 700, 200
     Uw = rand(rng, (V, d + 64), 0.02, "bf16")
     hw = rand(rng, (rows, d + 8), 1.0, "bf16")
     idx = np.stack([rng.permutation(V)[:k] for _ in range(rows)]).astype(np.int32)
@@ -100,6 +105,8 @@ def test_strided_rows():
     zd = sv.dense_logits(th, tU).cpu().numpy()
     assert_logits_close(z, oracle.subset_logits(hw[:, :d], Uw[:, :d], idx), "bf16")
     assert_logits_close(zd, oracle.dense_logits(hw[:, :d], Uw[:, :d]), "bf16")
+    zs = sv.subset_logits(th, tU, torch.from_numpy(idx[0]).to(DEV)).cpu().numpy()      # one shared set
+    assert_logits_close(zs, oracle.subset_logits(hw[:, :d], Uw[:, :d], idx[0]), "bf16")
 
 
 def test_duplicate_and_unsorted_indices_are_just_gathered():
