@@ -435,6 +435,7 @@ AUX_SHAPES = [
     ("bf16", 20, 2048, 128, 9000),       # matrix-core projections
     ("bf16", 80, 512, 64, 5000),         # tiled matrix-core scores
     ("bf16", 2, 256, 8, 1),              # V = 1: log q = 0
+    ("bf16", 1, 16, 8, 5000000),         # past the selection's vocabulary limit: larger vocabulary blocks
 ]
 
 
