@@ -528,6 +528,9 @@ def test_select_threshold_pads_in_place(rows):
     assert torch.equal(idx_t, torch.where(keep, idx, torch.full_like(idx, -1)))
     assert torch.equal(sc_t, torch.where(keep, sc, torch.full_like(sc, -float("inf"))))
     assert 0 < int(keep.sum()) < keep.numel()
+    tau_eq = float(sc[0, 5])                                 # inclusive: a token scoring exactly tau stays
+    idx_e, _ = sv.select(th, tWd, tWv, k, tau=tau_eq)
+    assert int(idx_e[0, 5]) == int(idx[0, 5]) and torch.equal(idx_e, torch.where(sc >= tau_eq, idx, torch.full_like(idx, -1)))
     # and the oracle agrees on what stays (scores within tolerance of tau may fall on either side)
     ref_idx, ref_sc = oracle.select(h, Wd, Wv, k, tau=tau)
     got, want = idx_t.cpu().numpy(), ref_idx

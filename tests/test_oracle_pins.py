@@ -554,6 +554,11 @@ def test_score_threshold_pads_the_selected_list_in_place():
     assert np.array_equal(idx_t, np.where(keep, idx, -1))
     assert np.array_equal(sc_t, np.where(keep, sc, -np.inf))
     assert 0 < keep.sum() < keep.size
+    # the threshold is inclusive: a token scoring exactly tau stays
+    tau_eq = float(sc[1, 7])
+    idx_e, sc_e = oracle.select(h, Wd, Wv, k, tau=tau_eq)
+    assert idx_e[1, 7] == idx[1, 7] and sc_e[1, 7] == tau_eq
+    assert np.array_equal(idx_e, np.where(sc >= tau_eq, idx, -1))
     # tau = -inf is the plain selection; tau above every score empties the lists
     assert np.array_equal(oracle.select(h, Wd, Wv, k, tau=-np.inf)[0], idx)
     assert np.all(oracle.select(h, Wd, Wv, k, tau=1e30)[0] == -1)
