@@ -2,9 +2,12 @@
 //
 // One wavefront owns one (or RPI) whole rows of the matrix at a time: the 64 lanes read the row
 // as consecutive 16-byte units (one global_load_dwordx4 per 1 KiB), so every byte of a gathered
-// row is fetched exactly once and in full cache lines.  The hidden-state row is held in
-// registers in the same lane layout for the whole life of the wave.  Products are accumulated
-// per lane in float32 and reduced across the wave with DPP row operations.
+// row is fetched exactly once and in full cache lines.  Products are accumulated per lane in
+// float32 and reduced across the wave with DPP row operations.
+//   gemv_rows_once_kernel   rows of 3 to 16 KiB: one row per wavefront, the hidden-state row in LDS
+//   gemv_rows_kernel        shorter rows: several rows per wavefront and a loop, the hidden-state row
+//                           in registers in the same lane layout for the whole life of the wave
+//   gemv_long_rows_kernel   longer rows, walked in 1 KiB pieces
 #include "sv_device.h"
 #include "sv_launch.h"
 
@@ -89,6 +92,65 @@ __global__ __launch_bounds__(256) void gemv_rows_kernel(const GemvArgs a) {
         finish(w);
     }
 
+    if (a.zero_words) {     // clear a later kernel's scratch with this launch
+        const size_t nthr = (size_t)gridDim.x * gridDim.y * blockDim.x;
+        for (size_t i = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x; i < a.zero_words;
+             i += nthr)
+            a.zero_ptr[i] = 0u;
+    }
+}
+
+// One row per wavefront and one wavefront per item, rows of up to NL * 64 units (NL = 4 .. 16).  The
+// hidden-state row waits in LDS instead of registers, which halves the registers of a wavefront: all
+// wavefronts of a short gather are resident at once, so the index -> row round trip is paid once, and a
+// long product simply streams workgroup after workgroup.  Loads are branch-free: units past the end of
+// a row are clamped to its last unit and meet zeros in the staged hidden row (FULL: rows of exactly
+// NL * 64 units, nothing to clamp -- the address arithmetic in front of the first requests is worth 1 %).
+constexpr int kOnceWaves = 4;       // measured: 2, 8 and 16 wavefronts per workgroup are all 1-5 % slower
+template <int DT, int NL, bool OUT_BF16, bool FULL>
+__global__ __launch_bounds__(kOnceWaves * 64) void gemv_rows_once_kernel(const GemvArgs a) {
+    constexpr int kT = kOnceWaves * 64;
+    constexpr int kUnits = NL * 64;
+    constexpr int kRounds = (kUnits + kT - 1) / kT;
+    __shared__ u32x4 s_x[kUnits];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t r = blockIdx.y;
+    const int64_t n = a.n_items;
+    const int last = a.chunks - 1;
+    const int64_t it = (int64_t)blockIdx.x * kOnceWaves + wave;
+
+    // request order as in gemv_rows_kernel: hidden row, scalar index, row of the matrix
+    const u32x4* xp = reinterpret_cast<const u32x4*>(a.x + r * a.x_row_bytes);
+    u32x4 xs[kRounds];
+    int unit[kRounds];
+#pragma unroll
+    for (int q = 0; q < kRounds; ++q) {
+        unit[q] = q * kT + tid < kUnits ? q * kT + tid : kUnits - 1;   // spare threads: the last unit once more
+        xs[q] = xp[FULL || unit[q] < last ? unit[q] : last];
+    }
+    const int64_t item = it < n ? it : n - 1;          // tail: recompute the last item, never stored
+    const int64_t row = a.idx ? (int64_t)a.idx[r * a.idx_row_stride + item] : item;
+    const u32x4* mp = reinterpret_cast<const u32x4*>(a.M + row * a.m_row_bytes);
+    u32x4 w[NL];
+#pragma unroll
+    for (int c = 0; c < NL; ++c) {
+        const int ch = c * 64 + lane;
+        w[c] = load16<true>(mp + (FULL || ch < last ? ch : last));
+    }
+    __builtin_amdgcn_sched_barrier(0);                 // every row request leaves before anything waits
+#pragma unroll
+    for (int q = 0; q < kRounds; ++q) s_x[unit[q]] = FULL || unit[q] <= last ? xs[q] : zero16();
+    __syncthreads();
+    float part[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int c = 0; c < NL; ++c) part[c & 3] = dot16<DT>(w[c], s_x[c * 64 + lane], part[c & 3]);
+    const float acc = wave_sum((part[0] + part[1]) + (part[2] + part[3]));
+    if (lane == 0 && it < n) {
+        if constexpr (OUT_BF16) a.out_bf16[r * a.out_row_stride + it] = f32_to_bf16_rne(acc);
+        else a.out_f32[r * a.out_row_stride + it] = acc;
+    }
     if (a.zero_words) {     // clear a later kernel's scratch with this launch
         const size_t nthr = (size_t)gridDim.x * gridDim.y * blockDim.x;
         for (size_t i = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x; i < a.zero_words;
@@ -189,18 +251,42 @@ hipError_t launch_rows(const GemvArgs& a, int cus, hipStream_t stream) {
     return hipGetLastError();
 }
 
+template <int DT, int NL>
+hipError_t launch_once(const GemvArgs& a, hipStream_t stream) {
+    dim3 grid((unsigned)((a.n_items + kOnceWaves - 1) / kOnceWaves), (unsigned)a.rows, 1), block(kOnceWaves * 64, 1, 1);
+    const bool full = a.chunks == NL * 64;
+    if (a.out_bf16) {
+        if (full) hipLaunchKernelGGL((gemv_rows_once_kernel<DT, NL, true, true>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((gemv_rows_once_kernel<DT, NL, true, false>), grid, block, 0, stream, a);
+    } else {
+        if (full) hipLaunchKernelGGL((gemv_rows_once_kernel<DT, NL, false, true>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((gemv_rows_once_kernel<DT, NL, false, false>), grid, block, 0, stream, a);
+    }
+    return hipGetLastError();
+}
+
 template <int DT>
 hipError_t launch_dt(const GemvArgs& a, int cus, hipStream_t stream) {
     const int nl = (a.chunks + 63) / 64;
+    switch (nl) {
+        case 4: return launch_once<DT, 4>(a, stream);
+        case 5: return launch_once<DT, 5>(a, stream);
+        case 6: return launch_once<DT, 6>(a, stream);
+        case 7: return launch_once<DT, 7>(a, stream);
+        case 8: return launch_once<DT, 8>(a, stream);
+        case 9: return launch_once<DT, 9>(a, stream);
+        case 10: return launch_once<DT, 10>(a, stream);
+        case 11: return launch_once<DT, 11>(a, stream);
+        case 12: return launch_once<DT, 12>(a, stream);
+        case 13: return launch_once<DT, 13>(a, stream);
+        case 14: return launch_once<DT, 14>(a, stream);
+        case 15: return launch_once<DT, 15>(a, stream);
+        case 16: return launch_once<DT, 16>(a, stream);
+        default: break;
+    }
     if (nl <= 1) return launch_rows<DT, 1, 4>(a, cus, stream);
     if (nl <= 2) return launch_rows<DT, 2, 4>(a, cus, stream);
-    if (nl <= 4) return launch_rows<DT, 4, 2>(a, cus, stream);
-    if (nl <= 8) {
-        // a short gather (one pass of the chip) runs slightly faster with one row per wavefront
-        if (a.n_items <= (int64_t)cus * 32) return launch_rows<DT, 8, 1>(a, cus, stream);
-        return launch_rows<DT, 8, 2>(a, cus, stream);
-    }
-    if (nl <= 16) return launch_rows<DT, 16, 1>(a, cus, stream);
+    if (nl <= 3) return launch_rows<DT, 4, 2>(a, cus, stream);
     int64_t bx = (a.n_items + 3) / 4;
     const int64_t cap = ((int64_t)cus * 8 + a.rows - 1) / a.rows;
     if (bx > cap) bx = cap;
