@@ -46,6 +46,14 @@ LOGIT_SHAPES = [
     ("f32", 2, 4100, 300, 33, "per_row"),        # long-row path, float32
     ("f32", 70, 260, 500, 64, "per_row"),        # float32 has no matrix-core path: one launch row by row
     ("bf16", 7, 1024, 5000, 1000, "per_row"),
+    # one row per wavefront, hidden row in LDS: rows of 3 to 16 KiB, whole and ragged numbers of 1 KiB pieces
+    ("bf16", 1, 3840, 3000, 333, "per_row"),     # 480 units: 8 loads per lane, the last one half empty
+    ("bf16", 3, 1544, 900, 200, "per_row"),      # 193 units: 4 loads per lane, the last one a single unit
+    ("f32", 1, 2052, 700, 100, "per_row"),       # 513 units: 9 loads per lane
+    ("bf16", 1, 8184, 500, 129, "per_row"),      # 1023 units: 16 loads per lane, one unit short
+    ("bf16", 2, 5120, 800, 300, "per_row"),      # 640 units: 10 whole loads per lane
+    ("bf16", 1, 3584, 600, 100, "per_row"),      # 448 units: 7 whole loads per lane
+    ("f32", 1, 1536, 601, 601, "per_step"),      # 384 units: 6 whole loads per lane, k = V, odd item count
     ("bf16", 4, 8192, 30000, 13000, "per_row"),  # few rows, enough gathered bytes for the union-of-sets path
     ("bf16", 16, 1024, 6000, 1100, "per_row"),   # 16 rows: union-of-sets path
     ("bf16", 60, 520, 3000, 600, "per_row"),     # a tree's worth of rows, ragged reduction slice
