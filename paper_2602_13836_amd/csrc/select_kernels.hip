@@ -30,6 +30,8 @@
 #include "sv_device.h"
 #include "sv_launch.h"
 
+#include <type_traits>
+
 namespace sv {
 
 namespace {
@@ -118,9 +120,14 @@ __device__ __forceinline__ void locate_bin(const uint32_t (&c)[PER], uint32_t re
 // ------------------------------------------------------------------------------------------
 // scores (+ histogram)
 // ------------------------------------------------------------------------------------------
-template <int DT, int G, int UNR>
+// FULL: a selector row is exactly G units, so the UNR loads of a wavefront sit at compile-time offsets
+// from one base address.  Loads are branch-free and all leave before the first product: a window that
+// would run past the last row is moved back to end at it (rows it re-computes are not stored or counted
+// again); vocabularies shorter than one window clamp row by row instead.
+template <int DT, int G, int UNR, bool FULL>
 __global__ __launch_bounds__(kScoreThreads) void scores_hist_kernel(const ScoresArgs a, uint32_t* scratch) {
     constexpr int RPW = 64 / G;                       // vocabulary rows per wave-wide load
+    constexpr int64_t kWindow = (int64_t)RPW * UNR;   // rows per wavefront and iteration
     __shared__ uint32_t lh[kHistBins];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -128,43 +135,58 @@ __global__ __launch_bounds__(kScoreThreads) void scores_hist_kernel(const Scores
     const int g = lane % G;                           // 16-byte unit within the row
     const int sub = lane / G;                         // which of the RPW rows
     const int64_t r = blockIdx.y;
-    const int C = a.chunks;
+    const int C = FULL ? G : a.chunks;
     const int64_t V = a.V;
     const int64_t row_bytes = (int64_t)C * 16;
 
     for (int b = tid; b < kHistBins; b += kScoreThreads) lh[b] = 0u;
-    const u32x4 xreg = g < C ? reinterpret_cast<const u32x4*>(a.hp + r * row_bytes)[g] : zero16();
+    const int gc = (FULL || g < C) ? g : C - 1;
+    const u32x4 xraw = reinterpret_cast<const u32x4*>(a.hp + r * row_bytes)[gc];
+    const u32x4 xreg = (FULL || g < C) ? xraw : zero16();   // units past the end of a row meet zeros
     float* s = a.s + r * V;
     __syncthreads();
 
-    const int64_t per_iter = (int64_t)RPW * UNR;
-    const int64_t step = (int64_t)gridDim.x * kScoreWaves * per_iter;
-    for (int64_t base = ((int64_t)blockIdx.x * kScoreWaves + wave) * per_iter; base < V; base += step) {
-        u32x4 w[UNR];
+    const int64_t step = (int64_t)gridDim.x * kScoreWaves * kWindow;
+    // two copies of the loop (a branch around the loads inside one loop makes the compiler wait for
+    // everything in flight, the previous iteration's stores included)
+    auto run = [&](auto tiny_tag) {
+        constexpr bool TINY = decltype(tiny_tag)::value;
+        for (int64_t base = ((int64_t)blockIdx.x * kScoreWaves + wave) * kWindow; base < V; base += step) {
+            const int64_t b0 = (TINY || base + kWindow <= V) ? base : V - kWindow;
+            u32x4 w[UNR];
+            if constexpr (!TINY) {
+                const char* p = a.Wv + (b0 + sub) * row_bytes + (int64_t)gc * 16;
 #pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            const int64_t v = base + (int64_t)u * RPW + sub;
-            w[u] = (v < V && g < C)
-                       ? load16<false>(reinterpret_cast<const u32x4*>(a.Wv + v * row_bytes) + g)
-                       : zero16();
-        }
+                for (int u = 0; u < UNR; ++u)
+                    w[u] = load16<false>(reinterpret_cast<const u32x4*>(p + (int64_t)u * RPW * row_bytes));
+            } else {
 #pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            float acc = dot16<DT>(w[u], xreg, 0.0f);
-            // sum over the G lanes of the group (G is a power of two, groups are lane-aligned)
-            if constexpr (G >= 2) acc += dpp_f32<DPP_QUAD_1032>(acc);
-            if constexpr (G >= 4) acc += dpp_f32<DPP_QUAD_2301>(acc);
-            if constexpr (G >= 8) acc += dpp_f32<DPP_ROW_HALF_MIRROR>(acc);
-            if constexpr (G >= 16) acc += dpp_f32<DPP_ROW_MIRROR>(acc);
-            if constexpr (G >= 32) acc += __shfl_xor(acc, 16);
-            if constexpr (G >= 64) acc += __shfl_xor(acc, 32);
-            const int64_t v = base + (int64_t)u * RPW + sub;
-            if (g == 0 && v < V) {
-                s[v] = acc;
-                atomicAdd(&lh[f32_to_ord(acc) >> kKeyLowBits], 1u);
+                for (int u = 0; u < UNR; ++u) {
+                    const int64_t v = b0 + (int64_t)u * RPW + sub;
+                    w[u] = load16<false>(reinterpret_cast<const u32x4*>(a.Wv + (v < V ? v : V - 1) * row_bytes) + gc);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);        // every request leaves before anything waits
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                float acc = dot16<DT>(w[u], xreg, 0.0f);
+                // sum over the G lanes of the group (G is a power of two, groups are lane-aligned)
+                if constexpr (G >= 2) acc += dpp_f32<DPP_QUAD_1032>(acc);
+                if constexpr (G >= 4) acc += dpp_f32<DPP_QUAD_2301>(acc);
+                if constexpr (G >= 8) acc += dpp_f32<DPP_ROW_HALF_MIRROR>(acc);
+                if constexpr (G >= 16) acc += dpp_f32<DPP_ROW_MIRROR>(acc);
+                if constexpr (G >= 32) acc += __shfl_xor(acc, 16);
+                if constexpr (G >= 64) acc += __shfl_xor(acc, 32);
+                const int64_t v = b0 + (int64_t)u * RPW + sub;
+                if (g == 0 && v >= base && v < V) {
+                    s[v] = acc;
+                    atomicAdd(&lh[f32_to_ord(acc) >> kKeyLowBits], 1u);
+                }
             }
         }
-    }
+    };
+    if (V < kWindow) run(std::true_type{});
+    else run(std::false_type{});
     __syncthreads();
 
     const SelLayout L = sel_layout(V, a.rows);
@@ -228,8 +250,12 @@ hipError_t launch_scores_g(const ScoresArgs& a, uint32_t* scratch, int cus, hipS
     int64_t cap = ((int64_t)cus + a.rows - 1) / a.rows;         // one long-lived block per CU
     if (cap < 1) cap = 1;
     if (bx > cap) bx = cap;
-    hipLaunchKernelGGL((scores_hist_kernel<DT, G, UNR>), dim3((unsigned)bx, (unsigned)a.rows),
-                       dim3(kScoreThreads), 0, stream, a, scratch);
+    if (a.chunks == G)
+        hipLaunchKernelGGL((scores_hist_kernel<DT, G, UNR, true>), dim3((unsigned)bx, (unsigned)a.rows),
+                           dim3(kScoreThreads), 0, stream, a, scratch);
+    else
+        hipLaunchKernelGGL((scores_hist_kernel<DT, G, UNR, false>), dim3((unsigned)bx, (unsigned)a.rows),
+                           dim3(kScoreThreads), 0, stream, a, scratch);
     return hipGetLastError();
 }
 
