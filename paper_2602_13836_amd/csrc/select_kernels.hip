@@ -436,16 +436,26 @@ __device__ __forceinline__ void resolve_row(const SelPtrs& p, const SelLayout& L
     const int tid = threadIdx.x;
     const uint32_t B = p.binfo[0];
     const uint32_t above = p.binfo[1];
-    const uint32_t n = p.state[ST_NCAND];
-    const bool in_regs = n <= (uint32_t)(kSelThreads * kCandPerThread);
 
     // candidates: 52-bit sub-keys (20 low key bits, then the inverted id); the top 12 bits are all B
     constexpr uint64_t kSubMask = (1ull << 52) - 1ull;
     uint64_t sk[kCandPerThread];
+    // the first kSpec slots of every thread are requested before the count is known (a typical row has
+    // one to two thousand candidates): one memory round trip instead of two on the usual path
+    constexpr int kSpec = 2;
+    uint64_t spec[kSpec];
+#pragma unroll
+    for (int i = 0; i < kSpec; ++i) {
+        const int64_t j = (int64_t)i * kSelThreads + tid;
+        spec[i] = p.cand[j < L.V ? j : L.V - 1];
+    }
+    const uint32_t n = p.state[ST_NCAND];
+    const bool in_regs = n <= (uint32_t)(kSelThreads * kCandPerThread);
 #pragma unroll
     for (int i = 0; i < kCandPerThread; ++i) {
         const uint32_t j = (uint32_t)i * kSelThreads + tid;
-        sk[i] = (in_regs && j < n) ? (p.cand[j] & kSubMask) : 0ull;
+        if (i < kSpec) sk[i] = (in_regs && j < n) ? (spec[i] & kSubMask) : 0ull;
+        else sk[i] = (in_regs && j < n) ? (p.cand[j] & kSubMask) : 0ull;
     }
     auto for_each_candidate = [&](auto&& f) {
         if (in_regs) {
