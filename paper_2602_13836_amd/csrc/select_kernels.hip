@@ -65,7 +65,7 @@ __host__ __device__ inline SelLayout sel_layout(int64_t V, int64_t rows) {
     L.V = V;
     L.chunk = (int64_t)kEpt * kSelThreads;
     L.nb = (V + L.chunk - 1) / L.chunk;
-    L.replicas = rows <= 2 ? 8 : (rows <= 16 ? 2 : 1);
+    L.replicas = rows <= 2 ? 8 : (rows <= 16 ? 2 : 1);     // at most kMaxReplicas
     L.zero_words = ST_WORDS + (size_t)L.replicas * kHistBins;
     L.rest_words = 2 * (size_t)V + 2 * (size_t)L.nb + 2;
     return L;
@@ -92,6 +92,20 @@ __host__ __device__ inline SelPtrs sel_ptrs(uint32_t* base, int64_t rows, int64_
     p.offset = p.sure + L.nb;
     p.binfo = p.offset + L.nb;
     return p;
+}
+
+// c[0..4) += bins [4 * tid, 4 * tid + 4) of every replica of the histogram.  All loads leave at once: the
+// replica count varies at run time, so indices past it repeat the last replica and are not added.
+constexpr int kMaxReplicas = 8;
+__device__ __forceinline__ void sum_replicas(const uint32_t* hist, int replicas, int tid, uint32_t (&c)[4]) {
+    u32x4 q[kMaxReplicas];
+#pragma unroll
+    for (int rep = 0; rep < kMaxReplicas; ++rep)
+        q[rep] = reinterpret_cast<const u32x4*>(hist + (size_t)(rep < replicas ? rep : replicas - 1) * kHistBins)[tid];
+#pragma unroll
+    for (int rep = 0; rep < kMaxReplicas; ++rep)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c[i] += rep < replicas ? q[rep][i] : 0u;
 }
 
 // Histogram held as PER consecutive bins per thread (thread t owns bins [t*PER, t*PER+PER)):
@@ -284,11 +298,7 @@ __global__ __launch_bounds__(kSelThreads) void locate_kernel(int64_t V, int64_t 
     const SelPtrs p = sel_ptrs(scratch, rows, blockIdx.x, L);
     constexpr int PER = kHistBins / kSelThreads;
     uint32_t c[PER] = {0u, 0u, 0u, 0u};
-    for (int rep = 0; rep < L.replicas; ++rep) {
-        const u32x4 q = reinterpret_cast<const u32x4*>(p.hist + (size_t)rep * kHistBins)[tid];
-#pragma unroll
-        for (int i = 0; i < PER; ++i) c[i] += q[i];
-    }
+    sum_replicas(p.hist, L.replicas, tid, c);
     locate_bin<PER>(c, (uint32_t)k, s_w, s_out);
     if (tid == 0) {
         p.binfo[0] = s_out[0];
@@ -321,11 +331,7 @@ __global__ __launch_bounds__(kSelThreads) void collect_kernel(const float* s_all
     // the bin B of the k-th largest score, from the sum of the histogram replicas
     constexpr int PER = kHistBins / kSelThreads;          // 4 consecutive bins per thread
     uint32_t c[PER] = {0u, 0u, 0u, 0u};
-    for (int rep = 0; rep < L.replicas; ++rep) {
-        const u32x4 q = reinterpret_cast<const u32x4*>(p.hist + (size_t)rep * kHistBins)[tid];
-#pragma unroll
-        for (int i = 0; i < PER; ++i) c[i] += q[i];
-    }
+    sum_replicas(p.hist, L.replicas, tid, c);
     if (tid == 0) s_n = 0u;
     locate_bin<PER>(c, (uint32_t)k, s_w, s_out);
     const uint32_t B = s_out[0];
@@ -427,6 +433,8 @@ struct ResolveSmem {
     uint32_t w[kSelWaves];
     uint32_t out[4];
     uint32_t cnt[kMaxBlocksPerRow];
+    uint64_t few[64];       // the last candidates, ranked by one wavefront
+    uint32_t nfew;
 };
 
 // Row-wide part of the selection, run by one whole workgroup: the 64-bit threshold T and, in thread
@@ -436,6 +444,8 @@ __device__ __forceinline__ void resolve_row(const SelPtrs& p, const SelLayout& L
     const int tid = threadIdx.x;
     const uint32_t B = p.binfo[0];
     const uint32_t above = p.binfo[1];
+    const uint32_t sure_of_block_tid = tid < (int)L.nb ? p.sure[tid] : 0u;   // requested with everything else
+    if (tid == 0) sm.nfew = 0u;
 
     // candidates: 52-bit sub-keys (20 low key bits, then the inverted id); the top 12 bits are all B
     constexpr uint64_t kSubMask = (1ull << 52) - 1ull;
@@ -489,8 +499,25 @@ __device__ __forceinline__ void resolve_row(const SelPtrs& p, const SelLayout& L
         prefix |= (uint64_t)sm.out[0] << shift;
         remain -= sm.out[1];
         decided += w;
-        all_of_prefix = (remain == sm.out[2]);          // every candidate with this prefix is selected
+        const uint32_t left = sm.out[2];                // candidates that share the decided prefix
+        all_of_prefix = (remain == left);               // every one of them is selected
         __syncthreads();
+        if (!all_of_prefix && left <= 64u) {
+            // A handful left (the usual case after the first digit): one wavefront ranks them by counting
+            // instead of more digit passes.  Sub-keys are unique (they end in the id), so exactly one has
+            // remain - 1 larger ones: that one is the threshold.
+            for_each_candidate([&](uint64_t x) {
+                if ((x >> (52 - decided)) == (prefix >> (52 - decided))) sm.few[atomicAdd(&sm.nfew, 1u)] = x;
+            });
+            __syncthreads();
+            const int lane = tid & 63;
+            const uint64_t mine = (uint32_t)lane < left ? sm.few[lane] : 0ull;
+            uint32_t larger = 0u;
+            for (uint32_t j = 0; j < left; ++j) larger += readlane_u64(mine, (int)j) > mine;
+            const uint64_t pick = __builtin_amdgcn_ballot_w64((uint32_t)lane < left && larger == remain - 1u);
+            prefix = readlane_u64(mine, pick ? __ffsll((long long)pick) - 1 : 0);
+            break;
+        }
     }
     // threshold: selected(v) <=> (key << 32 | ~v) >= T, T = (B << 20 | prefix.hi) << 32 | prefix.lo
     T = ((uint64_t)((B << kKeyLowBits) | (uint32_t)(prefix >> 32)) << 32) | (uint32_t)prefix;
@@ -503,7 +530,7 @@ __device__ __forceinline__ void resolve_row(const SelPtrs& p, const SelLayout& L
         if (x >= prefix) atomicAdd(&sm.cnt[(uint32_t)(~(uint32_t)x) / (uint32_t)L.chunk], 1u);
     });
     __syncthreads();
-    const uint32_t mine = tid < nb ? sm.cnt[tid] + p.sure[tid] : 0u;
+    const uint32_t mine = tid < nb ? sm.cnt[tid] + sure_of_block_tid : 0u;
     offset_of_block_tid = block_prefix_exclusive<kSelWaves>(mine, sm.w);
 }
 

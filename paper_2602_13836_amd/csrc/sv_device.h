@@ -139,8 +139,13 @@ __device__ __forceinline__ uint32_t block_prefix_exclusive(uint32_t x, uint32_t*
     __syncthreads();                                   // s_w may still be read from an earlier scan
     if (lane == 63) s_w[wave] = incl;
     __syncthreads();
+    // all WAVES partial sums are read at once (a loop up to `wave` would wait for one LDS read after the other)
     uint32_t lower = 0;
-    for (int w = 0; w < wave; ++w) lower += s_w[w];
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) {
+        const uint32_t v = s_w[w];
+        lower += w < wave ? v : 0u;
+    }
     return incl - x + lower;
 }
 // sum over the threads with a HIGHER index
@@ -157,7 +162,11 @@ __device__ __forceinline__ uint32_t block_suffix_exclusive(uint32_t x, uint32_t*
     if (lane == 0) s_w[wave] = incl;
     __syncthreads();
     uint32_t higher = 0;
-    for (int w = wave + 1; w < WAVES; ++w) higher += s_w[w];
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) {
+        const uint32_t v = s_w[w];
+        higher += w > wave ? v : 0u;
+    }
     return incl - x + higher;
 }
 
