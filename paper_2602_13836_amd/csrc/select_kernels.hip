@@ -526,9 +526,33 @@ __device__ __forceinline__ void resolve_row(const SelPtrs& p, const SelLayout& L
     const int nb = (int)L.nb;
     sm.cnt[tid] = 0u;
     __syncthreads();
-    for_each_candidate([&](uint64_t x) {
-        if (x >= prefix) atomicAdd(&sm.cnt[(uint32_t)(~(uint32_t)x) / (uint32_t)L.chunk], 1u);
-    });
+    // Candidates of one vocabulary block sit next to each other in the list, so the lanes of a wavefront
+    // mostly count into the same word: one atomic per distinct block and wavefront, not one per candidate.
+    constexpr int kChunkShift = 12;
+    static_assert((1 << kChunkShift) == kEpt * kSelThreads, "a vocabulary block is 4096 ids");
+    auto count_selected = [&](bool valid, uint64_t x) {
+        const bool sel = valid && x >= prefix;
+        const uint32_t blk = (uint32_t)(~(uint32_t)x) >> kChunkShift;
+        uint64_t todo = __builtin_amdgcn_ballot_w64(sel);
+        while (todo) {
+            const uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)blk, __ffsll((long long)todo) - 1);
+            const uint64_t same = __builtin_amdgcn_ballot_w64(sel && blk == b);
+            if ((tid & 63) == __ffsll((long long)same) - 1) atomicAdd(&sm.cnt[b], (uint32_t)__popcll(same));
+            todo &= ~same;
+        }
+    };
+    if (in_regs) {
+#pragma unroll
+        for (int i = 0; i < kCandPerThread; ++i) {
+            if ((uint32_t)i * kSelThreads >= n) break;             // uniform: no candidate in this round
+            count_selected((uint32_t)i * kSelThreads + tid < n, sk[i]);
+        }
+    } else {
+        for (uint32_t j0 = 0; j0 < n; j0 += kSelThreads) {
+            const uint32_t j = j0 + tid;
+            count_selected(j < n, j < n ? (p.cand[j] & kSubMask) : 0ull);
+        }
+    }
     __syncthreads();
     const uint32_t mine = tid < nb ? sm.cnt[tid] + sure_of_block_tid : 0u;
     offset_of_block_tid = block_prefix_exclusive<kSelWaves>(mine, sm.w);
