@@ -551,6 +551,62 @@ def test_select_threshold_pads_in_place(rows):
     assert torch.equal(torch.isneginf(z), idx_t < 0)
 
 
+def _int_valued(rng, shape, span, dtype):
+    x = rng.integers(-span, span + 1, shape).astype(np.float32)
+    return x if dtype == "f32" else f32_to_bf16_bits(x)
+
+
+def test_select_is_exact_on_integer_valued_inputs():
+    """Small integers make every product and sum exact on both sides whatever the order of accumulation,
+    and leave thousands of exactly tied scores: ids and scores must equal the oracle's one by one (the k-th
+    score falls inside a tie almost always, so this is the tie rule at every size the tail kernels branch on)."""
+    rng = np.random.default_rng(12345)
+    for case in range(60):
+        rows = int(rng.choice([1, 1, 2, 3, 4, 5, 6, 9, 17]))
+        V = int(rng.choice([1, 2, 3, 5, 63, 64, 100, 1000, 4095, 4096, 4097, 9000, 20000, 70001]))
+        k = min(V, int(rng.choice([1, 2, max(1, V // 16), max(1, V // 2), max(1, V - 1), V])))
+        dp = int(rng.choice([8, 16, 24, 64]))
+        d = dp + int(rng.choice([0, 8, 40]))
+        span = int(rng.choice([1, 2, 3]))
+        dtype = str(rng.choice(["bf16", "f32"]))
+        tau = float(rng.integers(-3, 6)) if rng.random() < 0.3 else None
+        say(f"integer select {case}: {dtype} rows={rows} V={V} k={k} d'={dp} d={d} span={span} tau={tau}")
+        h = _int_valued(rng, (rows, d), span, dtype)
+        Wd = np.zeros((dp, d), np.float32)
+        Wd[np.arange(dp), np.arange(dp)] = 1.0              # h' = the first d' entries of h
+        Wd = Wd if dtype == "f32" else f32_to_bf16_bits(Wd)
+        Wv = _int_valued(rng, (V, dp), span, dtype)
+        idx, sc = sv.select(to_dev(h), to_dev(Wd), to_dev(Wv), k, want_scores=True, tau=tau)
+        ref_idx, ref_sc = oracle.select(h, Wd, Wv, k, tau=tau)[:2]
+        assert np.array_equal(idx.cpu().numpy(), ref_idx), (case, dtype, rows, V, k)
+        assert np.array_equal(sc.cpu().numpy(), ref_sc.astype(np.float32)), (case, dtype, rows, V, k)
+
+
+def test_draft_step_is_exact_on_integer_valued_inputs():
+    """The same for subset logits + top-kd: exact logits, exact ties, so tokens equal the oracle's."""
+    rng = np.random.default_rng(54321)
+    for case in range(40):
+        rows = int(rng.choice([1, 1, 2, 3, 5, 18, 70]))
+        d = int(rng.choice([8, 64, 264, 1024, 4096]))
+        V = int(rng.choice([10, 300, 5000, 20000]))
+        k = min(V, int(rng.choice([1, 7, 64, 1000, 1025, 4096, 8192, 9001])))
+        kd = min(k, int(rng.choice([1, 4, 10, 64])))
+        per_row = bool(rng.random() < 0.5)
+        say(f"integer draft step {case}: rows={rows} d={d} V={V} k={k} kd={kd} per_row={per_row}")
+        U = _int_valued(rng, (V, d), 1, "bf16")
+        h = _int_valued(rng, (rows, d), 1, "bf16")
+        if per_row:
+            idx = np.stack([rng.permutation(V)[:k] for _ in range(rows)]).astype(np.int32)
+        else:
+            idx = rng.permutation(V)[:k].astype(np.int32)
+        z, tok, prob, _ = sv.draft_step(to_dev(h), to_dev(U), torch.from_numpy(idx).to(DEV), kd)
+        z_ref = oracle.subset_logits(h, U, idx)
+        assert np.array_equal(z.cpu().numpy(), z_ref.astype(np.float32)), case
+        ref_tok, ref_prob = oracle.softmax_topk(z_ref, idx, kd)
+        assert np.array_equal(tok.cpu().numpy(), ref_tok), case
+        np.testing.assert_allclose(prob.cpu().numpy(), ref_prob, rtol=2e-5, atol=1e-30)
+
+
 def test_k_varies_from_step_to_step():
     """Section 3.3 Step 2 allows k to change per decoding step: k is a call argument, and buffers and
     workspace sized once for the largest k serve every step."""
