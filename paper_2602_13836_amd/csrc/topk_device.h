@@ -28,6 +28,10 @@ constexpr int kCap = 512;                    // candidate list capacity
 // M == 0: the row is streamed from global memory (L2) in every pass (any k).
 // VEC (M % 4 == 0, k % 4 == 0, 16-byte aligned rows): a thread owns groups of 4 consecutive
 // elements and moves them with 128-bit loads and stores.
+// Long rows (M >= kDeferFrom): one compute unit pulls a long row slowly, so the token ids -- half the
+// bytes -- are not read up front: candidates carry their position and only the few of them fetch
+// their token (one more round trip, a quarter of a megabyte less at k = 32768).
+constexpr int kDeferFrom = 16;
 template <int M, bool VEC>
 __device__ __forceinline__ void softmax_topk_block(const TopkArgs& a, const int64_t r) {
     __shared__ __attribute__((aligned(16))) uint32_t s_rowmax[kRows16];   // exact row maxima
@@ -48,9 +52,15 @@ __device__ __forceinline__ void softmax_topk_block(const TopkArgs& a, const int6
     if (tid == 0) s_count = 0u;
 
     // ---- 1. keys and row maxima
+    constexpr bool DEFER = M >= kDeferFrom;
     uint32_t key[M > 0 ? M : 1];
-    int32_t tk[M > 0 ? M : 1];
+    int32_t tk[M > 0 && !DEFER ? M : 1];
     uint32_t lmax = 0u;
+    // position of the thread's i-th element in the row
+    auto pos_of = [&](int i) -> int32_t {                 // < M * 1024
+        if constexpr (VEC) return (i / 4) * (4 * kThreads) + 4 * tid + (i & 3);
+        else return i * kThreads + tid;
+    };
     if constexpr (M > 0 && VEC) {
 #pragma unroll
         for (int q = 0; q < M / 4; ++q) {
@@ -58,12 +68,12 @@ __device__ __forceinline__ void softmax_topk_block(const TopkArgs& a, const int6
             u32x4 zz = zero16(), tt = zero16();
             if (j0 < k) {
                 zz = *reinterpret_cast<const u32x4*>(z + j0);
-                tt = *reinterpret_cast<const u32x4*>(idx + j0);
+                if constexpr (!DEFER) tt = *reinterpret_cast<const u32x4*>(idx + j0);
             }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 key[q * 4 + e] = j0 < k ? f32_to_ord(__uint_as_float(zz[e])) : 0u;
-                tk[q * 4 + e] = (int32_t)tt[e];
+                if constexpr (!DEFER) tk[q * 4 + e] = (int32_t)tt[e];
                 lmax = key[q * 4 + e] > lmax ? key[q * 4 + e] : lmax;
             }
         }
@@ -72,7 +82,7 @@ __device__ __forceinline__ void softmax_topk_block(const TopkArgs& a, const int6
         for (int i = 0; i < M; ++i) {
             const int64_t j = (int64_t)i * kThreads + tid;
             key[i] = j < k ? f32_to_ord(z[j]) : 0u;          // 0 = no element (finite keys are larger)
-            tk[i] = j < k ? idx[j] : 0;
+            if constexpr (!DEFER) tk[i] = j < k ? idx[j] : 0;
             lmax = key[i] > lmax ? key[i] : lmax;
         }
     } else {
@@ -126,8 +136,12 @@ __device__ __forceinline__ void softmax_topk_block(const TopkArgs& a, const int6
     };
     if constexpr (M > 0) {
 #pragma unroll
-        for (int i = 0; i < M; ++i)
-            if (key[i] != 0u) visit(key[i], tk[i]);
+        for (int i = 0; i < M; ++i) {
+            if (key[i] != 0u) {
+                if constexpr (DEFER) visit(key[i], pos_of(i));              // the token follows below
+                else visit(key[i], tk[i]);
+            }
+        }
     } else {
         for (int64_t j = tid; j < k; j += kThreads) visit(f32_to_ord(z[j]), idx[j]);
     }
@@ -145,6 +159,16 @@ __device__ __forceinline__ void softmax_topk_block(const TopkArgs& a, const int6
     };
 
     if (n <= (uint32_t)kCap) {
+        if constexpr (DEFER) {
+            // the candidates' tokens: only the first wavefront goes on from here, and it sees its own LDS writes
+            if (wave == 0) {
+                for (uint32_t c = lane; c < n; c += 64) {
+                    const uint64_t e = s_cand[c];
+                    const int32_t tok = idx[(uint32_t)(~(uint32_t)e)];
+                    s_cand[c] = (e & 0xFFFFFFFF00000000ull) | (uint32_t)(~(uint32_t)tok);
+                }
+            }
+        }
         // ---- 4. rank the candidates by counting; ranks are unique (position breaks exact ties)
         if (wave == 0 && n <= 64u) {
             // the usual case: one candidate per lane, the others arrive by lane broadcast (no LDS latency)
@@ -181,7 +205,7 @@ __device__ __forceinline__ void softmax_topk_block(const TopkArgs& a, const int6
                 const uint64_t k64 = ((uint64_t)kk << 32) | (uint32_t)(~(uint32_t)tok);
                 if (k64 < prev && k64 > cand) cand = k64;
             };
-            if constexpr (M > 0) {
+            if constexpr (M > 0 && !DEFER) {
 #pragma unroll
                 for (int i = 0; i < M; ++i)
                     if (key[i] != 0u) consider(key[i], tk[i]);

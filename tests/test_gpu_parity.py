@@ -210,17 +210,21 @@ TOPK_SHAPES = [
     (2, 2048, 10, "per_row"), (2, 2049, 10, "per_row"), (1, 8192, 10, "per_row"),
     (3, 8192, 64, "per_step"), (2, 20000, 10, "per_row"), (2, 32768, 8, "per_row"),
     (1, 40000, 10, "per_row"), (60, 4096, 10, "per_row"),
+    (2, 12000, 10, "per_row"), (1, 12001, 10, "per_row"), (1, 16384, 64, "per_step"),   # tokens fetched late
+    (2, 30001, 5, "per_row"),
 ]
 
 
 @pytest.mark.parametrize("rows,k,kd,mode", TOPK_SHAPES)
-@pytest.mark.parametrize("ties", [False, True])
+@pytest.mark.parametrize("ties", [False, True, "negative"])
 def test_draft_topk_matches_oracle_on_identical_logits(rows, k, kd, mode, ties):
     """Both sides get the same float32 logits, so tokens must match bit-exactly, ties included."""
     say(f"draft_topk rows={rows} k={k} kd={kd} {mode} ties={ties}")
     rng = np.random.default_rng(1000 * k + kd + rows)
     z = (rng.standard_normal((rows, k)) * 3.0).astype(np.float32)
-    if ties:
+    if ties == "negative":
+        z = -np.abs(z) - np.float32(40.0)     # every logit far below zero: still an ordinary row
+    elif ties:
         z = np.round(z * 2.0) / 2.0           # a handful of distinct values: ties everywhere
         z[z == 0.0] = -0.0                    # -0.0 must order like +0.0
     V = max(4 * k, 1000)

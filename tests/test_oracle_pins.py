@@ -123,6 +123,9 @@ def test_softmax_uniform_and_shift_invariance():
     _, _, q0 = oracle.softmax_topk(z, idx, 1, full=True)
     _, _, q1 = oracle.softmax_topk(z + np.float32(8.0), idx, 1, full=True)
     assert np.allclose(q0, q1, rtol=1e-13)
+    # a row whose logits are all negative is an ordinary row, not an empty one
+    _, _, qn = oracle.softmax_topk(z - np.float32(8.0), idx, 1, full=True)
+    assert np.allclose(q0, qn, rtol=1e-13) and abs(qn.sum() - 1.0) < 1e-12
     # huge logits must not overflow (max is subtracted)
     _, p = oracle.softmax_topk(np.array([1e4, 1e4 - 1.0], np.float32), np.array([3, 9], np.int32), 2)
     assert np.allclose(p[0], [1 / (1 + math.exp(-1)), math.exp(-1) / (1 + math.exp(-1))], rtol=1e-12)
@@ -384,6 +387,8 @@ def test_p8_operation_counts():
     oracle.reset_mac_count()
     oracle.dense_logits(h, U)
     assert oracle.mac_count() == rows * V * d
+    oracle.dense_logits(h, U, acc="f64")                   # the float64 cross-check counts alike
+    assert oracle.mac_count() == 2 * rows * V * d
     oracle.reset_mac_count()
     idx, _ = oracle.select(h, Wd, Wv, k)
     assert oracle.mac_count() == rows * (V * dp + d * dp)
