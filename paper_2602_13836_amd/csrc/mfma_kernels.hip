@@ -282,12 +282,18 @@ hipError_t launch_wn(const GemvArgs& a, int row0, hipStream_t stream) {
     const int64_t per_block = (int64_t)WPB * 16;
     const int64_t bx = (a.n_items + per_block - 1) / per_block;
     const size_t lds = (size_t)2 * 16 * NB * kXRowBytes;
-    static bool configured = false;               // more than 64 KiB of LDS needs an explicit opt-in
-    if (!configured && lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&skinny_mfma_kernel<WPB, NB>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (lds > 64 * 1024) {                        // more than 64 KiB of LDS needs an explicit opt-in,
+        static bool configured[64] = {};          // once per device and instance
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
         if (e != hipSuccess) return e;
-        configured = true;
+        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+        if (!configured[dev]) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&skinny_mfma_kernel<WPB, NB>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            configured[dev] = true;
+        }
     }
     hipLaunchKernelGGL((skinny_mfma_kernel<WPB, NB>), dim3((unsigned)bx), dim3(WPB * 64), lds, stream, a, row0);
     return hipGetLastError();

@@ -274,12 +274,18 @@ hipError_t launch_tile(const GemvArgs& a, hipStream_t stream) {
     const int64_t bx = groups * RT * kXcds;
     if (bx > 0x7fffffffLL) return hipErrorInvalidValue;         // more tiles than a grid dimension holds
     const size_t lds = (size_t)2 * (TM + TN) * kRowB;
-    static bool configured = false;                             // more than 64 KiB of LDS needs an explicit opt-in
-    if (!configured && lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tile_mfma_kernel<GM, GN, WM, WN, PIPE>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (lds > 64 * 1024) {                                      // more than 64 KiB of LDS needs an explicit opt-in,
+        static bool configured[64] = {};                        // once per device and instance
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
         if (e != hipSuccess) return e;
-        configured = true;
+        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+        if (!configured[dev]) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tile_mfma_kernel<GM, GN, WM, WN, PIPE>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            configured[dev] = true;
+        }
     }
     hipLaunchKernelGGL((tile_mfma_kernel<GM, GN, WM, WN, PIPE>), dim3((unsigned)bx), dim3(64 * GM * GN), lds, stream, a);
     return hipGetLastError();
