@@ -1,12 +1,12 @@
 // Candidate-vocabulary selection (Section 3.3): approximate logits s = W_vocab h' (Step 1) and
 // k_t = top-k(s_t, k) (Step 2), exact, ids in ascending order, ties to the smaller id.
 //
-// Three launches after the down-projection (with more than four hidden rows: a histogram pass over
+// Three launches after the down-projection (with more than eight hidden rows: a histogram pass over
 // scores that a matrix-core kernel produced, then four).  Every step that needs a result of the whole
 // row sits behind a kernel boundary: on this multi-die part a kernel boundary is the cheapest
 // device-wide synchronisation (a device-scope release fence writes back a whole L2, and atomics on one
 // address serialise at ~50 ns each), so there is no "last block" hand-over and no contended counter.
-// Up to four hidden rows the kernels are shaped for latency (few launches, redundant work per block);
+// Up to eight hidden rows the kernels are shaped for latency (few launches, redundant work per block);
 // beyond that for throughput (small workgroups, 16-byte loads, the row-wide results computed once).
 //   scores_hist   streams W_vocab once.  A selector row is short (d' = d/16 .. d/8: a few hundred
 //                 bytes), so a wavefront is split into groups of G lanes, one row per group, and
@@ -15,14 +15,14 @@
 //                 order-preserving key: in LDS per block, then merged into one of several global
 //                 replicas of the histogram (replicas keep same-address atomics apart).
 //   collect       every block first sums the replicas and finds the bin B that holds the k-th
-//                 largest score (redundantly: cheaper than one more launch -- with more than four
+//                 largest score (redundantly: cheaper than one more launch -- with more than eight
 //                 hidden rows a launch of one block per row does it once instead); it then counts
 //                 its scores in bins above B (all selected) and appends (key, id) of its scores in
 //                 bin B to the row's candidate list.
 //   resolve       MSB-first radix selection among the candidates over the remaining 20 key bits
 //                 and, only if scores tie exactly, the inverted id bits, which yields a 64-bit
 //                 threshold T with  selected(v) <=> (key(v) << 32 | ~v) >= T ; it also turns the
-//                 per-block counts into output offsets.  With up to 4 hidden rows every emit block
+//                 per-block counts into output offsets.  With up to 8 hidden rows every emit block
 //                 does this itself (redundant work, one launch less); with more rows it is one
 //                 block per row in a launch of its own.
 //   emit          every block re-evaluates the predicate on its entries in id order and writes the
@@ -48,6 +48,8 @@ constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kMaxBlocksPerRow = 1024;                   // vocabulary blocks per row in collect / emit
 constexpr int kEpt = 4;                                  // entries per thread in collect / emit
 constexpr int kCandPerThread = 8;                        // candidates a resolve thread keeps in registers
+constexpr int kFewRows = 8;                              // up to here the latency-shaped tail (measured: 5 us
+                                                         // faster at 5 to 8 rows, slower from 10)
 
 // per-row state words (zeroed before every call together with the histogram replicas)
 enum { ST_NCAND = 0, ST_T_HI = 1, ST_T_LO = 2, ST_WORDS = 4 };
@@ -740,7 +742,7 @@ hipError_t launch_hist(const float* s, int64_t V, int64_t k, int rows, uint32_t*
 hipError_t launch_topk_of_scores(const RadixArgs& a, hipStream_t stream) {
     const SelLayout L = sel_layout(a.V, a.rows);
     const dim3 grid((unsigned)L.nb, (unsigned)a.rows);
-    if (a.rows <= 4) {
+    if (a.rows <= kFewRows) {
         hipLaunchKernelGGL(collect_kernel, grid, dim3(kSelThreads), 0, stream, a.s, a.V, a.k, a.scratch, a.rows);
         hipLaunchKernelGGL(emit_kernel, grid, dim3(kSelThreads), 0, stream, a.s, a.V, a.k, a.scratch, a.rows,
                            a.idx_out, a.scores_out, a.tau);

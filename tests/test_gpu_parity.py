@@ -377,9 +377,12 @@ SELECT_SHAPES = [
     ("bf16", 1, 1024, 520, 3000, 64),         # longer than a wave-wide load: generic row kernel
     ("f32", 2, 264, 12, 700, 33),
     ("bf16", 100, 512, 64, 3000, 500),        # a batch of rows: scores on the tiled matrix-core kernel
-    ("bf16", 5, 256, 32, 4099, 4099),         # many-row tail kernels: k = V, rows of s not 16-byte aligned
+    ("bf16", 5, 256, 32, 4099, 4099),         # five rows on the few-row tail: k = V, rows of s not 16-byte aligned
+    ("bf16", 11, 256, 32, 4099, 4099),        # many-row tail kernels: the same
     ("bf16", 9, 256, 64, 10007, 777),         # three vocabulary blocks per row, ragged, odd V
     ("f32", 6, 264, 12, 5001, 100),
+    ("f32", 10, 264, 12, 5001, 100),          # float32 scores through the many-row tail
+    ("bf16", 8, 512, 64, 9000, 2000),         # the last row count of the few-row tail
     ("bf16", 40, 2048, 48, 3000, 300),        # batch down-projection on the matrix cores (two row groups)
 ]
 
@@ -400,7 +403,7 @@ def test_select(dtype, rows, d, dp, V, k):
         assert_logits_close(sc[r], s_ref[r, idx[r]], dtype, "scores at the selected ids")
 
 
-@pytest.mark.parametrize("rows", [2, 6])          # 6 rows: the many-row forms of the tail kernels
+@pytest.mark.parametrize("rows", [2, 6, 12])      # 12 rows: the many-row forms of the tail kernels
 def test_select_ties_go_to_smaller_ids(rows):
     """Rows of W_vocab repeated: repeated rows score bit-identically on the GPU as well, so the
     set is decided by the tie rule alone wherever the distinct scores are far apart."""
@@ -414,16 +417,20 @@ def test_select_ties_go_to_smaller_ids(rows):
     for k in (1, 1999, 2000, 5000, V):
         idx, _ = sv.select(to_dev(h), to_dev(Wd), to_dev(Wv), k)
         ref_idx, _, s_ref, _ = oracle.select(h, Wd, Wv, k, full=True)
-        for r in range(rows):                                 # the premise of an exact comparison
+        clear = []                                            # rows that meet the premise of an exact comparison
+        for r in range(rows):
             vals = np.unique(s_ref[r])
-            assert len(vals) == 5 and np.diff(vals).min() > 0.01      # >> any rounding difference
-        assert np.array_equal(idx.cpu().numpy(), ref_idx), k
+            assert len(vals) == 5
+            if np.diff(vals).min() > 0.01:                    # >> any rounding difference
+                clear.append(r)
+        assert 2 * len(clear) > rows
+        assert np.array_equal(idx.cpu().numpy()[clear], ref_idx[clear]), k
     Wv[:] = Wv[0]
     idx, _ = sv.select(to_dev(h), to_dev(Wd), to_dev(Wv), 4321)
     assert np.array_equal(idx.cpu().numpy(), np.tile(np.arange(4321, dtype=np.int32), (rows, 1)))
 
 
-@pytest.mark.parametrize("rows", [1, 5])
+@pytest.mark.parametrize("rows", [1, 5, 9])
 def test_select_at_the_largest_vocabulary(rows):
     """V = 4194304, the most specvocab_select accepts: 1024 vocabulary blocks per row, both forms of the
     tail kernels."""
@@ -523,7 +530,7 @@ def test_empty_rows_and_draft_topk_on_padding():
     assert tok_ref[0].tolist() == [-1] * kd and tok_ref[2].tolist()[:4] == [7, 9, 8, 6]
 
 
-@pytest.mark.parametrize("rows", [1, 7])
+@pytest.mark.parametrize("rows", [1, 7, 10])
 def test_select_threshold_pads_in_place(rows):
     """specvocab_select_threshold: the plain selection with the entries scoring below tau turned into
     padding slots, then usable as a padded list."""
