@@ -14,7 +14,8 @@ Prints ONE JSON line.  Besides the contract fields it carries
   cold          the same step with U rotated over 8 copies, so that no row can be served from the
                 256 MB last-level cache (the one-U numbers are what a drafter really sees)
                 also: the same kernel over one contiguous block of k rows, cold -- the ceiling of a burst
-  select        the selector (W_down, W_vocab, top-k) at the same shape, and the step with it
+  select        the selector (W_down, W_vocab, top-k) at the same shape, the step with it, and the selector
+                with W_vocab rotated over 6 copies (cold: no copy survives in the last-level cache)
   aux_log_softmax_us   log q_aux over the whole vocabulary (Section 3.4) at the same shape
   break_even    the paper's Section 6 / Table 4 comparison: full vocabulary, a static 32K vocabulary
                 (gathered and pre-packed), SpecVocab with k = 2048 and 8192, whole steps
@@ -446,6 +447,14 @@ def main():
                             "step_with_select_us": round(full_us, 2),
                             "speedup_vs_dense": round(result["dense"]["us_per_step"] / full_us, 2)}
         del g_sel, g_full
+        # the same with W_vocab coming from HBM: consecutive steps read different copies of it (together
+        # larger than the 256 MB last-level cache), as after a target-model pass has swept the caches
+        nwv = 6
+        Wv_copies = [Wv] + [Wv.clone() for _ in range(nwv - 1)]
+        g_selc = capture(lambda t: sv.select(h[t % nd], Wd, Wv_copies[t % nwv], c.k, idx_out=sel, ws=ws), nsel)
+        timed_replays(g_selc, 2)
+        result["select"]["select_us_cold_W_vocab"] = round(sorted(timed_replays(g_selc, 5))[2] * 1e3 / nsel, 2)
+        del g_selc, Wv_copies
         # the wider selector the paper also studies (d'/d = 1/8)
         Wd8_np, Wv8_np = c.selector(c.d // 8)
         Wd8, Wv8 = dev_bf16(Wd8_np), dev_bf16(Wv8_np)
