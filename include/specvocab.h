@@ -75,9 +75,11 @@ typedef enum { SV_IDX_PER_ROW = 0, SV_IDX_PER_STEP = 1 } sv_idx_mode;
  * name no token.  A padding slot reads no row of U, its logit is -inf and its probability 0; the real
  * entries of the row are computed exactly as without padding, and the draft top-kd behaves as on the
  * compacted list of real entries (if a row has fewer than kd of them, the remaining tok_out entries
- * are -1 with probability 0; a row of padding only gets all probabilities 0).  The gathering calls
- * need extra workspace for a padded list (specvocab_workspace_bytes with the flagged idx_mode) and
- * two small extra launches; lists without the flag must not contain -1. */
+ * are -1 with probability 0; a row of padding only gets all probabilities 0).  With one hidden
+ * row (and wherever the row-gather kernel serves the call) a padded list costs nothing extra; where
+ * the matrix cores multiply (several bf16 hidden rows) the gathering calls need extra workspace
+ * (specvocab_workspace_bytes with the flagged idx_mode) and two small extra launches.  Lists
+ * without the flag must not contain -1. */
 #define SV_IDX_PADDED 4
 
 typedef enum {

@@ -106,9 +106,14 @@ sv::GemvArgs gather_args(const void* h, int64_t rows, int64_t d, int64_t ldh, co
     return g;
 }
 
-// bytes of the clean copy of a padded index list (0 if the list is not padded)
-size_t pad_ws_bytes(int64_t rows, int64_t k, int idx_mode) {
-    if (!is_padded(idx_mode)) return 0;
+// the row-gather kernels take padding slots as they are; the matrix-core and union paths need a clean copy
+bool padded_needs_copy(int dt, const sv::GemvArgs& g) {
+    return sv::skinny_mfma_supported(dt, g) || sv::union_path_wanted(dt, g);
+}
+
+// bytes of the clean copy of a padded index list (0 if the list is not padded or no copy is needed)
+size_t pad_ws_bytes(int64_t rows, int64_t k, int idx_mode, int dt, const sv::GemvArgs& g) {
+    if (!is_padded(idx_mode) || !padded_needs_copy(dt, g)) return 0;
     const int64_t sets = base_mode(idx_mode) == SV_IDX_PER_ROW ? rows : 1;
     return round256((size_t)sets * (size_t)k * sizeof(int32_t));
 }
@@ -116,12 +121,13 @@ size_t pad_ws_bytes(int64_t rows, int64_t k, int idx_mode) {
 size_t gather_ws_bytes(int64_t rows, int64_t d, int64_t V, int64_t k, int dt, int idx_mode) {
     sv::GemvArgs g = gather_args(nullptr, rows, d, d, nullptr, d, dt, reinterpret_cast<const int32_t*>(16), k,
                                  idx_mode, nullptr);
-    return pad_ws_bytes(rows, k, idx_mode) + (sv::union_path_wanted(dt, g) ? sv::union_ws_bytes(rows, V, k) : 0);
+    return pad_ws_bytes(rows, k, idx_mode, dt, g) + (sv::union_path_wanted(dt, g) ? sv::union_ws_bytes(rows, V, k) : 0);
 }
 
-// Gathered logits for an index list that may carry padding slots (SV_IDX_PADDED): the kernels run on
-// a clean copy of the list (padding -> token 0) and the padding slots get -inf afterwards, so the
-// paths for plain lists stay exactly as they are.
+// Gathered logits for an index list that may carry padding slots (SV_IDX_PADDED).  The row-gather
+// kernels read a padding slot as "row 0, result -inf" themselves.  The matrix-core and union paths run
+// on a clean copy of the list (padding -> token 0) and the padding slots get -inf afterwards, so those
+// paths stay exactly as they are for plain lists.
 int launch_gather(int dt, const void* h, int64_t rows, int64_t d, int64_t ldh, const void* U, int64_t V,
                   int64_t ldu, const int32_t* idx, int64_t k, int idx_mode, float* logits_out, void* ws,
                   size_t ws_bytes, hipStream_t s) {
@@ -132,8 +138,10 @@ int launch_gather(int dt, const void* h, int64_t rows, int64_t d, int64_t ldh, c
     const int32_t* use = idx;
     char* rest = static_cast<char*>(ws);
     size_t rest_bytes = ws_bytes;
+    const sv::GemvArgs g0 = gather_args(h, rows, d, ldh, U, ldu, dt, idx, k, idx_mode, logits_out);
+    if (padded && !padded_needs_copy(dt, g0)) return sv::launch_gemv(dt, g0, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
     if (padded) {
-        const size_t pb = pad_ws_bytes(rows, k, idx_mode);
+        const size_t pb = pad_ws_bytes(rows, k, idx_mode, dt, g0);
         if (!ws || ws_bytes < pb) return SV_ERR_WORKSPACE;
         if (!aligned16(ws)) return SV_ERR_ALIGN;
         if (sv::launch_pad_clean(idx, sets * k, reinterpret_cast<int32_t*>(ws), s) != hipSuccess) return SV_ERR_HIP;

@@ -8,6 +8,8 @@
 //   gemv_rows_kernel        shorter rows: several rows per wavefront and a loop, the hidden-state row
 //                           in registers in the same lane layout for the whole life of the wave
 //   gemv_long_rows_kernel   longer rows, walked in 1 KiB pieces
+// An index of -1 (a padding slot of a padded list) reads row 0 and stores -inf: negative indices cost a
+// scalar maximum and a select, so all three kernels accept them whether the list is padded or not.
 #include "sv_device.h"
 #include "sv_launch.h"
 
@@ -38,7 +40,7 @@ __global__ __launch_bounds__(256) void gemv_rows_kernel(const GemvArgs a) {
         const int ch = c * 64 + lane;
         xreg[c] = (FULL || ch < C) ? xp[ch] : zero16();
     }
-    auto row_of = [&](int64_t item) -> int64_t {
+    auto row_of = [&](int64_t item) -> int64_t {          // -1 (a padding slot of a padded list) stays -1
         if (item > n - 1) item = n - 1;               // tail: recompute the last item, never stored
         return idx ? (int64_t)idx[item] : item;
     };
@@ -49,7 +51,7 @@ __global__ __launch_bounds__(256) void gemv_rows_kernel(const GemvArgs a) {
     auto load_rows = [&](u32x4 (&w)[RPI][NL]) {
 #pragma unroll
         for (int q = 0; q < RPI; ++q) {
-            const u32x4* mp = reinterpret_cast<const u32x4*>(a.M + row[q] * a.m_row_bytes);
+            const u32x4* mp = reinterpret_cast<const u32x4*>(a.M + (row[q] < 0 ? 0 : row[q]) * a.m_row_bytes);
 #pragma unroll
             for (int c = 0; c < NL; ++c) {
                 const int ch = c * 64 + lane;
@@ -73,7 +75,7 @@ __global__ __launch_bounds__(256) void gemv_rows_kernel(const GemvArgs a) {
             for (int q = 0; q < RPI; ++q) {
                 if (it + q < n) {
                     if constexpr (OUT_BF16) a.out_bf16[r * a.out_row_stride + it + q] = f32_to_bf16_rne(acc[q]);
-                    else a.out_f32[r * a.out_row_stride + it + q] = acc[q];
+                    else a.out_f32[r * a.out_row_stride + it + q] = row[q] < 0 ? -INFINITY : acc[q];
                 }
             }
         }
@@ -131,8 +133,8 @@ __global__ __launch_bounds__(kOnceWaves * 64) void gemv_rows_once_kernel(const G
         xs[q] = xp[FULL || unit[q] < last ? unit[q] : last];
     }
     const int64_t item = it < n ? it : n - 1;          // tail: recompute the last item, never stored
-    const int64_t row = a.idx ? (int64_t)a.idx[r * a.idx_row_stride + item] : item;
-    const u32x4* mp = reinterpret_cast<const u32x4*>(a.M + row * a.m_row_bytes);
+    const int64_t row = a.idx ? (int64_t)a.idx[r * a.idx_row_stride + item] : item;   // -1: a padding slot
+    const u32x4* mp = reinterpret_cast<const u32x4*>(a.M + (row < 0 ? 0 : row) * a.m_row_bytes);
     u32x4 w[NL];
 #pragma unroll
     for (int c = 0; c < NL; ++c) {
@@ -149,7 +151,7 @@ __global__ __launch_bounds__(kOnceWaves * 64) void gemv_rows_once_kernel(const G
     const float acc = wave_sum((part[0] + part[1]) + (part[2] + part[3]));
     if (lane == 0 && it < n) {
         if constexpr (OUT_BF16) a.out_bf16[r * a.out_row_stride + it] = f32_to_bf16_rne(acc);
-        else a.out_f32[r * a.out_row_stride + it] = acc;
+        else a.out_f32[r * a.out_row_stride + it] = row < 0 ? -INFINITY : acc;
     }
     if (a.zero_words) {     // clear a later kernel's scratch with this launch
         const size_t nthr = (size_t)gridDim.x * gridDim.y * blockDim.x;
@@ -177,14 +179,14 @@ __global__ __launch_bounds__(256) void gemv_long_rows_kernel(const GemvArgs a) {
     const int64_t n = a.n_items;
     const int64_t step = (int64_t)gridDim.x * 4;
     for (int64_t it = (int64_t)blockIdx.x * 4 + wave; it < n; it += step) {
-        const int64_t row = idx ? (int64_t)idx[it] : it;
-        const u32x4* mp = reinterpret_cast<const u32x4*>(a.M + row * a.m_row_bytes);
+        const int64_t row = idx ? (int64_t)idx[it] : it;                      // -1: a padding slot
+        const u32x4* mp = reinterpret_cast<const u32x4*>(a.M + (row < 0 ? 0 : row) * a.m_row_bytes);
         float acc = 0.0f;
         for (int ch = lane; ch < C; ch += 64) acc = dot16<DT>(load16<true>(mp + ch), xp[ch], acc);
         acc = wave_sum(acc);
         if (lane == 0) {
             if constexpr (OUT_BF16) a.out_bf16[r * a.out_row_stride + it] = f32_to_bf16_rne(acc);
-            else a.out_f32[r * a.out_row_stride + it] = acc;
+            else a.out_f32[r * a.out_row_stride + it] = row < 0 ? -INFINITY : acc;
         }
     }
 }

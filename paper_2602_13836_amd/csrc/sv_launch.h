@@ -37,6 +37,8 @@ struct GemvArgs {
     const uint32_t* n_items_dev;   // optional (matrix-core kernel only): the item count lives on the
                                    // device; n_items is then an upper bound that sizes the grid
 };
+// (the row-gather kernels behind launch_gemv accept idx entries of -1 = no token: such a slot reads
+// row 0 and gets -inf in a float32 output; the matrix-core and union paths need lists without them)
 hipError_t launch_gemv(int dt, const GemvArgs& a, hipStream_t stream);
 
 // debug aid: number of entries of idx[0..n) outside [0, V) (padded: -1 is allowed); synchronises the stream

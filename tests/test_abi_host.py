@@ -105,10 +105,13 @@ def test_dense_select_topk_reject_bad_arguments(lib):
     st = lib.specvocab_select_threshold
     assert st(A, 1, 256, 256, A, 32, A, 1000, 1, 10, float("nan"), A, None, A, 1 << 30, None) == 2
     assert st(A, 1, 256, 256, A, 32, A, 1000, 1, 10, 0.5, None, None, A, 1 << 30, None) == 1
-    # a padded list needs room for its clean copy; the comparator takes plain lists only
-    plain = sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 1, 4096, 128256, 8192)
-    assert sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 1, 4096, 128256, 8192, idx_mode=sv.SV_IDX_PADDED) == plain + 8192 * 4
-    assert lib.specvocab_subset_logits(A, 1, 256, 256, A, 1000, 256, 1, A, 100, 4, A, None, 0, None) == 5
+    # a padded list needs room for its clean copy where the matrix cores multiply (several hidden rows, one
+    # shared list), none where the row-gather kernel reads the list itself; the comparator takes plain lists only
+    assert sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 1, 4096, 128256, 8192, idx_mode=sv.SV_IDX_PADDED) == 0
+    plain = sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 8, 4096, 128256, 8192, idx_mode=sv.SV_IDX_PER_STEP)
+    assert sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 8, 4096, 128256, 8192,
+                              idx_mode=sv.SV_IDX_PER_STEP | sv.SV_IDX_PADDED) == plain + 8192 * 4
+    assert lib.specvocab_subset_logits(A, 8, 256, 256, A, 1000, 256, 1, A, 100, 5, A, None, 0, None) == 5
     assert lib.specvocab_indexed_head_naive(A, 1, 256, 256, A, 1000, 256, 1, A, 100, 4, A, A, 1 << 30, None) == 6
     assert lib.specvocab_subset_logits(A, 1, 256, 256, A, 1000, 256, 1, A, 100, 2, A, None, 0, None) == 3
 

@@ -475,7 +475,9 @@ def test_aux_log_softmax(dtype, rows, d, dp, V):
 
 PADDED_SHAPES = [
     # dtype, rows, d, V, k, mode          (which kernel family the clean copy goes through)
-    ("bf16", 1, 1024, 9000, 2048, "per_row"),     # row gather
+    ("bf16", 1, 1024, 9000, 2048, "per_row"),     # row gather: the kernels read the padding slots themselves
+    ("bf16", 1, 4096, 3000, 1000, "per_step"),    # ... one row per wavefront
+    ("bf16", 3, 8200, 300, 120, "per_row"),       # ... rows longer than 16 KiB
     ("f32", 2, 264, 900, 100, "per_row"),
     ("bf16", 6, 1024, 5000, 700, "per_step"),     # matrix cores, one shared padded list
     ("bf16", 20, 512, 6000, 1100, "per_row"),     # union of sets
