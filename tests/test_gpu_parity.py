@@ -98,6 +98,8 @@ def test_subset_and_dense_logits(dtype, rows, d, V, k, mode):
 
 @pytest.mark.parametrize("rows,d,V,k", [
     (3, 512, 700, 200),          # row kernel
+    (1, 4096, 600, 200),         # one row per wavefront, whole 8 KiB rows inside a wider matrix
+    (2, 3840, 500, 100),         # ... ragged rows
     (24, 2048, 3000, 800),       # skinny matrix-core kernels (shared set: reduction split; dense: streamed)
     (90, 512, 1500, 400),        # tiled matrix-core kernel
 ])
