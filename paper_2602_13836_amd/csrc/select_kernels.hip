@@ -439,10 +439,12 @@ struct ResolveSmem {
     uint32_t nfew;
 };
 
-// Row-wide part of the selection, run by one whole workgroup: the 64-bit threshold T and, in thread
-// t, the first output slot of vocabulary block t.
+// Row-wide part of the selection, run by one whole workgroup: the 64-bit threshold T and the first
+// output slots of the vocabulary blocks -- ONE < 0: of block t in thread t (an exclusive scan over all
+// blocks); ONE >= 0: of that block alone, in every thread (one sum instead of a histogram and a scan).
+template <bool ONE_BLOCK>
 __device__ __forceinline__ void resolve_row(const SelPtrs& p, const SelLayout& L, int64_t k, ResolveSmem& sm,
-                                            uint64_t& T, uint32_t& offset_of_block_tid) {
+                                            uint64_t& T, uint32_t& offset_out, const uint32_t one_block = 0u) {
     const int tid = threadIdx.x;
     const uint32_t B = p.binfo[0];
     const uint32_t above = p.binfo[1];
@@ -524,14 +526,30 @@ __device__ __forceinline__ void resolve_row(const SelPtrs& p, const SelLayout& L
     // threshold: selected(v) <=> (key << 32 | ~v) >= T, T = (B << 20 | prefix.hi) << 32 | prefix.lo
     T = ((uint64_t)((B << kKeyLowBits) | (uint32_t)(prefix >> 32)) << 32) | (uint32_t)prefix;
 
-    // output offsets: selected entries per block = sure + selected candidates, exclusive scan
+    // output offsets: selected entries per block = sure + selected candidates
     const int nb = (int)L.nb;
+    constexpr int kChunkShift = 12;
+    static_assert((1 << kChunkShift) == kEpt * kSelThreads, "a vocabulary block is 4096 ids");
+    if constexpr (ONE_BLOCK) {
+        // everything in front of one block: its sure entries and the selected candidates of lower blocks
+        uint32_t before = tid < (int)one_block ? sure_of_block_tid : 0u;
+        for_each_candidate([&](uint64_t x) {
+            before += (x >= prefix && ((uint32_t)(~(uint32_t)x) >> kChunkShift) < one_block) ? 1u : 0u;
+        });
+        before = wave_sum_u32(before);
+        __syncthreads();                                  // sm.w may still be read by the last locate
+        if ((tid & 63) == 0) sm.w[tid >> 6] = before;
+        __syncthreads();
+        uint32_t tot = 0u;
+#pragma unroll
+        for (int w = 0; w < kSelWaves; ++w) tot += sm.w[w];
+        offset_out = tot;
+        return;
+    }
     sm.cnt[tid] = 0u;
     __syncthreads();
     // Candidates of one vocabulary block sit next to each other in the list, so the lanes of a wavefront
     // mostly count into the same word: one atomic per distinct block and wavefront, not one per candidate.
-    constexpr int kChunkShift = 12;
-    static_assert((1 << kChunkShift) == kEpt * kSelThreads, "a vocabulary block is 4096 ids");
     auto count_selected = [&](bool valid, uint64_t x) {
         const bool sel = valid && x >= prefix;
         const uint32_t blk = (uint32_t)(~(uint32_t)x) >> kChunkShift;
@@ -557,7 +575,7 @@ __device__ __forceinline__ void resolve_row(const SelPtrs& p, const SelLayout& L
     }
     __syncthreads();
     const uint32_t mine = tid < nb ? sm.cnt[tid] + sure_of_block_tid : 0u;
-    offset_of_block_tid = block_prefix_exclusive<kSelWaves>(mine, sm.w);
+    offset_out = block_prefix_exclusive<kSelWaves>(mine, sm.w);
 }
 
 // one block per row (many hidden rows: the result is shared by the row's emit blocks through memory)
@@ -568,7 +586,7 @@ __global__ __launch_bounds__(kSelThreads) void resolve_kernel(int64_t V, int64_t
     const SelPtrs p = sel_ptrs(scratch, rows, blockIdx.x, L);
     uint64_t T;
     uint32_t off;
-    resolve_row(p, L, k, sm, T, off);
+    resolve_row<false>(p, L, k, sm, T, off);
     if (tid == 0) {
         p.state[ST_T_HI] = (uint32_t)(T >> 32);
         p.state[ST_T_LO] = (uint32_t)T;
@@ -586,7 +604,6 @@ __global__ __launch_bounds__(kSelThreads) void emit_kernel(const float* s_all, i
                                                            float* scores_out, float tau) {
     __shared__ uint32_t s_w[kSelWaves];
     __shared__ ResolveSmem sm;
-    __shared__ uint32_t s_off;
     const int tid = threadIdx.x;
     const int64_t r = blockIdx.y;
     const SelLayout L = sel_layout(V, rows);
@@ -599,11 +616,8 @@ __global__ __launch_bounds__(kSelThreads) void emit_kernel(const float* s_all, i
 #pragma unroll
     for (int i = 0; i < kEpt; ++i) val[i] = (v0 + i < V) ? s[v0 + i] : 0.0f;
     uint64_t T;
-    uint32_t off;
-    resolve_row(p, L, k, sm, T, off);
-    if (tid == (int)blockIdx.x) s_off = off;
-    __syncthreads();
-    const uint32_t block_off = s_off;
+    uint32_t block_off;
+    resolve_row<true>(p, L, k, sm, T, block_off, blockIdx.x);
 
     uint32_t mask = 0u;
 #pragma unroll
