@@ -124,18 +124,42 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x) {
            (uint32_t)__builtin_amdgcn_readlane((int)x, 32) + (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
 }
 
+// ---- wave-wide inclusive scans on DPP row shifts (a shuffle-based scan costs six LDS-path round trips)
+constexpr int DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, DPP_ROW_SHR8 = 0x118;
+constexpr int DPP_ROW_SHL1 = 0x101, DPP_ROW_SHL2 = 0x102, DPP_ROW_SHL4 = 0x104, DPP_ROW_SHL8 = 0x108;
+
+// sum over the lanes with a lower or equal index.  All lanes must be active.
+__device__ __forceinline__ uint32_t wave_prefix_inclusive_u32(uint32_t x) {
+    x += dpp_u32<DPP_ROW_SHR1>(x);            // lanes shifted in from outside a 16-lane row read 0
+    x += dpp_u32<DPP_ROW_SHR2>(x);
+    x += dpp_u32<DPP_ROW_SHR4>(x);
+    x += dpp_u32<DPP_ROW_SHR8>(x);            // inclusive within each row of 16
+    const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)x, 15);
+    const uint32_t r1 = (uint32_t)__builtin_amdgcn_readlane((int)x, 31);
+    const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)x, 47);
+    const int row = (threadIdx.x & 63) >> 4;
+    return x + (row >= 1 ? r0 : 0u) + (row >= 2 ? r1 : 0u) + (row >= 3 ? r2 : 0u);
+}
+// sum over the lanes with a higher or equal index.  All lanes must be active.
+__device__ __forceinline__ uint32_t wave_suffix_inclusive_u32(uint32_t x) {
+    x += dpp_u32<DPP_ROW_SHL1>(x);
+    x += dpp_u32<DPP_ROW_SHL2>(x);
+    x += dpp_u32<DPP_ROW_SHL4>(x);
+    x += dpp_u32<DPP_ROW_SHL8>(x);
+    const uint32_t r1 = (uint32_t)__builtin_amdgcn_readlane((int)x, 16);
+    const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)x, 32);
+    const uint32_t r3 = (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
+    const int row = (threadIdx.x & 63) >> 4;
+    return x + (row <= 0 ? r1 : 0u) + (row <= 1 ? r2 : 0u) + (row <= 2 ? r3 : 0u);
+}
+
 // ---- block-wide exclusive scans, one value per thread, WAVES wavefronts per workgroup -------
 // s_w: WAVES words of LDS.  Every thread of the workgroup must call.
 // sum over the threads with a LOWER index
 template <int WAVES>
 __device__ __forceinline__ uint32_t block_prefix_exclusive(uint32_t x, uint32_t* s_w) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t incl = x;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t o = __shfl_up(incl, off);
-        if (lane >= off) incl += o;
-    }
+    const uint32_t incl = wave_prefix_inclusive_u32(x);
     __syncthreads();                                   // s_w may still be read from an earlier scan
     if (lane == 63) s_w[wave] = incl;
     __syncthreads();
@@ -152,12 +176,7 @@ __device__ __forceinline__ uint32_t block_prefix_exclusive(uint32_t x, uint32_t*
 template <int WAVES>
 __device__ __forceinline__ uint32_t block_suffix_exclusive(uint32_t x, uint32_t* s_w) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t incl = x;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t o = __shfl_down(incl, off);
-        if (lane + off < 64) incl += o;
-    }
+    const uint32_t incl = wave_suffix_inclusive_u32(x);
     __syncthreads();
     if (lane == 0) s_w[wave] = incl;
     __syncthreads();
