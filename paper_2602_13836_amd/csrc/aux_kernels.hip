@@ -50,8 +50,7 @@ __device__ __forceinline__ void for_each_group(const float* s, int64_t V, int64_
 }
 
 __device__ __forceinline__ float block_max(float x, float* s_w) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));
+    x = wave_max_f32(x);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) s_w[threadIdx.x >> 6] = x;
     __syncthreads();

@@ -84,6 +84,15 @@ __device__ __forceinline__ float wave_sum(float x) {
     return (readlane_f32(x, 0) + readlane_f32(x, 16)) + (readlane_f32(x, 32) + readlane_f32(x, 48));
 }
 
+// max over all 64 lanes, result uniform across the wave. All lanes must be active.
+__device__ __forceinline__ float wave_max_f32(float x) {
+    x = fmaxf(x, dpp_f32<DPP_QUAD_1032>(x));
+    x = fmaxf(x, dpp_f32<DPP_QUAD_2301>(x));
+    x = fmaxf(x, dpp_f32<DPP_ROW_HALF_MIRROR>(x));
+    x = fmaxf(x, dpp_f32<DPP_ROW_MIRROR>(x));
+    return fmaxf(fmaxf(readlane_f32(x, 0), readlane_f32(x, 16)), fmaxf(readlane_f32(x, 32), readlane_f32(x, 48)));
+}
+
 __device__ __forceinline__ uint64_t umax64(uint64_t a, uint64_t b) { return a > b ? a : b; }
 
 __device__ __forceinline__ uint64_t readlane_u64(uint64_t x, int lane) {
