@@ -19,8 +19,8 @@ Prints ONE JSON line.  Besides the contract fields it carries
   aux_log_softmax_us   log q_aux over the whole vocabulary (Section 3.4) at the same shape
   break_even    the paper's Section 6 / Table 4 comparison: full vocabulary, a static 32K vocabulary
                 (gathered and pre-packed), SpecVocab with k = 2048 and 8192, whole steps
-  other_configs tree rows (config 3), the 262144-token head with a k sweep (config 4), 512 hidden
-                rows with selection (config 5), each next to the dense projection
+  other_configs tree rows (config 3; also with selection, at 8 and at 60 rows), the 262144-token head with a
+                k sweep (config 4), 512 hidden rows with selection (config 5), each next to the dense projection
   indexed_lm_head_microbenchmark   fused gather against materialise-then-multiply at four model
                 shapes, k from 512 to 32768 (the paper's kernel microbenchmark in kind)
 """
@@ -127,7 +127,35 @@ def other_configs(sv, torch, np, dev, capture, timed_replays):
                              "speedup_vs_dense": round(dense_us / step_us, 2),
                              "unique_rows_per_step": round(uniq), "unique_row_MB": round(uniq * c.d * 2 / 1e6, 1),
                              "dense_frac_hbm_peak": round(c.V * c.d * 2 / (dense_us * 1e-6) / 8e12, 3)}
-    del U, h, idx, z, zd
+    # the same shape with selection, at the width of one level of a small draft tree (8 rows) and at 60:
+    # the selector has random weights, so its sets are timed, and the draft step runs on config 3's recipe
+    from workloads import tree_subsets
+    c2 = CONFIGS[2]
+    Wd_np, Wv_np = c2.selector()
+    Wd, Wv = dev_bf16(Wd_np), dev_bf16(Wv_np)
+    for rows in (8, c.rows):
+        rng = make_rng(c.number, 100 + rows)
+        idx_r = torch.from_numpy(np.stack([tree_subsets(rng, c.V, rows, c.k, c.k // 2)[0] for _ in range(nst)])).to(dev)
+        h_r = h[:, :rows].contiguous()
+        sel = torch.empty((rows, c.k), dtype=torch.int32, device=dev)
+        ws_s = torch.empty(sv.workspace_bytes(sv.SV_OP_SELECT, rows, c.d, c.V, c.k, c2.d_prime, 0, sv.SV_BF16),
+                           dtype=torch.uint8, device=dev)
+        nb = sv.workspace_bytes(sv.SV_OP_DRAFT_STEP, rows, c.d, c.V, c.k, 0, c.kd, sv.SV_BF16)
+        ws_g = torch.empty(max(nb, 16), dtype=torch.uint8, device=dev)
+        zr = torch.empty((rows, c.k), dtype=torch.float32, device=dev)
+
+        def level(t):
+            sv.select(h_r[t % nst], Wd, Wv, c.k, idx_out=sel, ws=ws_s)
+            sv.draft_step(h_r[t % nst], U, idx_r[t % nst], c.kd, logits_out=zr, tok_out=tok[:rows],
+                          prob_out=prob[:rows], ws=ws_g)
+        sel_us = med_us(lambda t: sv.select(h_r[t % nst], Wd, Wv, c.k, idx_out=sel, ws=ws_s), 20)
+        lvl_us = med_us(level, 20)
+        dn_us = med_us(lambda t: sv.dense_logits(h_r[t % nst], U, out=zd[:rows]), 10)
+        out["config3_tree60"][f"with_selection_{rows}_rows"] = {
+            "select_us": round(sel_us, 1), "select_plus_step_us": round(lvl_us, 1), "dense_us": round(dn_us, 1),
+            "speedup_vs_dense": round(dn_us / lvl_us, 2)}
+        del idx_r, h_r, sel, ws_s, ws_g, zr
+    del U, h, idx, z, zd, Wd, Wv
     torch.cuda.empty_cache()
 
     # ---- config 4: V=262144, d=3840, 8 rows, k sweep, one set per step and one set per row
