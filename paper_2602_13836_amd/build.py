@@ -19,6 +19,9 @@ HIPCC_FLAGS = [
     "-Wno-unused-function",
     # keep fp32 arithmetic scalar: no compiler-formed packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the first kernel arguments arrive in scalar registers with the wavefront instead of being loaded by
+    # its first instructions (kernels that take plain arguments; a struct passed by value is not eligible)
+    "-mllvm", "-amdgpu-kernarg-preload-count=16",
 ]
 
 

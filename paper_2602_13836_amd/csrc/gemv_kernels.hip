@@ -109,8 +109,13 @@ __global__ __launch_bounds__(256) void gemv_rows_kernel(const GemvArgs a) {
 // a row are clamped to its last unit and meet zeros in the staged hidden row (FULL: rows of exactly
 // NL * 64 units, nothing to clamp -- the address arithmetic in front of the first requests is worth 1 %).
 constexpr int kOnceWaves = 4;       // measured: 2, 8 and 16 wavefronts per workgroup are all 1-5 % slower
+// The arguments the first requests need come first and one by one: plain leading arguments are preloaded
+// into scalar registers with the wavefront (a struct passed by value is fetched by the first instructions).
 template <int DT, int NL, bool OUT_BF16, bool FULL>
-__global__ __launch_bounds__(kOnceWaves * 64) void gemv_rows_once_kernel(const GemvArgs a) {
+__global__ __launch_bounds__(kOnceWaves * 64) void gemv_rows_once_kernel(
+    const char* __restrict__ x_base, const char* __restrict__ m_base, const int32_t* __restrict__ idx_base,
+    const int64_t n, const int64_t x_row_bytes, const int64_t m_row_bytes, const int64_t idx_row_stride,
+    const GemvArgs a) {
     constexpr int kT = kOnceWaves * 64;
     constexpr int kUnits = NL * 64;
     constexpr int kRounds = (kUnits + kT - 1) / kT;
@@ -119,12 +124,11 @@ __global__ __launch_bounds__(kOnceWaves * 64) void gemv_rows_once_kernel(const G
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t r = blockIdx.y;
-    const int64_t n = a.n_items;
-    const int last = a.chunks - 1;
+    const int last = FULL ? kUnits - 1 : a.chunks - 1;
     const int64_t it = (int64_t)blockIdx.x * kOnceWaves + wave;
 
     // request order as in gemv_rows_kernel: hidden row, scalar index, row of the matrix
-    const u32x4* xp = reinterpret_cast<const u32x4*>(a.x + r * a.x_row_bytes);
+    const u32x4* xp = reinterpret_cast<const u32x4*>(x_base + r * x_row_bytes);
     u32x4 xs[kRounds];
     int unit[kRounds];
 #pragma unroll
@@ -133,8 +137,8 @@ __global__ __launch_bounds__(kOnceWaves * 64) void gemv_rows_once_kernel(const G
         xs[q] = xp[FULL || unit[q] < last ? unit[q] : last];
     }
     const int64_t item = it < n ? it : n - 1;          // tail: recompute the last item, never stored
-    const int64_t row = a.idx ? (int64_t)a.idx[r * a.idx_row_stride + item] : item;   // -1: a padding slot
-    const u32x4* mp = reinterpret_cast<const u32x4*>(a.M + (row < 0 ? 0 : row) * a.m_row_bytes);
+    const int64_t row = idx_base ? (int64_t)idx_base[r * idx_row_stride + item] : item;   // -1: a padding slot
+    const u32x4* mp = reinterpret_cast<const u32x4*>(m_base + (row < 0 ? 0 : row) * m_row_bytes);
     u32x4 w[NL];
 #pragma unroll
     for (int c = 0; c < NL; ++c) {
@@ -257,13 +261,17 @@ template <int DT, int NL>
 hipError_t launch_once(const GemvArgs& a, hipStream_t stream) {
     dim3 grid((unsigned)((a.n_items + kOnceWaves - 1) / kOnceWaves), (unsigned)a.rows, 1), block(kOnceWaves * 64, 1, 1);
     const bool full = a.chunks == NL * 64;
+#define SV_ONCE(OUT, FULLROW)                                                                                     \
+    hipLaunchKernelGGL((gemv_rows_once_kernel<DT, NL, OUT, FULLROW>), grid, block, 0, stream, a.x, a.M, a.idx,    \
+                       a.n_items, a.x_row_bytes, a.m_row_bytes, a.idx_row_stride, a)
     if (a.out_bf16) {
-        if (full) hipLaunchKernelGGL((gemv_rows_once_kernel<DT, NL, true, true>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((gemv_rows_once_kernel<DT, NL, true, false>), grid, block, 0, stream, a);
+        if (full) SV_ONCE(true, true);
+        else SV_ONCE(true, false);
     } else {
-        if (full) hipLaunchKernelGGL((gemv_rows_once_kernel<DT, NL, false, true>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((gemv_rows_once_kernel<DT, NL, false, false>), grid, block, 0, stream, a);
+        if (full) SV_ONCE(false, true);
+        else SV_ONCE(false, false);
     }
+#undef SV_ONCE
     return hipGetLastError();
 }
 

@@ -7,8 +7,17 @@ namespace {
 
 using topk::kThreads;
 
+// what the first loads need comes first and as plain arguments: those are preloaded into scalar registers
+// with the wavefront, the struct is fetched by instructions
 template <int M, bool VEC>
-__global__ __launch_bounds__(kThreads) void softmax_topk_kernel(const TopkArgs a) {
+__global__ __launch_bounds__(kThreads) void softmax_topk_kernel(const float* logits, const int32_t* idx,
+                                                                const int64_t idx_row_stride, const int64_t k,
+                                                                const TopkArgs rest) {
+    TopkArgs a = rest;
+    a.logits = logits;
+    a.idx = idx;
+    a.idx_row_stride = idx_row_stride;
+    a.k = k;
     topk::softmax_topk_block<M, VEC>(a, blockIdx.x);
 }
 
@@ -18,9 +27,11 @@ hipError_t launch_m(const TopkArgs& a, hipStream_t stream) {
     const bool aligned = ((reinterpret_cast<uintptr_t>(a.logits) | reinterpret_cast<uintptr_t>(a.idx) |
                            reinterpret_cast<uintptr_t>(a.probs_full_out)) & 15u) == 0 && a.k % 4 == 0;
     if (can_vec && aligned)
-        hipLaunchKernelGGL((softmax_topk_kernel<M, can_vec>), dim3((unsigned)a.rows), dim3(kThreads), 0, stream, a);
+        hipLaunchKernelGGL((softmax_topk_kernel<M, can_vec>), dim3((unsigned)a.rows), dim3(kThreads), 0, stream,
+                           a.logits, a.idx, a.idx_row_stride, a.k, a);
     else
-        hipLaunchKernelGGL((softmax_topk_kernel<M, false>), dim3((unsigned)a.rows), dim3(kThreads), 0, stream, a);
+        hipLaunchKernelGGL((softmax_topk_kernel<M, false>), dim3((unsigned)a.rows), dim3(kThreads), 0, stream,
+                           a.logits, a.idx, a.idx_row_stride, a.k, a);
     return hipGetLastError();
 }
 
