@@ -140,8 +140,12 @@ __device__ __forceinline__ void locate_bin(const uint32_t (&c)[PER], uint32_t re
 // from one base address.  Loads are branch-free and all leave before the first product: a window that
 // would run past the last row is moved back to end at it (rows it re-computes are not stored or counted
 // again); vocabularies shorter than one window clamp row by row instead.
+// (leading plain arguments are preloaded into scalar registers with the wavefront; the struct is not)
 template <int DT, int G, int UNR, bool FULL>
-__global__ __launch_bounds__(kScoreThreads) void scores_hist_kernel(const ScoresArgs a, uint32_t* scratch) {
+__global__ __launch_bounds__(kScoreThreads) void scores_hist_kernel(const char* __restrict__ hp_base,
+                                                                    const char* __restrict__ wv_base, const int64_t V,
+                                                                    float* __restrict__ s_base, const int chunks,
+                                                                    const ScoresArgs a, uint32_t* scratch) {
     constexpr int RPW = 64 / G;                       // vocabulary rows per wave-wide load
     constexpr int64_t kWindow = (int64_t)RPW * UNR;   // rows per wavefront and iteration
     __shared__ uint32_t lh[kHistBins];
@@ -151,15 +155,14 @@ __global__ __launch_bounds__(kScoreThreads) void scores_hist_kernel(const Scores
     const int g = lane % G;                           // 16-byte unit within the row
     const int sub = lane / G;                         // which of the RPW rows
     const int64_t r = blockIdx.y;
-    const int C = FULL ? G : a.chunks;
-    const int64_t V = a.V;
+    const int C = FULL ? G : chunks;
     const int64_t row_bytes = (int64_t)C * 16;
 
     for (int b = tid; b < kHistBins; b += kScoreThreads) lh[b] = 0u;
     const int gc = (FULL || g < C) ? g : C - 1;
-    const u32x4 xraw = reinterpret_cast<const u32x4*>(a.hp + r * row_bytes)[gc];
+    const u32x4 xraw = reinterpret_cast<const u32x4*>(hp_base + r * row_bytes)[gc];
     const u32x4 xreg = (FULL || g < C) ? xraw : zero16();   // units past the end of a row meet zeros
-    float* s = a.s + r * V;
+    float* s = s_base + r * V;
     __syncthreads();
 
     const int64_t step = (int64_t)gridDim.x * kScoreWaves * kWindow;
@@ -171,7 +174,7 @@ __global__ __launch_bounds__(kScoreThreads) void scores_hist_kernel(const Scores
             const int64_t b0 = (TINY || base + kWindow <= V) ? base : V - kWindow;
             u32x4 w[UNR];
             if constexpr (!TINY) {
-                const char* p = a.Wv + (b0 + sub) * row_bytes + (int64_t)gc * 16;
+                const char* p = wv_base + (b0 + sub) * row_bytes + (int64_t)gc * 16;
 #pragma unroll
                 for (int u = 0; u < UNR; ++u)
                     w[u] = load16<false>(reinterpret_cast<const u32x4*>(p + (int64_t)u * RPW * row_bytes));
@@ -179,7 +182,7 @@ __global__ __launch_bounds__(kScoreThreads) void scores_hist_kernel(const Scores
 #pragma unroll
                 for (int u = 0; u < UNR; ++u) {
                     const int64_t v = b0 + (int64_t)u * RPW + sub;
-                    w[u] = load16<false>(reinterpret_cast<const u32x4*>(a.Wv + (v < V ? v : V - 1) * row_bytes) + gc);
+                    w[u] = load16<false>(reinterpret_cast<const u32x4*>(wv_base + (v < V ? v : V - 1) * row_bytes) + gc);
                 }
             }
             __builtin_amdgcn_sched_barrier(0);        // every request leaves before anything waits
@@ -268,10 +271,10 @@ hipError_t launch_scores_g(const ScoresArgs& a, uint32_t* scratch, int cus, hipS
     if (bx > cap) bx = cap;
     if (a.chunks == G)
         hipLaunchKernelGGL((scores_hist_kernel<DT, G, UNR, true>), dim3((unsigned)bx, (unsigned)a.rows),
-                           dim3(kScoreThreads), 0, stream, a, scratch);
+                           dim3(kScoreThreads), 0, stream, a.hp, a.Wv, a.V, a.s, a.chunks, a, scratch);
     else
         hipLaunchKernelGGL((scores_hist_kernel<DT, G, UNR, false>), dim3((unsigned)bx, (unsigned)a.rows),
-                           dim3(kScoreThreads), 0, stream, a, scratch);
+                           dim3(kScoreThreads), 0, stream, a.hp, a.Wv, a.V, a.s, a.chunks, a, scratch);
     return hipGetLastError();
 }
 
