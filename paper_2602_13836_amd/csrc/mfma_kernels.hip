@@ -28,8 +28,30 @@ constexpr int kSteps = kKC / 32;                 // MFMA k-steps per slice (8)
 constexpr int kXRowBytes = kKC * 2 + 16;         // padded LDS row of the x slice (528 B = 132 words)
 
 // WPB wavefronts per workgroup (16 rows of M each); NB blocks of 16 hidden rows (N = 16 NB)
+// (what the first requests need is repeated as leading plain arguments: those are preloaded into scalar
+// registers with the wavefront, a struct passed by value is fetched by instructions)
+#define SV_HOT_PARAMS                                                                                          \
+    const char *__restrict__ m_base, const int32_t *__restrict__ idx_base, const char *__restrict__ x_base,    \
+        const int64_t n_items_arg, const int64_t m_row_bytes_arg, const int64_t x_row_bytes_arg,               \
+        const uint32_t *__restrict__ n_items_dev_arg
+#define SV_HOT_ARGS(a) (a).M, (a).idx, (a).x, (a).n_items, (a).m_row_bytes, (a).x_row_bytes, (a).n_items_dev
+__device__ __forceinline__ GemvArgs with_hot(GemvArgs a, const char* m_base, const int32_t* idx_base, const char* x_base,
+                                             int64_t n_items, int64_t m_row_bytes, int64_t x_row_bytes,
+                                             const uint32_t* n_items_dev) {
+    a.M = m_base;
+    a.idx = idx_base;
+    a.x = x_base;
+    a.n_items = n_items;
+    a.m_row_bytes = m_row_bytes;
+    a.x_row_bytes = x_row_bytes;
+    a.n_items_dev = n_items_dev;
+    return a;
+}
+
 template <int WPB, int NB>
-__global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(const GemvArgs a, const int row0) {
+__global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(SV_HOT_PARAMS, const GemvArgs rest, const int row0) {
+    const GemvArgs a = with_hot(rest, m_base, idx_base, x_base, n_items_arg, m_row_bytes_arg, x_row_bytes_arg,
+                                n_items_dev_arg);
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];     // [2][16 NB][kXRowBytes]
     constexpr int N = 16 * NB;
     constexpr int kThreads = WPB * 64;
@@ -155,7 +177,10 @@ __global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(const GemvArgs a,
 // selector's down-projection of Section 3.3 Step 1); output float32 or bf16 (round to nearest even);
 // the launch can also clear scratch words of a later kernel.
 template <int NB>
-__global__ __launch_bounds__(512) void skinny_mfma_ksplit_kernel(const GemvArgs a, const int row_base) {
+__global__ __launch_bounds__(512) void skinny_mfma_ksplit_kernel(SV_HOT_PARAMS, const GemvArgs rest,
+                                                                 const int row_base) {
+    const GemvArgs a = with_hot(rest, m_base, idx_base, x_base, n_items_arg, m_row_bytes_arg, x_row_bytes_arg,
+                                n_items_dev_arg);
     constexpr int WPB = 8;
     constexpr int N = 16 * NB;
     __shared__ f32x4_t s_part[WPB][NB][64];
@@ -273,7 +298,7 @@ template <int NB>
 hipError_t launch_ksplit(const GemvArgs& a, int row0, int groups, hipStream_t stream) {
     const int64_t bx = (a.n_items + 15) / 16;
     hipLaunchKernelGGL((skinny_mfma_ksplit_kernel<NB>), dim3((unsigned)bx, (unsigned)groups), dim3(512), 0, stream,
-                       a, row0);
+                       SV_HOT_ARGS(a), a, row0);
     return hipGetLastError();
 }
 
@@ -295,7 +320,8 @@ hipError_t launch_wn(const GemvArgs& a, int row0, hipStream_t stream) {
             configured[dev] = true;
         }
     }
-    hipLaunchKernelGGL((skinny_mfma_kernel<WPB, NB>), dim3((unsigned)bx), dim3(WPB * 64), lds, stream, a, row0);
+    hipLaunchKernelGGL((skinny_mfma_kernel<WPB, NB>), dim3((unsigned)bx), dim3(WPB * 64), lds, stream, SV_HOT_ARGS(a),
+                       a, row0);
     return hipGetLastError();
 }
 
