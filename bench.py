@@ -369,7 +369,7 @@ def main():
     gather_gbps = gather_bytes / (gather_us * 1e-6) / 1e9
     # HBM-side bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB plain copy
     # (profiles/gather_gemv_config2_hbm_traffic.md)
-    traffic_bytes = 67.473e6 + 0.066e6
+    traffic_bytes = 67.487e6 + 0.066e6
     roofline = {"bound": "hbm",
                 "kernel": "gemv_rows_once_kernel<bf16, 8 loads/lane, 1 row/wave>: row gather of 8192 rows of U "
                           "(specvocab_subset_logits), 1 of the 2 launches of a step",
