@@ -20,9 +20,11 @@
 //                 its scores in bins above B (all selected) and appends (key, id) of its scores in
 //                 bin B to the row's candidate list.
 //   resolve       MSB-first radix selection among the candidates over the remaining 20 key bits
-//                 and, only if scores tie exactly, the inverted id bits, which yields a 64-bit
-//                 threshold T with  selected(v) <=> (key(v) << 32 | ~v) >= T ; it also turns the
-//                 per-block counts into output offsets.  With up to 8 hidden rows every emit block
+//                 and, only if scores tie exactly, the inverted id bits (digits of 11, 9, 11, 11 and
+//                 10 bits; as soon as at most 64 candidates share the decided prefix, one wavefront
+//                 ranks them by counting instead), which yields a 64-bit threshold T with
+//                 selected(v) <=> (key(v) << 32 | ~v) >= T ; it also turns the per-block counts into
+//                 output offsets (all of them, or just the one block's that asks).  With up to 8 hidden rows every emit block
 //                 does this itself (redundant work, one launch less); with more rows it is one
 //                 block per row in a launch of its own.
 //   emit          every block re-evaluates the predicate on its entries in id order and writes the

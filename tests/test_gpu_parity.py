@@ -40,7 +40,7 @@ LOGIT_SHAPES = [
     ("bf16", 5, 4096, 2048, 1, "per_row"),       # k = 1
     ("bf16", 2, 520, 301, 301, "per_step"),      # k = V
     ("bf16", 1, 8192, 600, 129, "per_row"),      # 16 loads per lane
-    ("bf16", 2, 8200, 300, 50, "per_row"),       # longer than the register-resident path
+    ("bf16", 2, 8200, 300, 50, "per_row"),       # longer than 16 KiB: the kernel that walks a row in pieces
     ("f32", 2, 260, 500, 64, "per_row"),
     ("f32", 1, 4096, 700, 100, "per_step"),      # 16 loads per lane, float32
     ("f32", 2, 4100, 300, 33, "per_row"),        # long-row path, float32
