@@ -22,6 +22,8 @@
  * Stream.   `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *           enqueue work: they do not synchronise, do not read device memory on the host, and can
  *           be captured into a HIP graph.  Outputs are valid once the stream reaches that point.
+ *           The first call on a device also runs a one-time device set-up (see specvocab_init); a
+ *           caller whose first call would fall inside a stream capture calls specvocab_init before.
  * Workspace.`ws` is device scratch of at least specvocab_workspace_bytes(...) bytes for the same
  *           shape (may be NULL when that is 0).  Its contents need not be initialised and are
  *           undefined afterwards.  Calls that share a workspace must be ordered on one stream.
@@ -38,7 +40,8 @@
  *           (round-to-nearest-even) before the second projection; with SV_F32 it stays float32.
  * Ties.     Wherever "largest" decides, equal values are ordered by smaller token id first.
  * Threads.  Entry points may be called from several host threads; the library keeps no per-call
- *           state on the host (only idempotent per-process caches of device attributes).
+ *           state on the host (only the per-device set-up, done once under a lock and read-only
+ *           afterwards).
  */
 #ifndef SPECVOCAB_H
 #define SPECVOCAB_H
@@ -97,6 +100,13 @@ typedef enum {
 
 /* SPECVOCAB_VERSION of the loaded library. */
 int specvocab_version(void);
+
+/* One-time set-up of the current HIP device: device attributes, the opt-in of the kernels that use more
+ * than 64 KiB of LDS.
+ * Every entry point does this by itself on its first call on a device; call specvocab_init explicitly,
+ * once per device and outside any stream capture, when that first call would otherwise happen while a
+ * stream is being captured.  Idempotent and thread-safe.  Returns SV_OK or SV_ERR_HIP. */
+int specvocab_init(void);
 
 /* Static, NUL-terminated description of an sv_status value. */
 const char* specvocab_status_string(int status);

@@ -26,6 +26,7 @@ MAX_KD = 64
 
 EXPORTS = (
     "specvocab_version",
+    "specvocab_init",
     "specvocab_status_string",
     "specvocab_workspace_bytes",
     "specvocab_select",
@@ -71,6 +72,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.specvocab_select.restype = ci
     lib.specvocab_select.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, ci, i64, vp, vp, vp,
                                      ctypes.c_size_t, vp]
+    lib.specvocab_init.restype = ci
+    lib.specvocab_init.argtypes = []
     lib.specvocab_select_threshold.restype = ci
     lib.specvocab_select_threshold.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, ci, i64, ctypes.c_float, vp, vp,
                                                vp, ctypes.c_size_t, vp]
@@ -93,6 +96,12 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     if path is None:
         _lib = lib
     return lib
+
+
+def init() -> None:
+    """specvocab_init: one-time set-up of the current device (needed explicitly only before a first call that
+    would fall inside a stream capture)."""
+    _check(load_library().specvocab_init(), "specvocab_init")
 
 
 def version() -> int:

@@ -9,22 +9,55 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
+#include <mutex>
+
 namespace sv {
 
-hipError_t device_info(DeviceInfo* out) {
-    static DeviceInfo cached[64] = {};
+namespace {
+
+// Per-device set-up, done once under a lock and published with release/acquire: device attributes, the
+// and the opt-in of the kernels that use more than 64 KiB of LDS.
+struct DeviceState {
+    std::atomic<int> ready{0};
+    int cus = 0;
+};
+constexpr int kMaxDevices = 64;
+DeviceState g_dev[kMaxDevices];
+std::mutex g_dev_mutex;
+
+hipError_t device_state(const DeviceState** out) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-    if (!cached[dev].valid) {
-        int cus = 0;
-        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess) return e;
-        cached[dev].cus = cus > 0 ? cus : 256;
-        cached[dev].valid = 1;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    DeviceState& st = g_dev[dev];
+    if (!st.ready.load(std::memory_order_acquire)) {
+        std::lock_guard<std::mutex> lock(g_dev_mutex);
+        if (!st.ready.load(std::memory_order_relaxed)) {
+            int cus = 0;
+            e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+            if (e != hipSuccess) return e;
+            st.cus = cus > 0 ? cus : 256;
+            e = configure_skinny_mfma_lds();
+            if (e != hipSuccess) return e;
+            e = configure_tile_mfma_lds();
+            if (e != hipSuccess) return e;
+            st.ready.store(1, std::memory_order_release);
+        }
     }
-    *out = cached[dev];
+    *out = &st;
+    return hipSuccess;
+}
+
+}  // namespace
+
+hipError_t device_info(DeviceInfo* out) {
+    const DeviceState* st = nullptr;
+    hipError_t e = device_state(&st);
+    if (e != hipSuccess) return e;
+    out->cus = st->cus;
+    out->valid = 1;
     return hipSuccess;
 }
 
@@ -50,6 +83,12 @@ inline int check_row(int64_t n, int64_t ld, int dt) {
     if (n % per16 != 0) return SV_ERR_UNSUPPORTED;
     if (ld % per16 != 0) return SV_ERR_ALIGN;
     return SV_OK;
+}
+
+// the library's per-device set-up, if this is the first call on the current device
+inline int ensure_device() {
+    sv::DeviceInfo di;
+    return sv::device_info(&di) == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
 
 struct SelectWs {
@@ -133,17 +172,25 @@ int launch_gather(int dt, const void* h, int64_t rows, int64_t d, int64_t ldh, c
                   size_t ws_bytes, hipStream_t s) {
     const bool padded = is_padded(idx_mode);
     const int64_t sets = base_mode(idx_mode) == SV_IDX_PER_ROW ? rows : 1;
+    const sv::GemvArgs g0 = gather_args(h, rows, d, ldh, U, ldu, dt, idx, k, idx_mode, logits_out);
+    // everything the call will need from the workspace (clean copy of a padded list, union of the sets) is
+    // checked here, before the first launch
+    const bool copy = padded && padded_needs_copy(dt, g0);
+    const size_t pb = copy ? pad_ws_bytes(rows, k, idx_mode, dt, g0) : 0;
+    const size_t need = pb + (sv::union_path_wanted(dt, g0) ? sv::union_ws_bytes(rows, V, k) : 0);
+    if (need) {
+        if (!ws || ws_bytes < need) return SV_ERR_WORKSPACE;
+        if (!aligned16(ws)) return SV_ERR_ALIGN;
+    }
+    sv::DeviceInfo di;
+    if (sv::device_info(&di) != hipSuccess) return SV_ERR_HIP;       // device set-up, if this is the first call
     int st = validate_indices(idx, sets * k, V, s, padded);
     if (st != SV_OK) return st;
+    if (padded && !copy) return sv::launch_gemv(dt, g0, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
     const int32_t* use = idx;
     char* rest = static_cast<char*>(ws);
     size_t rest_bytes = ws_bytes;
-    const sv::GemvArgs g0 = gather_args(h, rows, d, ldh, U, ldu, dt, idx, k, idx_mode, logits_out);
-    if (padded && !padded_needs_copy(dt, g0)) return sv::launch_gemv(dt, g0, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
-    if (padded) {
-        const size_t pb = pad_ws_bytes(rows, k, idx_mode, dt, g0);
-        if (!ws || ws_bytes < pb) return SV_ERR_WORKSPACE;
-        if (!aligned16(ws)) return SV_ERR_ALIGN;
+    if (copy) {
         if (sv::launch_pad_clean(idx, sets * k, reinterpret_cast<int32_t*>(ws), s) != hipSuccess) return SV_ERR_HIP;
         use = reinterpret_cast<const int32_t*>(ws);
         rest += pb;
@@ -152,7 +199,7 @@ int launch_gather(int dt, const void* h, int64_t rows, int64_t d, int64_t ldh, c
     const sv::GemvArgs g = gather_args(h, rows, d, ldh, U, ldu, dt, use, k, idx_mode, logits_out);
     st = launch_rows_product(dt, g, V, rest_bytes ? rest : nullptr, rest_bytes, s);
     if (st != SV_OK) return st;
-    if (padded && sv::launch_pad_mask(idx, g.idx_row_stride, (int)rows, k, logits_out, s) != hipSuccess)
+    if (copy && sv::launch_pad_mask(idx, g.idx_row_stride, (int)rows, k, logits_out, s) != hipSuccess)
         return SV_ERR_HIP;
     return SV_OK;
 }
@@ -288,6 +335,7 @@ static int select_impl(const void* h, int64_t rows, int64_t d, int64_t ldh, cons
     if (!aligned16(h) || !aligned16(W_down) || !aligned16(W_vocab) || !aligned16(ws)) return SV_ERR_ALIGN;
     const SelectWs w = select_ws(rows, V, d_prime, dt);
     if (!ws || ws_bytes < w.total) return SV_ERR_WORKSPACE;
+    if (ensure_device() != SV_OK) return SV_ERR_HIP;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int es = esize_of(dt);
@@ -355,6 +403,8 @@ int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh, const 
                        ws_bytes, stream);
 }
 
+int specvocab_init(void) { return ensure_device(); }
+
 int specvocab_select_threshold(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* W_down,
                                int64_t d_prime, const void* W_vocab, int64_t V, int dt, int64_t k, float tau,
                                int32_t* idx_out, float* scores_out, void* ws, size_t ws_bytes, void* stream) {
@@ -374,6 +424,7 @@ int specvocab_aux_log_softmax(const void* h, int64_t rows, int64_t d, int64_t ld
     if (!aligned16(h) || !aligned16(W_down) || !aligned16(W_vocab) || !aligned16(ws)) return SV_ERR_ALIGN;
     const AuxWs w = aux_ws(rows, V, d_prime, dt);
     if (!ws || ws_bytes < w.total) return SV_ERR_WORKSPACE;
+    if (ensure_device() != SV_OK) return SV_ERR_HIP;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int es = esize_of(dt);
@@ -429,6 +480,7 @@ int specvocab_indexed_head_naive(const void* h, int64_t rows, int64_t d, int64_t
     const int64_t sets = idx_mode == SV_IDX_PER_ROW ? rows : 1;
     const size_t need = (size_t)sets * (size_t)k * (size_t)d * (size_t)es;
     if (!ws || ws_bytes < need) return SV_ERR_WORKSPACE;
+    if (ensure_device() != SV_OK) return SV_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
     st = validate_indices(idx, sets * k, V, s);
     if (st != SV_OK) return st;
@@ -463,6 +515,7 @@ int specvocab_pack_rows(const void* U, int64_t V, int64_t d, int64_t ldu, int dt
     int st = check_row(d, ldu, dt);
     if (st != SV_OK) return st;
     if (!aligned16(U) || !aligned16(U_packed)) return SV_ERR_ALIGN;
+    if (ensure_device() != SV_OK) return SV_ERR_HIP;
     hipStream_t s = static_cast<hipStream_t>(stream);
     st = validate_indices(idx, k, V, s);
     if (st != SV_OK) return st;
@@ -483,6 +536,7 @@ int specvocab_draft_topk(const float* logits, const int32_t* idx, int idx_mode, 
     if (rows < 1 || k < 1 || k > kMaxVocab || kd < 1 || kd > k) return SV_ERR_SHAPE;
     if (kd > SPECVOCAB_MAX_KD) return SV_ERR_UNSUPPORTED;
     if (rows > kMaxVocab) return SV_ERR_SHAPE;
+    if (ensure_device() != SV_OK) return SV_ERR_HIP;
 
     sv::TopkArgs t{};
     t.logits = logits;
@@ -540,6 +594,7 @@ int specvocab_dense_logits(const void* h, int64_t rows, int64_t d, int64_t ldh, 
     st = check_row(d, ldu, dt);
     if (st != SV_OK) return st;
     if (!aligned16(h) || !aligned16(U)) return SV_ERR_ALIGN;
+    if (ensure_device() != SV_OK) return SV_ERR_HIP;
 
     const int es = esize_of(dt);
     sv::GemvArgs g{};

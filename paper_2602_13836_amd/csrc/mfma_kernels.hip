@@ -295,6 +295,25 @@ __global__ __launch_bounds__(512) void skinny_mfma_ksplit_kernel(SV_HOT_PARAMS, 
 }
 
 template <int NB>
+constexpr size_t skinny_lds_bytes() { return (size_t)2 * 16 * NB * kXRowBytes; }
+
+// more than 64 KiB of dynamic LDS needs an explicit opt-in per kernel instance and device
+template <int WPB, int NB>
+hipError_t opt_in_lds() {
+    if (skinny_lds_bytes<NB>() <= 64 * 1024) return hipSuccess;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&skinny_mfma_kernel<WPB, NB>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)skinny_lds_bytes<NB>());
+}
+template <int WPB>
+hipError_t opt_in_lds_all_nb() {
+    hipError_t e = opt_in_lds<WPB, 1>();
+    if (e == hipSuccess) e = opt_in_lds<WPB, 2>();
+    if (e == hipSuccess) e = opt_in_lds<WPB, 3>();
+    if (e == hipSuccess) e = opt_in_lds<WPB, 4>();
+    return e;
+}
+
+template <int NB>
 hipError_t launch_ksplit(const GemvArgs& a, int row0, int groups, hipStream_t stream) {
     const int64_t bx = (a.n_items + 15) / 16;
     hipLaunchKernelGGL((skinny_mfma_ksplit_kernel<NB>), dim3((unsigned)bx, (unsigned)groups), dim3(512), 0, stream,
@@ -306,20 +325,7 @@ template <int WPB, int NB>
 hipError_t launch_wn(const GemvArgs& a, int row0, hipStream_t stream) {
     const int64_t per_block = (int64_t)WPB * 16;
     const int64_t bx = (a.n_items + per_block - 1) / per_block;
-    const size_t lds = (size_t)2 * 16 * NB * kXRowBytes;
-    if (lds > 64 * 1024) {                        // more than 64 KiB of LDS needs an explicit opt-in,
-        static bool configured[64] = {};          // once per device and instance
-        int dev = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e != hipSuccess) return e;
-        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-        if (!configured[dev]) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&skinny_mfma_kernel<WPB, NB>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            configured[dev] = true;
-        }
-    }
+    const size_t lds = skinny_lds_bytes<NB>();     // above 64 KiB: opted in by configure_skinny_mfma_lds()
     hipLaunchKernelGGL((skinny_mfma_kernel<WPB, NB>), dim3((unsigned)bx), dim3(WPB * 64), lds, stream, SV_HOT_ARGS(a),
                        a, row0);
     return hipGetLastError();
@@ -334,6 +340,15 @@ hipError_t launch_w(const GemvArgs& a, int row0, int nrows, hipStream_t stream) 
 }
 
 }  // namespace
+
+// every instance launch_skinny_mfma can pick, on the current device (called once per device, outside any
+// stream capture, by the library's device set-up)
+hipError_t configure_skinny_mfma_lds() {
+    hipError_t e = opt_in_lds_all_nb<2>();
+    if (e == hipSuccess) e = opt_in_lds_all_nb<4>();
+    if (e == hipSuccess) e = opt_in_lds_all_nb<8>();
+    return e;
+}
 
 // bf16, rows >= 2, one shared set of rows of M (dense or one index list for the whole step)
 bool skinny_mfma_supported(int dt, const GemvArgs& a) {

@@ -11,8 +11,13 @@ struct DeviceInfo {
     int cus;         // compute units of the current device
     int valid;
 };
-// cached per process; queries the current device the first time
+// Cached per device; the first call on a device runs the library's device set-up (attributes, LDS opt-in of
+// the large matrix-core kernels, address of the static scratch array) under a lock.  That first call must
+// not happen while the calling thread's stream is being captured: specvocab_init() exists for that.
 hipError_t device_info(DeviceInfo* out);
+// opt-in of the kernel instances that need more than 64 KiB of LDS, on the current device
+hipError_t configure_skinny_mfma_lds();
+hipError_t configure_tile_mfma_lds();
 
 // out[r, j] = < M[row(r, j), :], x[r, :] >  for j in [0, n_items)
 //   row(r, j) = j                       if idx == nullptr   (dense)

@@ -265,6 +265,17 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
         }
 }
 
+template <int GM, int GN, int WM, int WN>
+constexpr size_t tile_lds_bytes() { return (size_t)2 * (32 * GM * WM + 32 * GN * WN) * kRowB; }
+
+// more than 64 KiB of dynamic LDS needs an explicit opt-in per kernel instance and device
+template <int GM, int GN, int WM, int WN, bool PIPE>
+hipError_t opt_in_lds() {
+    if (tile_lds_bytes<GM, GN, WM, WN>() <= 64 * 1024) return hipSuccess;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&tile_mfma_kernel<GM, GN, WM, WN, PIPE>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)tile_lds_bytes<GM, GN, WM, WN>());
+}
+
 template <int GM, int GN, int WM, int WN, bool PIPE>
 hipError_t launch_tile(const GemvArgs& a, hipStream_t stream) {
     constexpr int TM = 32 * GM * WM, TN = 32 * GN * WN;
@@ -273,25 +284,21 @@ hipError_t launch_tile(const GemvArgs& a, hipStream_t stream) {
     const int64_t groups = (IT + kXcds - 1) / kXcds;            // item tiles per XCD, rounded up
     const int64_t bx = groups * RT * kXcds;
     if (bx > 0x7fffffffLL) return hipErrorInvalidValue;         // more tiles than a grid dimension holds
-    const size_t lds = (size_t)2 * (TM + TN) * kRowB;
-    if (lds > 64 * 1024) {                                      // more than 64 KiB of LDS needs an explicit opt-in,
-        static bool configured[64] = {};                        // once per device and instance
-        int dev = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e != hipSuccess) return e;
-        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-        if (!configured[dev]) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tile_mfma_kernel<GM, GN, WM, WN, PIPE>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            configured[dev] = true;
-        }
-    }
+    const size_t lds = tile_lds_bytes<GM, GN, WM, WN>();     // above 64 KiB: opted in by configure_tile_mfma_lds()
     hipLaunchKernelGGL((tile_mfma_kernel<GM, GN, WM, WN, PIPE>), dim3((unsigned)bx), dim3(64 * GM * GN), lds, stream, a);
     return hipGetLastError();
 }
 
 }  // namespace
+
+// every instance launch_tile_mfma can pick, on the current device (called once per device, outside any
+// stream capture, by the library's device set-up)
+hipError_t configure_tile_mfma_lds() {
+    hipError_t e = opt_in_lds<2, 2, 2, 2, false>();
+    if (e == hipSuccess) e = opt_in_lds<2, 4, 4, 2, true>();
+    if (e == hipSuccess) e = opt_in_lds<2, 2, 2, 2, true>();
+    return e;
+}
 
 hipError_t launch_tile_mfma(const GemvArgs& a, hipStream_t stream) {
     if (a.n_items <= 0 || a.rows <= 0) return hipSuccess;

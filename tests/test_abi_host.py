@@ -115,6 +115,17 @@ def test_dense_select_topk_reject_bad_arguments(lib):
     assert lib.specvocab_indexed_head_naive(A, 1, 256, 256, A, 1000, 256, 1, A, 100, 4, A, A, 1 << 30, None) == 6
     assert lib.specvocab_subset_logits(A, 1, 256, 256, A, 1000, 256, 1, A, 100, 2, A, None, 0, None) == 3
 
+    # several hidden rows with their own padded lists: the clean copy AND the union of the sets must fit, and
+    # that is decided before anything is enqueued (a workspace that holds the clean copy only is refused)
+    both = sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 20, 256, 5000, 1000, idx_mode=sv.SV_IDX_PER_ROW | sv.SV_IDX_PADDED)
+    pad_only = 20 * 1000 * 4
+    assert both > pad_only + 5000 * 8
+    assert lib.specvocab_subset_logits(A, 20, 256, 256, A, 5000, 256, 1, A, 1000, 4, A, A, 80128, None) == 5
+    assert lib.specvocab_subset_logits(A, 20, 256, 256, A, 5000, 256, 1, A, 1000, 4, A, A, both - 1, None) == 5
+    assert lib.specvocab_subset_logits(A, 20, 256, 256, A, 5000, 256, 1, A, 1000, 4, A, MIS, both, None) == 4
+    assert lib.specvocab_draft_step(A, 20, 256, 256, A, 5000, 256, 1, A, 1000, 4, 10, A, A, A, None, A, 80128,
+                                    None) == 5
+
     q = lib.specvocab_aux_log_softmax
     assert q(A, 1, 256, 256, A, 32, A, 1000, 1, None, A, 1 << 30, None) == 1
     assert q(A, 1, 256, 256, A, 32, A, 1000, 1, A, None, 0, None) == 5

@@ -578,6 +578,8 @@ def test_select_is_exact_on_integer_valued_inputs():
     rng = np.random.default_rng(12345)
     for case in range(60):
         rows = int(rng.choice([1, 1, 2, 3, 4, 5, 6, 9, 17]))
+        if case % 10 == 9:
+            rows = (17, 70, 300)[(case // 10) % 3]            # batches: the matrix-core forms of the selection
         V = int(rng.choice([1, 2, 3, 5, 63, 64, 100, 1000, 4095, 4096, 4097, 9000, 20000, 70001]))
         k = min(V, int(rng.choice([1, 2, max(1, V // 16), max(1, V // 2), max(1, V - 1), V])))
         dp = int(rng.choice([8, 16, 24, 64]))
@@ -595,6 +597,26 @@ def test_select_is_exact_on_integer_valued_inputs():
         ref_idx, ref_sc = oracle.select(h, Wd, Wv, k, tau=tau)[:2]
         assert np.array_equal(idx.cpu().numpy(), ref_idx), (case, dtype, rows, V, k)
         assert np.array_equal(sc.cpu().numpy(), ref_sc.astype(np.float32)), (case, dtype, rows, V, k)
+
+
+@pytest.mark.parametrize("rows", [1, 12, 70])
+def test_select_is_exact_at_the_full_vocabulary(rows):
+    """The same exactness at the size of the Qwen3-8B-shaped configuration (V = 151936, d' = 256, k = 8192):
+    integer-valued inputs, thousands of exactly tied scores around the k-th, every id equal to the oracle's."""
+    say(f"integer select at V=151936 d'=256 rows={rows}")
+    rng = np.random.default_rng(151936 + rows)
+    V, dp, d, k = 151936, 256, 264, 8192
+    h = _int_valued(rng, (rows, d), 2, "bf16")
+    Wd = np.zeros((dp, d), np.float32)
+    Wd[np.arange(dp), np.arange(dp)] = 1.0
+    Wd = f32_to_bf16_bits(Wd)
+    Wv = _int_valued(rng, (V, dp), 2, "bf16")
+    idx, sc = sv.select(to_dev(h), to_dev(Wd), to_dev(Wv), k, want_scores=True)
+    ref_idx, ref_sc = oracle.select(h, Wd, Wv, k)[:2]
+    assert np.array_equal(idx.cpu().numpy(), ref_idx)
+    assert np.array_equal(sc.cpu().numpy(), ref_sc.astype(np.float32))
+    idx2, _ = sv.select(to_dev(h), to_dev(Wd), to_dev(Wv), k)          # without the scores output
+    assert torch.equal(idx2, idx)
 
 
 def test_draft_step_is_exact_on_integer_valued_inputs():
@@ -738,8 +760,9 @@ def test_config2_chain_full_size(llama_head):
     say("config 2 shape with the selector (d'=256)")
     sel, sc = sv.select(to_dev(hs[0]), tWd, tWv, c.k, want_scores=True)
     ref_sel, _, s_ref, _ = oracle.select(hs[0], Wd, Wv, c.k, full=True)
-    band, diff = check_selected_set(sel[0].cpu().numpy(), s_ref[0], ref_sel[0], c.k, "bf16")
-    say(f"  {band} scores within tolerance of the k-th, {diff} ids differ from the oracle")
+    band, diff, band_s, outside = check_selected_set(sel[0].cpu().numpy(), s_ref[0], ref_sel[0], c.k, "bf16", tight=True)
+    say(f"  config 2 select: {band} scores within 2e-2 of the k-th, {band_s} within 1e-3, {diff} ids differ from "
+        f"the oracle's set, {outside} of them outside the 1e-3 band")
     assert_logits_close(sc[0].cpu().numpy(), s_ref[0, sel[0].cpu().numpy()], "bf16")
 
 
@@ -754,11 +777,12 @@ def test_config3_tree_full_size(llama_head):
     z = sv.subset_logits(th, tU, tidx)
     tok, prob, _ = sv.draft_topk(z, tidx, c.kd)
     zn, tokn, probn = z.cpu().numpy(), tok.cpu().numpy(), prob.cpu().numpy()
-    for r in (0, 17, 59):
-        z_ref = oracle.subset_logits(h[r:r + 1], U, idx[r:r + 1])
-        assert_logits_close(zn[r:r + 1], z_ref, "bf16")
-        tok_ref, prob_ref = oracle.softmax_topk(z_ref, idx[r:r + 1], c.kd)
-        check_draft_tokens(tokn[r], probn[r], z_ref[0], idx[r], tok_ref[0], prob_ref[0], "bf16")
+    z_ref = oracle.subset_logits(h, U, idx)                  # all 60 rows x 4096 entries
+    err = assert_logits_close(zn, z_ref, "bf16")
+    say(f"  config 3: all {c.rows} x {c.k} logits against the oracle, max |err| = {err:.3e}")
+    tok_ref, prob_ref = oracle.softmax_topk(z_ref, idx, c.kd)
+    for r in range(c.rows):
+        check_draft_tokens(tokn[r], probn[r], z_ref[r], idx[r], tok_ref[r], prob_ref[r], "bf16")
     tok_same, _ = oracle.softmax_topk(zn, idx, c.kd)
     assert np.array_equal(tokn, tok_same)
     # property that holds for every row: shared tokens get the logit <U[tok], h_r> whichever row asks
@@ -779,16 +803,20 @@ def test_config4_gemma_head_full_size():
         say(f"config 4 k={k}")
         shared = zipf_subset(rng, c.V, k)
         z = sv.subset_logits(th, tU, torch.from_numpy(shared).to(DEV)).cpu().numpy()
-        sample = rng.permutation(k)[:512]
-        z_ref = oracle.subset_logits(h, U, shared[sample])
-        assert_logits_close(z[:, sample], z_ref, "bf16")
+        err = assert_logits_close(z, oracle.subset_logits(h, U, shared), "bf16")     # every entry, all 8 rows
+        say(f"  shared set: all {c.rows} x {k} logits against the oracle, max |err| = {err:.3e}")
         per_row = np.stack([zipf_subset(rng, c.V, k) for _ in range(c.rows)])
         z = sv.subset_logits(th, tU, torch.from_numpy(per_row).to(DEV))
-        z_ref = oracle.subset_logits(h, U, per_row[:, sample])
-        assert_logits_close(z.cpu().numpy()[:, sample], z_ref, "bf16")
+        z_ref = oracle.subset_logits(h, U, per_row)
+        err = assert_logits_close(z.cpu().numpy(), z_ref, "bf16")
+        say(f"  one set per row: all {c.rows} x {k} logits against the oracle, max |err| = {err:.3e}")
         tok, _, _ = sv.draft_topk(z, torch.from_numpy(per_row).to(DEV), c.kd)
         tok_same, _ = oracle.softmax_topk(z.cpu().numpy(), per_row, c.kd)
         assert np.array_equal(tok.cpu().numpy(), tok_same)
+        tok_ref, prob_ref = oracle.softmax_topk(z_ref, per_row, c.kd)
+        probn = sv.draft_topk(z, torch.from_numpy(per_row).to(DEV), c.kd)[1].cpu().numpy()
+        for r in range(c.rows):
+            check_draft_tokens(tok[r].cpu().numpy(), probn[r], z_ref[r], per_row[r], tok_ref[r], prob_ref[r], "bf16")
     say("config 4 dense baseline on sampled vocabulary entries")
     zd = sv.dense_logits(th, tU).cpu().numpy()
     sample = rng.permutation(c.V)[:2048].astype(np.int32)
@@ -818,10 +846,68 @@ def test_config5_full_step_with_selection():
     tok_same, prob_same = oracle.softmax_topk(zn, seln, c.kd)
     assert np.array_equal(tokn, tok_same)
     assert np.allclose(probn, prob_same, rtol=1e-3, atol=1e-6)
-    for r in (0, 255, 511):                       # sampled rows against the oracle
-        say(f"config 5 oracle row {r}")
+    rows_checked = list(range(0, c.rows, 8))      # 64 of the 512 rows against the oracle, select and logits
+    bands, diffs, bands_s, outs, worst = [], [], [], [], 0.0
+    for r in rows_checked:
         ref_sel, _, s_ref, _ = oracle.select(h[r:r + 1], Wd, Wv, c.k, full=True)
-        band, diff = check_selected_set(seln[r], s_ref[0], ref_sel[0], c.k, "bf16")
-        say(f"  {band} scores within tolerance of the k-th, {diff} ids differ from the oracle")
+        band, diff, band_s, outside = check_selected_set(seln[r], s_ref[0], ref_sel[0], c.k, "bf16", tight=True)
+        bands.append(band); diffs.append(diff); bands_s.append(band_s); outs.append(outside)
         z_ref = oracle.subset_logits(h[r:r + 1], U, seln[r:r + 1])
-        assert_logits_close(zn[r:r + 1], z_ref, "bf16")
+        worst = max(worst, assert_logits_close(zn[r:r + 1], z_ref, "bf16"))
+        tok_ref, prob_ref = oracle.softmax_topk(z_ref, seln[r:r + 1], c.kd)
+        check_draft_tokens(tokn[r], probn[r], z_ref[0], seln[r], tok_ref[0], prob_ref[0], "bf16")
+    say(f"  config 5 select over {len(rows_checked)} rows: scores within 2e-2 of the k-th per row {min(bands)}..{max(bands)}, "
+        f"within 1e-3 {min(bands_s)}..{max(bands_s)}; ids differing from the oracle's set per row "
+        f"{min(diffs)}..{max(diffs)} (total {sum(diffs)}), of them outside the 1e-3 band {sum(outs)}; "
+        f"subset logits max |err| = {worst:.3e}")
+
+
+# ---------------------------------------------------------------- first call inside a stream capture
+_CAPTURE_FIRST = r"""
+import sys
+import numpy as np, torch
+sys.path.insert(0, {root!r})
+import paper_2602_13836_amd as sv
+dev = "cuda:0"
+gen = torch.Generator(device=dev); gen.manual_seed(5)
+rows, d, V = 512, 256, 3000
+U = (torch.randn((V, d), generator=gen, device=dev) * 0.02).to(torch.bfloat16)
+h = torch.randn((rows, d), generator=gen, device=dev).to(torch.bfloat16)
+out = torch.zeros((rows, V), dtype=torch.float32, device=dev)
+sv.init()                                   # device set-up outside the capture; no kernel has run yet
+stream = torch.cuda.Stream()
+g = torch.cuda.CUDAGraph()
+torch.cuda.synchronize()
+with torch.cuda.stream(stream):
+    with torch.cuda.graph(g, stream=stream):
+        sv.dense_logits(h, U, out=out)      # 256 x 256 tiles: 144 KiB of LDS, opted in by init()
+torch.cuda.synchronize()
+for rep in range(2):
+    out.zero_()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(stream):
+        g.replay()
+    torch.cuda.synchronize()
+    got = out.clone()
+    ref = sv.dense_logits(h, U)
+    torch.cuda.synchronize()
+    assert torch.equal(got, ref), rep
+ref64 = h.double() @ U.double().T
+assert float((got.double() - ref64).abs().max()) <= 2e-2
+print("captured-first-call ok")
+"""
+
+
+def test_first_call_may_be_captured_after_init():
+    """A fresh process whose FIRST library call happens inside a stream capture: specvocab_init has done the
+    per-device set-up (the LDS opt-in of the 256 x 256 tile kernel among it) beforehand, so nothing but the
+    kernel launch falls into the capture."""
+    import os
+    import subprocess
+    import sys
+    say("first call inside a capture, fresh process")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, "-c", _CAPTURE_FIRST.format(root=root)], capture_output=True, text=True,
+                         timeout=300)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert "captured-first-call ok" in res.stdout
