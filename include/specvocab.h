@@ -124,7 +124,15 @@ int specvocab_workspace_bytes(int op, int64_t rows, int64_t d, int64_t V, int64_
  *     idx_out[r, :] = token ids of the k largest s[r, :], in ascending id order
  * h: device [rows x d], row stride ldh.  idx_out: device [rows x k] int32.
  * scores_out: device [rows x k] float32 receiving s[r, idx_out[r, j]], or NULL.
- * Requires 1 <= k <= V, 1 <= d_prime, rows >= 1; V above 4194304 is SV_ERR_UNSUPPORTED. */
+ * Requires 1 <= k <= V, 1 <= d_prime, rows >= 1; V above 4194304 is SV_ERR_UNSUPPORTED.
+ * Cost.  With 65 or more bf16 hidden rows, 32768 <= V <= 393216 and scores_out == NULL the scores are never
+ * written to memory: the scores of 8192 evenly spaced tokens (ids floor(j V / 8192)) bracket every row's k-th
+ * score, the full product is classified against the bracket on the fly and only the few per cent of scores
+ * inside it are kept and resolved exactly.  The result is the same exact top-k; a row whose bracket misses
+ * (probability ~1e-9 per row on scores that do not depend on the token id modulo the sampling stride; certain
+ * for inputs built so that the sampled tokens score unlike all others) is recomputed by a slow exact path,
+ * about a millisecond per such row.  Every other shape, and every call with scores_out, materialises s in the
+ * workspace. */
 int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh,
                      const void* W_down, int64_t d_prime,
                      const void* W_vocab, int64_t V,

@@ -23,6 +23,7 @@ SV_OP_INDEXED_HEAD_NAIVE = 5
 SV_OP_AUX_LOG_SOFTMAX = 6
 SV_IDX_PADDED = 4        # OR into idx_mode: the list may hold padding slots (-1)
 MAX_KD = 64
+SELECT_SAMPLE = 8192     # sampled tokens of the batch selection: ids floor(j * V / SELECT_SAMPLE)
 
 EXPORTS = (
     "specvocab_version",

@@ -93,13 +93,19 @@ inline int ensure_device() {
 
 struct SelectWs {
     size_t hp_off, s_off, radix_off, total;
+    size_t bracket_off;      // scratch of the bracketed selection (it aliases the score matrix: one or the other)
 };
-SelectWs select_ws(int64_t rows, int64_t V, int64_t d_prime, int dt) {
+SelectWs select_ws(int64_t rows, int64_t V, int64_t d_prime, int64_t k, int dt) {
     SelectWs w;
     w.hp_off = 0;
     w.s_off = round256((size_t)rows * (size_t)d_prime * (size_t)esize_of(dt));
     w.radix_off = w.s_off + round256((size_t)rows * (size_t)V * sizeof(float));
     w.total = w.radix_off + round256(sv::select_scratch_words(rows, V) * sizeof(uint32_t));
+    w.bracket_off = w.s_off;
+    if (sv::bracket_select_supported(dt, rows, V, k)) {
+        const size_t t = w.bracket_off + round256(sv::bracket_scratch_words(rows, V) * sizeof(uint32_t));
+        if (t > w.total) w.total = t;
+    }
     return w;
 }
 
@@ -208,7 +214,7 @@ int launch_gather(int dt, const void* h, int64_t rows, int64_t d, int64_t ldh, c
 // optionally clears zero_words words at zero_ptr in the same launch
 int launch_down_projection(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* W_down,
                            int64_t d_prime, int dt, char* hp, uint32_t* zero_ptr, size_t zero_words,
-                           hipStream_t s) {
+                           hipStream_t s, int32_t* spread_ptr = nullptr, int64_t spread_n = 0, int64_t spread_V = 0) {
     const int es = esize_of(dt);
     sv::GemvArgs g{};
     g.x = static_cast<const char*>(h);
@@ -225,6 +231,9 @@ int launch_down_projection(const void* h, int64_t rows, int64_t d, int64_t ldh, 
     g.out_row_stride = d_prime;
     g.zero_ptr = zero_ptr;
     g.zero_words = zero_words;
+    g.spread_ptr = spread_ptr;
+    g.spread_n = spread_n;
+    g.spread_V = spread_V;
     if (sv::ksplit_rows_supported(dt, g))              // a batch of rows: W_down read once per 32 of them
         return sv::launch_ksplit_rows(g, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
     return sv::launch_gemv(dt, g, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
@@ -293,7 +302,7 @@ int specvocab_workspace_bytes(int op, int64_t rows, int64_t d, int64_t V, int64_
         case SV_OP_SELECT: {
             const int st = check_select_shape(rows, d, V, k, d_prime, dt);
             if (st != SV_OK) return st;
-            *bytes_out = select_ws(rows, V, d_prime, dt).total;
+            *bytes_out = select_ws(rows, V, d_prime, k, dt).total;
             return SV_OK;
         }
         case SV_OP_SUBSET_LOGITS:
@@ -333,7 +342,7 @@ static int select_impl(const void* h, int64_t rows, int64_t d, int64_t ldh, cons
     st = check_row(d, ldh, dt);
     if (st != SV_OK) return st;
     if (!aligned16(h) || !aligned16(W_down) || !aligned16(W_vocab) || !aligned16(ws)) return SV_ERR_ALIGN;
-    const SelectWs w = select_ws(rows, V, d_prime, dt);
+    const SelectWs w = select_ws(rows, V, d_prime, k, dt);
     if (!ws || ws_bytes < w.total) return SV_ERR_WORKSPACE;
     if (ensure_device() != SV_OK) return SV_ERR_HIP;
 
@@ -343,6 +352,42 @@ static int select_impl(const void* h, int64_t rows, int64_t d, int64_t ldh, cons
     char* hp = base + w.hp_off;
     float* scores = reinterpret_cast<float*>(base + w.s_off);
     uint32_t* radix = reinterpret_cast<uint32_t*>(base + w.radix_off);
+
+    // A batch of hidden rows whose scores nobody asked for: the selection that never writes the score matrix
+    // (a sample of the vocabulary brackets every row's k-th score; the full product is classified in the
+    // epilogue of the matrix-core kernel).  The down-projection launch also writes the sample's ids.
+    if (!scores_out && tau == -INFINITY && sv::bracket_select_supported(dt, rows, V, k)) {
+        uint32_t* bscratch = reinterpret_cast<uint32_t*>(base + w.bracket_off);
+        int32_t* ids = nullptr;
+        int64_t m = 0;
+        float* samp = nullptr;
+        sv::bracket_sample(rows, V, bscratch, &ids, &m, &samp);
+        if (launch_down_projection(h, rows, d, ldh, W_down, d_prime, dt, hp, nullptr, 0, s, ids, m, V) != SV_OK)
+            return SV_ERR_HIP;
+        sv::GemvArgs gs{};
+        gs.x = hp;
+        gs.x_row_bytes = d_prime * es;
+        gs.M = static_cast<const char*>(W_vocab);
+        gs.m_row_bytes = d_prime * es;
+        gs.idx = ids;
+        gs.n_items = m;
+        gs.chunks = (int)(d_prime * es / 16);
+        gs.rows = (int)rows;
+        gs.out_f32 = samp;
+        gs.out_row_stride = m;
+        const hipError_t e = rows > 64 ? sv::launch_tile_mfma(gs, s, true) : sv::launch_skinny_mfma(gs, s);
+        if (e != hipSuccess) return SV_ERR_HIP;
+        sv::BracketArgs ba{};
+        ba.hp = hp;
+        ba.Wv = static_cast<const char*>(W_vocab);
+        ba.chunks = gs.chunks;
+        ba.V = V;
+        ba.rows = (int)rows;
+        ba.k = k;
+        ba.idx_out = idx_out;
+        ba.scratch = bscratch;
+        return sv::launch_bracket_select(ba, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
+    }
 
     // Step 1a: h' = W_down h, stored in the storage dtype (bf16: rounded to nearest even); the same launch
     // clears the selection's counters and histogram

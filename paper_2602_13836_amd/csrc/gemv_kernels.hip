@@ -94,12 +94,7 @@ __global__ __launch_bounds__(256) void gemv_rows_kernel(const GemvArgs a) {
         finish(w);
     }
 
-    if (a.zero_words) {     // clear a later kernel's scratch with this launch
-        const size_t nthr = (size_t)gridDim.x * gridDim.y * blockDim.x;
-        for (size_t i = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x; i < a.zero_words;
-             i += nthr)
-            a.zero_ptr[i] = 0u;
-    }
+    prepare_scratch(a);     // clear / fill a later kernel's scratch with this launch
 }
 
 // One row per wavefront and one wavefront per item, rows of up to NL * 64 units (NL = 4 .. 16).  The
@@ -157,12 +152,7 @@ __global__ __launch_bounds__(kOnceWaves * 64) void gemv_rows_once_kernel(
         if constexpr (OUT_BF16) a.out_bf16[r * a.out_row_stride + it] = f32_to_bf16_rne(acc);
         else a.out_f32[r * a.out_row_stride + it] = row < 0 ? -INFINITY : acc;
     }
-    if (a.zero_words) {     // clear a later kernel's scratch with this launch
-        const size_t nthr = (size_t)gridDim.x * gridDim.y * blockDim.x;
-        for (size_t i = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x; i < a.zero_words;
-             i += nthr)
-            a.zero_ptr[i] = 0u;
-    }
+    prepare_scratch(a);     // clear / fill a later kernel's scratch with this launch
 }
 
 // any row length: the row is walked in 1 KiB pieces, x is re-read (from L2) for every item
@@ -172,12 +162,7 @@ __global__ __launch_bounds__(256) void gemv_long_rows_kernel(const GemvArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t r = blockIdx.y;
     const int C = a.chunks;
-    if (a.zero_words) {     // clear a later kernel's scratch with this launch
-        const size_t nthr = (size_t)gridDim.x * gridDim.y * blockDim.x;
-        for (size_t i = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x; i < a.zero_words;
-             i += nthr)
-            a.zero_ptr[i] = 0u;
-    }
+    prepare_scratch(a);     // clear / fill a later kernel's scratch with this launch
     const u32x4* xp = reinterpret_cast<const u32x4*>(a.x + r * a.x_row_bytes);
     const int32_t* idx = a.idx ? a.idx + r * a.idx_row_stride : nullptr;
     const int64_t n = a.n_items;

@@ -191,11 +191,7 @@ __global__ __launch_bounds__(512) void skinny_mfma_ksplit_kernel(SV_HOT_PARAMS, 
     const int g = lane >> 4;
     const int C = a.chunks;
     const int nslices = (C * 8 + kKC - 1) / kKC;
-    if (a.zero_words) {
-        const size_t step = (size_t)gridDim.x * gridDim.y * blockDim.x;
-        for (size_t z = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + tid; z < a.zero_words; z += step)
-            a.zero_ptr[z] = 0u;
-    }
+    prepare_scratch(a);
     const int row0 = row_base + (int)blockIdx.y * N;
     const int rows_here = min(a.rows - row0, N);
     const int64_t n_items = a.n_items_dev ? (int64_t)*a.n_items_dev : a.n_items;
@@ -352,7 +348,7 @@ hipError_t configure_skinny_mfma_lds() {
 
 // bf16, rows >= 2, one shared set of rows of M (dense or one index list for the whole step)
 bool skinny_mfma_supported(int dt, const GemvArgs& a) {
-    return dt == DT_BF16 && a.rows >= 2 && a.idx_row_stride == 0 && a.out_bf16 == nullptr && a.zero_words == 0;
+    return dt == DT_BF16 && a.rows >= 2 && a.idx_row_stride == 0 && a.out_bf16 == nullptr && a.zero_words == 0 && a.spread_n == 0;
 }
 
 // A batch of hidden rows against few rows of M (a few thousand at most), long reductions: one launch,

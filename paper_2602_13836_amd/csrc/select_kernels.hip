@@ -32,6 +32,8 @@
 #include "sv_device.h"
 #include "sv_launch.h"
 
+#include <math.h>
+
 #include <type_traits>
 
 namespace sv {
@@ -50,6 +52,8 @@ constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kMaxBlocksPerRow = 1024;                   // vocabulary blocks per row in collect / emit
 constexpr int kEpt = 4;                                  // entries per thread in collect / emit
 constexpr int kCandPerThread = 8;                        // candidates a resolve thread keeps in registers
+constexpr int kRbThreads = 256;                         // workgroup of the bracketed selection's per-row kernels
+constexpr int kRbWaves = kRbThreads / 64;
 constexpr int kFewRows = 8;                              // up to here the latency-shaped tail (measured: 5 us
                                                          // faster at 5 to 8 rows, slower from 10)
 
@@ -123,6 +127,25 @@ __device__ __forceinline__ void locate_bin(const uint32_t (&c)[PER], uint32_t re
 #pragma unroll
     for (int i = 0; i < PER; ++i) local += c[i];
     uint32_t above = block_suffix_exclusive<kSelWaves>(local, s_w);
+#pragma unroll
+    for (int i = PER - 1; i >= 0; --i) {
+        if (above < remain && remain <= above + c[i]) {
+            s_out[0] = (uint32_t)(threadIdx.x * PER + i);
+            s_out[1] = above;
+            s_out[2] = c[i];
+        }
+        above += c[i];
+    }
+    __syncthreads();
+}
+
+// locate_bin for a workgroup of WAVES wavefronts (see locate_bin)
+template <int PER, int WAVES>
+__device__ __forceinline__ void locate_bin_w(const uint32_t (&c)[PER], uint32_t remain, uint32_t* s_w, uint32_t* s_out) {
+    uint32_t local = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) local += c[i];
+    uint32_t above = block_suffix_exclusive<WAVES>(local, s_w);
 #pragma unroll
     for (int i = PER - 1; i >= 0; --i) {
         if (above < remain && remain <= above + c[i]) {
@@ -721,6 +744,511 @@ __global__ __launch_bounds__(kRowThreads) void emit_rows_kernel(const float* s_a
     }
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Bracketed selection: a batch of hidden rows without the score matrix
+// ------------------------------------------------------------------------------------------
+// With hundreds of hidden rows the scores s [rows x V] are hundreds of megabytes: writing them and reading
+// them back for the histogram, the collect and the emit passes costs several times the product that makes
+// them.  Here they never reach memory:
+//   sample    the scores of kSample evenly spaced tokens (a small matrix product);
+//   bracket   per row, from the sample's order statistics, two values hi > lo that enclose the k-th largest
+//             score of the whole row except with negligible probability (ranks k/V * m -/+ 6 standard
+//             deviations of the hypergeometric count, -/+ 8);
+//   classify  the full product on the matrix cores, whose epilogue keeps only: one bit per (row, token)
+//             "score > hi" (all of these are selected), and (key, id) of the few per cent of scores inside
+//             [lo, hi] (tile_mfma_kernels.hip);
+//   resolve   per row, with the row's bits in LDS: popcount of the bits = n_above; the (k - n_above)-th largest
+//             candidate by exact radix selection on (key, ~id) is the threshold; the selected candidates'
+//             bits are set; the ids of the set bits are written in ascending order.  A row whose bracket
+//             missed (k - n_above outside [0, candidates]) is only flagged;
+//   redo      a flagged row is redone by ONE workgroup that recomputes the row's scores itself in three
+//             passes (histogram, collect, emit): slow, exact, and only ever run for the one-in-a-billion row
+//             (or for inputs built to defeat the sample); every other workgroup of the launch leaves at once.
+// The result is exact with respect to the scores the classify pass computes: ties go to the smaller id.
+
+struct BracketLayout {
+    int64_t V;
+    int rows;
+    int tn;              // items per tile of the classify pass
+    int64_t tiles;       // item tiles per row
+    int64_t words;       // bit-mask words per row
+    int64_t m;           // sample size
+    int64_t nb;          // 4096-id vocabulary blocks (the redo path)
+    // offsets in uint32 words from the scratch base (all multiples of 4: 16-byte aligned)
+    size_t ids, samp, thr, flag, bits, cnt, sure, boff, state, cand, total;
+};
+__host__ __device__ inline size_t quad4(size_t n) { return (n + 3) & ~(size_t)3; }
+__host__ __device__ inline BracketLayout bracket_layout(int64_t V, int rows, int tn, int64_t m) {
+    BracketLayout L;
+    L.V = V;
+    L.rows = rows;
+    L.tn = tn;
+    L.tiles = (V + tn - 1) / tn;
+    L.words = L.tiles * (tn / 32);
+    L.m = m;
+    L.nb = (V + (int64_t)kEpt * kSelThreads - 1) / ((int64_t)kEpt * kSelThreads);
+    size_t o = 0;
+    L.ids = o;    o += quad4((size_t)m);
+    L.samp = o;   o += quad4((size_t)rows * m);
+    L.thr = o;    o += quad4((size_t)rows * 2);
+    L.flag = o;   o += quad4((size_t)rows);
+    L.bits = o;   o += quad4((size_t)rows * L.words);
+    L.cnt = o;    o += quad4((size_t)rows * L.tiles);
+    L.sure = o;   o += quad4((size_t)rows * L.nb);
+    L.boff = o;   o += quad4((size_t)rows * L.nb);
+    L.state = o;  o += (size_t)rows * 8;
+    L.cand = o;   o += (size_t)rows * L.tiles * tn * 2;
+    L.total = o;
+    return L;
+}
+
+// thr[r] = {hi, lo} from the row's m sample scores: hi = the largest value of the 2^-23-wide key interval
+// that holds the sample's rank_hi-th largest score (+inf if rank_hi < 1), lo = the smallest value of the
+// interval that holds the rank_lo-th largest (-inf if rank_lo > m)
+__global__ __launch_bounds__(kRbThreads) void bracket_kernel(const float* samp, int64_t m, int64_t rank_hi,
+                                                             int64_t rank_lo, float* thr) {
+    __shared__ uint32_t s_h1[kHistBins];
+    __shared__ uint32_t s_h2[2][2048];
+    __shared__ uint32_t s_w[kRbWaves];
+    __shared__ uint32_t s_out[4];
+    const int tid = threadIdx.x;
+    const float* s = samp + (int64_t)blockIdx.x * m;
+    // the first 32 sample scores of every thread stay in registers for both passes (all of them at the usual
+    // sample size); all loads leave at once, entries past the end repeat the last one and are not counted
+    constexpr int kHeld = 32;
+    float held[kHeld];
+#pragma unroll
+    for (int u = 0; u < kHeld; ++u) {
+        const int64_t j = (int64_t)u * kRbThreads + tid;
+        held[u] = s[j < m ? j : m - 1];
+    }
+    for (int b = tid; b < kHistBins; b += kRbThreads) s_h1[b] = 0u;
+    for (int b = tid; b < 2 * 2048; b += kRbThreads) (&s_h2[0][0])[b] = 0u;
+    __syncthreads();
+    auto for_each_key = [&](auto&& f) {
+#pragma unroll
+        for (int u = 0; u < kHeld; ++u)
+            if ((int64_t)u * kRbThreads + tid < m) f(f32_to_ord(held[u]));
+        for (int64_t j = (int64_t)kHeld * kRbThreads + tid; j < m; j += kRbThreads) f(f32_to_ord(s[j]));
+    };
+    for_each_key([&](uint32_t key) { atomicAdd(&s_h1[key >> kKeyLowBits], 1u); });
+    __syncthreads();
+    constexpr int PER = kHistBins / kRbThreads;
+    uint32_t c[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) c[i] = s_h1[tid * PER + i];
+    const bool has_hi = rank_hi >= 1, has_lo = rank_lo <= m;
+    uint32_t bin_hi = 0u, rem_hi = 0u, bin_lo = 0u, rem_lo = 0u;
+    if (has_hi) {                                             // uniform
+        locate_bin_w<PER, kRbWaves>(c, (uint32_t)rank_hi, s_w, s_out);
+        bin_hi = s_out[0];
+        rem_hi = (uint32_t)rank_hi - s_out[1];
+    }
+    if (has_lo) {
+        locate_bin_w<PER, kRbWaves>(c, (uint32_t)rank_lo, s_w, s_out);
+        bin_lo = s_out[0];
+        rem_lo = (uint32_t)rank_lo - s_out[1];
+    }
+    for_each_key([&](uint32_t key) {
+        if (has_hi && (key >> kKeyLowBits) == bin_hi) atomicAdd(&s_h2[0][(key >> 9) & 2047u], 1u);
+        if (has_lo && (key >> kKeyLowBits) == bin_lo) atomicAdd(&s_h2[1][(key >> 9) & 2047u], 1u);
+    });
+    __syncthreads();
+    constexpr int PER2 = 2048 / kRbThreads;
+    float hi = INFINITY, lo = -INFINITY;
+    if (has_hi) {
+        uint32_t c2[PER2];
+#pragma unroll
+        for (int i = 0; i < PER2; ++i) c2[i] = s_h2[0][tid * PER2 + i];
+        locate_bin_w<PER2, kRbWaves>(c2, rem_hi, s_w, s_out);
+        hi = ord_to_f32((bin_hi << kKeyLowBits) | (s_out[0] << 9) | 0x1FFu);
+    }
+    if (has_lo) {
+        uint32_t c2[PER2];
+#pragma unroll
+        for (int i = 0; i < PER2; ++i) c2[i] = s_h2[1][tid * PER2 + i];
+        locate_bin_w<PER2, kRbWaves>(c2, rem_lo, s_w, s_out);
+        lo = ord_to_f32((bin_lo << kKeyLowBits) | (s_out[0] << 9));
+    }
+    if (tid == 0) {
+        thr[2 * blockIdx.x] = hi;
+        thr[2 * blockIdx.x + 1] = lo;
+    }
+}
+
+// The redo of a row whose bracket missed, by one workgroup: the row's scores are recomputed three times
+// (histogram of the key's top bits; count above the k-th score's bin and collect that bin; emit), each
+// selector row by a group of 16 lanes.  Exact with respect to these scores; slow, and all but never run.
+struct RedoSmem {
+    uint32_t hist[kHistBins];
+    float val[kEpt * kSelThreads];
+    uint32_t w[kSelWaves];
+    uint32_t out[4];
+    uint32_t n;
+    ResolveSmem resolve;
+};
+template <int DT>
+__device__ __forceinline__ void redo_scores(const char* hp_row, const char* Wv, int chunks, int64_t V, int64_t base,
+                                            float* val) {
+    // 64 groups of 16 lanes; group q computes the scores of tokens base + q, base + q + 64, ...
+    const int tid = threadIdx.x;
+    const int g = tid & 15, q = tid >> 4;
+    for (int i = q; i < kEpt * kSelThreads; i += kSelThreads / 16) {
+        const int64_t v = base + i;
+        float acc = 0.0f;
+        if (v < V) {
+            const u32x4* wp = reinterpret_cast<const u32x4*>(Wv + v * (int64_t)chunks * 16);
+            const u32x4* xp = reinterpret_cast<const u32x4*>(hp_row);
+            for (int c = g; c < chunks; c += 16) acc = dot16<DT>(wp[c], xp[c], acc);
+        }
+        acc = row16_sum(acc);
+        if (g == 0) val[i] = acc;
+    }
+}
+template <int DT>
+__device__ __forceinline__ void redo_row(const char* hp_row, const char* Wv, int chunks, int64_t V, int64_t k,
+                                         const SelPtrs& p, const SelLayout& SL, int32_t* out, RedoSmem& rs) {
+    const int tid = threadIdx.x;
+    const int64_t chunk = (int64_t)kEpt * kSelThreads;
+    for (int b = tid; b < kHistBins; b += kSelThreads) rs.hist[b] = 0u;
+    if (tid == 0) rs.n = 0u;
+    __syncthreads();
+    for (int64_t blk = 0; blk < SL.nb; ++blk) {
+        redo_scores<DT>(hp_row, Wv, chunks, V, blk * chunk, rs.val);
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kEpt; ++i)
+            if (blk * chunk + tid * kEpt + i < V) atomicAdd(&rs.hist[f32_to_ord(rs.val[tid * kEpt + i]) >> kKeyLowBits], 1u);
+        __syncthreads();
+    }
+    constexpr int PER = kHistBins / kSelThreads;
+    uint32_t c[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) c[i] = rs.hist[tid * PER + i];
+    locate_bin<PER>(c, (uint32_t)k, rs.w, rs.out);
+    const uint32_t B = rs.out[0], above = rs.out[1];
+    for (int64_t blk = 0; blk < SL.nb; ++blk) {
+        redo_scores<DT>(hp_row, Wv, chunks, V, blk * chunk, rs.val);
+        __syncthreads();
+        uint32_t sure = 0u;
+#pragma unroll
+        for (int i = 0; i < kEpt; ++i) {
+            const int64_t v = blk * chunk + tid * kEpt + i;
+            if (v < V) {
+                const uint32_t key = f32_to_ord(rs.val[tid * kEpt + i]);
+                sure += (key >> kKeyLowBits) > B;
+                if ((key >> kKeyLowBits) == B) p.cand[atomicAdd(&rs.n, 1u)] = key64(key, (uint32_t)v);
+            }
+        }
+        sure = wave_sum_u32(sure);
+        if ((tid & 63) == 0) rs.w[tid >> 6] = sure;
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t tot = 0u;
+            for (int w = 0; w < kSelWaves; ++w) tot += rs.w[w];
+            p.sure[blk] = tot;
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        p.state[ST_NCAND] = rs.n;
+        p.binfo[0] = B;
+        p.binfo[1] = above;
+    }
+    __threadfence_block();
+    __syncthreads();
+    uint64_t T;
+    uint32_t off;
+    resolve_row<false>(p, SL, k, rs.resolve, T, off);
+    if (tid < (int)SL.nb) p.offset[tid] = off;
+    __threadfence_block();
+    __syncthreads();
+    for (int64_t blk = 0; blk < SL.nb; ++blk) {
+        redo_scores<DT>(hp_row, Wv, chunks, V, blk * chunk, rs.val);
+        __syncthreads();
+        const int64_t v0 = blk * chunk + (int64_t)tid * kEpt;
+        uint32_t mask = 0u;
+#pragma unroll
+        for (int i = 0; i < kEpt; ++i)
+            if (v0 + i < V && key64(f32_to_ord(rs.val[tid * kEpt + i]), (uint32_t)(v0 + i)) >= T) mask |= 1u << i;
+        uint32_t pos = p.offset[blk] + block_prefix_exclusive<kSelWaves>((uint32_t)__popc(mask), rs.w);
+#pragma unroll
+        for (int i = 0; i < kEpt; ++i)
+            if (mask & (1u << i)) {
+                if (pos < (uint32_t)k) out[pos] = (int32_t)(v0 + i);
+                ++pos;
+            }
+        __syncthreads();
+    }
+}
+
+// One workgroup of 256 threads per row (small workgroups: several rows per CU overlap their memory round trips
+// and barriers are cheap): see the overview above.  The row's bit mask lives in LDS from the first step to
+// the last, so the selected candidates join it there and the ids are written straight from it.
+constexpr int kRbTiles = 4;                              // item tiles per thread whose candidates are held in registers
+constexpr int kRbSpec = 8;                               // ... candidates per such tile; the rest are re-read per pass
+constexpr int kRbBins = 2048;
+struct ResolveEmitSmem {
+    uint32_t hist[kRbBins];
+    uint32_t w[kRbWaves];
+    uint32_t out[4];
+    uint64_t few[64];
+    uint32_t nfew;
+    uint32_t tot[kRbWaves];
+};
+
+__global__ __launch_bounds__(kRbThreads) void resolve_emit_kernel(int64_t V, int rows, int tn, int64_t m, int64_t k,
+                                                                  uint32_t* scratch, int32_t* idx_out) {
+    extern __shared__ __attribute__((aligned(16))) uint32_t s_bits[];         // [words]
+    __shared__ ResolveEmitSmem sm;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int64_t r = blockIdx.x;
+    const BracketLayout L = bracket_layout(V, rows, tn, m);
+    const uint32_t* bits = scratch + L.bits + (size_t)r * L.words;
+    const uint32_t* cnt = scratch + L.cnt + (size_t)r * L.tiles;
+    const uint64_t* cand = reinterpret_cast<const uint64_t*>(scratch + L.cand) + (size_t)r * L.tiles * tn;
+    // everything independent is requested up front: the bracket, the candidate counts of this thread's tiles
+    // and the first candidates of each (before their count is known)
+    const float hi = reinterpret_cast<const float*>(scratch + L.thr)[2 * r];
+    const float lo = reinterpret_cast<const float*>(scratch + L.thr)[2 * r + 1];
+    uint32_t tc[kRbTiles];
+    uint64_t reg[kRbTiles][kRbSpec];
+#pragma unroll
+    for (int j = 0; j < kRbTiles; ++j) {
+        const int64_t t = tid + (int64_t)j * kRbThreads;
+        tc[j] = t < L.tiles ? cnt[t] : 0u;
+        const uint64_t* p = cand + (t < L.tiles ? t : 0) * (int64_t)tn;
+#pragma unroll
+        for (int i = 0; i < kRbSpec; ++i) reg[j][i] = p[i];                   // a region has tn >= 128 entries
+    }
+    if (tid == 0) sm.nfew = 0u;
+    // the row's bits above hi: into LDS, counted on the way (eight loads in flight per thread)
+    uint32_t mine = 0u;
+    constexpr int kBatch = 8;
+    for (int64_t w0 = 0; w0 < L.words; w0 += (int64_t)kBatch * kRbThreads) {
+        uint32_t wv[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int64_t w = w0 + (int64_t)u * kRbThreads + tid;
+            wv[u] = bits[w < L.words ? w : L.words - 1];
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int64_t w = w0 + (int64_t)u * kRbThreads + tid;
+            if (w < L.words) {
+                s_bits[w] = wv[u];
+                mine += (uint32_t)__popc(wv[u]);
+            }
+        }
+    }
+    uint32_t band = 0u;
+#pragma unroll
+    for (int j = 0; j < kRbTiles; ++j) band += tc[j];
+    for (int64_t t = tid + (int64_t)kRbTiles * kRbThreads; t < L.tiles; t += kRbThreads) band += cnt[t];
+    mine = wave_sum_u32(mine);
+    band = wave_sum_u32(band);
+    if (lane == 0) {
+        sm.w[wave] = mine;
+        sm.tot[wave] = band;
+    }
+    __syncthreads();
+    uint32_t n_above = 0u, n_band = 0u;
+#pragma unroll
+    for (int w = 0; w < kRbWaves; ++w) {
+        n_above += sm.w[w];
+        n_band += sm.tot[w];
+    }
+    const bool miss = n_above > (uint32_t)k || (uint32_t)k - n_above > n_band;
+    if (tid == 0) scratch[L.flag + r] = miss ? 1u : 0u;
+    if (miss) return;                                         // uniform: the redo launch handles this row
+    uint32_t remain = (uint32_t)k - n_above;                  // candidates to select, 0 <= remain <= n_band
+
+    auto for_each_candidate = [&](auto&& f) {
+#pragma unroll
+        for (int j = 0; j < kRbTiles; ++j) {
+#pragma unroll
+            for (int i = 0; i < kRbSpec; ++i)
+                if ((uint32_t)i < tc[j]) f(reg[j][i]);
+            if (tc[j] > (uint32_t)kRbSpec) {                  // a crowded tile (ties): the rest from memory
+                const uint64_t* p = cand + (tid + (int64_t)j * kRbThreads) * tn;
+                for (uint32_t i = kRbSpec; i < tc[j]; ++i) f(p[i]);
+            }
+        }
+        for (int64_t t = tid + (int64_t)kRbTiles * kRbThreads; t < L.tiles; t += kRbThreads) {   // very large V
+            const uint32_t n = cnt[t];
+            const uint64_t* p = cand + t * tn;
+            for (uint32_t i = 0; i < n; ++i) f(p[i]);
+        }
+    };
+    if (remain > 0u) {                                        // uniform
+        // MSB-first radix selection of the remain-th largest (key << 32 | ~id).  All candidate keys lie in
+        // [key(lo), key(hi)]: the bits these two share are decided from the start.
+        const uint32_t khi = f32_to_ord(hi), klo = f32_to_ord(lo);
+        int decided = khi == klo ? 32 : __clz((int)(khi ^ klo));
+        uint64_t prefix = decided ? ((uint64_t)(khi >> (32 - decided)) << (64 - decided)) : 0ull;
+        constexpr int PER = kRbBins / kRbThreads;
+        auto set_bit = [&](uint64_t x) {
+            const uint32_t id = ~(uint32_t)x;
+            atomicOr(&s_bits[id >> 5], 1u << (id & 31u));
+        };
+        // One wavefront's worth of candidates that share the decided prefix, in sm.few: rank them by counting
+        // (keys are unique: they end in the id) and select the `remain` largest.  Called by every thread.
+        auto finish_few = [&](uint32_t left, uint32_t remain_now) {
+            __syncthreads();
+            if (wave == 0) {
+                const uint64_t cur = (uint32_t)lane < left ? sm.few[lane] : 0ull;
+                uint32_t larger = 0u;
+                for (uint32_t j = 0; j < left; ++j) larger += readlane_u64(cur, (int)j) > cur;
+                if ((uint32_t)lane < left && larger < remain_now) set_bit(cur);
+            }
+        };
+        // first digit: every candidate shares the bracket's common prefix, so nothing is filtered
+        int w = 64 - decided < 11 ? 64 - decided : 11;
+        int shift = 64 - decided - w;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) sm.hist[tid + i * kRbThreads] = 0u;
+        __syncthreads();
+        for_each_candidate([&](uint64_t x) { atomicAdd(&sm.hist[(uint32_t)(x >> shift) & ((1u << w) - 1u)], 1u); });
+        __syncthreads();
+        uint32_t c[PER];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) c[i] = sm.hist[tid * PER + i];
+        locate_bin_w<PER, kRbWaves>(c, remain, sm.w, sm.out);
+        const uint32_t digit = sm.out[0];
+        uint32_t left = sm.out[2];                            // candidates in the digit's bin
+        remain -= sm.out[1];                                  // ... of which this many are selected
+        prefix |= (uint64_t)digit << shift;
+        decided += w;
+        if (remain == left || left <= 64u || decided == 64) {
+            // the usual case, one more walk: bins above the digit's are selected, the digit's bin is selected
+            // as a whole or -- a handful -- ranked
+            const bool whole = remain == left || decided == 64;
+            for_each_candidate([&](uint64_t x) {
+                const uint32_t dg = (uint32_t)(x >> shift) & ((1u << w) - 1u);
+                if (dg > digit || (whole && dg == digit)) set_bit(x);
+                else if (dg == digit) sm.few[atomicAdd(&sm.nfew, 1u)] = x;
+            });
+            if (!whole) finish_few(left, remain);
+        } else {
+            // many candidates share the digit (tied scores): further digits, down to the inverted id
+            bool done = false;
+            uint64_t T = 0ull;
+            while (!done) {
+                w = 64 - decided < 11 ? 64 - decided : 11;
+                shift = 64 - decided - w;
+                __syncthreads();                              // the histogram may still be read by the last locate
+#pragma unroll
+                for (int i = 0; i < PER; ++i) sm.hist[tid + i * kRbThreads] = 0u;
+                __syncthreads();
+                for_each_candidate([&](uint64_t x) {
+                    if ((x >> (64 - decided)) == (prefix >> (64 - decided)))
+                        atomicAdd(&sm.hist[(uint32_t)(x >> shift) & ((1u << w) - 1u)], 1u);
+                });
+                __syncthreads();
+#pragma unroll
+                for (int i = 0; i < PER; ++i) c[i] = sm.hist[tid * PER + i];
+                locate_bin_w<PER, kRbWaves>(c, remain, sm.w, sm.out);
+                prefix |= (uint64_t)sm.out[0] << shift;
+                remain -= sm.out[1];
+                decided += w;
+                left = sm.out[2];
+                if (remain == left || decided == 64) {
+                    T = prefix;                               // every candidate with the prefix is selected
+                    done = true;
+                } else if (left <= 64u) {
+                    for_each_candidate([&](uint64_t x) {
+                        if ((x >> (64 - decided)) == (prefix >> (64 - decided))) sm.few[atomicAdd(&sm.nfew, 1u)] = x;
+                    });
+                    T = prefix | ((decided < 64 ? (1ull << (64 - decided)) : 0ull) - 1ull);   // above every key with the prefix
+                    T += 1ull;                                // (never wraps: the prefix is not all ones below an id)
+                    finish_few(left, remain);
+                    done = true;
+                }
+            }
+            for_each_candidate([&](uint64_t x) {
+                if (x >= T) set_bit(x);
+            });
+        }
+    }
+    __syncthreads();
+    // ids of the set bits, ascending: wavefront w owns the word pairs [w * ppw, w * ppw + ppw) and walks them 64 at
+    // a time with a running output position (no workgroup barrier inside the walk)
+    const uint64_t* s_pairs = reinterpret_cast<const uint64_t*>(s_bits);      // words is a multiple of 4
+    const int64_t pairs = L.words / 2;
+    const int64_t ppw = (pairs + kRbWaves - 1) / kRbWaves;
+    const int64_t pbeg = wave * ppw, pend = pbeg + ppw < pairs ? pbeg + ppw : pairs;
+    uint32_t total = 0u;
+    for (int64_t p = pbeg + lane; p < pend; p += 64) total += (uint32_t)__popcll(s_pairs[p]);
+    total = wave_sum_u32(total);
+    if (lane == 0) sm.tot[wave] = total;
+    __syncthreads();
+    uint32_t base = 0u;
+#pragma unroll
+    for (int w = 0; w < kRbWaves; ++w) base += w < wave ? sm.tot[w] : 0u;
+    int32_t* out = idx_out + r * k;
+    for (int64_t p0 = pbeg; p0 < pend; p0 += 64) {
+        const int64_t p = p0 + lane;
+        uint64_t word = p < pend ? s_pairs[p] : 0ull;
+        const uint32_t c = (uint32_t)__popcll(word);
+        const uint32_t incl = wave_prefix_inclusive_u32(c);
+        uint32_t pos = base + incl - c;
+        base += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+        while (word) {
+            const int b = __ffsll((long long)word) - 1;
+            if (pos < (uint32_t)k) out[pos] = (int32_t)(p * 64 + b);          // always true for consistent bits
+            ++pos;
+            word &= word - 1ull;
+        }
+    }
+}
+
+// Rows flagged by resolve_emit_kernel, redone one after the other by a few workgroups of 1024 threads that walk
+// the flags (a launch of one workgroup per row costs microseconds even when every workgroup leaves at once,
+// which is the normal case)
+constexpr int kRedoBlocks = 32;
+template <int DT>
+__global__ __launch_bounds__(kSelThreads) void redo_bracket_kernel(int64_t V, int rows, int tn, int64_t m, int64_t k,
+                                                                   uint32_t* scratch, int32_t* idx_out, const char* hp,
+                                                                   const char* Wv, int chunks) {
+    __shared__ RedoSmem rs;
+    __shared__ int s_todo[kSelThreads];
+    __shared__ uint32_t s_ntodo;
+    const BracketLayout L = bracket_layout(V, rows, tn, m);
+    const int tid = threadIdx.x;
+    // all flags are read at once (one round trip); this workgroup's share of the flagged rows goes to a list
+    for (int64_t base = 0; base < rows; base += kSelThreads) {
+        const int64_t cand_row = base + tid;
+        const bool mine = cand_row < rows && scratch[L.flag + cand_row] != 0u && cand_row % gridDim.x == blockIdx.x;
+        if (tid == 0) s_ntodo = 0u;
+        __syncthreads();
+        if (mine) s_todo[atomicAdd(&s_ntodo, 1u)] = (int)cand_row;
+        __syncthreads();
+        const uint32_t ntodo = s_ntodo;
+        for (uint32_t i = 0; i < ntodo; ++i) {
+            const int64_t r = s_todo[i];
+            SelLayout SL;
+            SL.V = V;
+            SL.chunk = (int64_t)kEpt * kSelThreads;
+            SL.nb = L.nb;
+            SL.replicas = 1;
+            SL.zero_words = 0;
+            SL.rest_words = 0;
+            SelPtrs p;
+            p.state = scratch + L.state + (size_t)r * 8;
+            p.hist = nullptr;
+            p.binfo = p.state + 4;
+            p.cand = reinterpret_cast<uint64_t*>(scratch + L.cand) + (size_t)r * L.tiles * tn;   // >= V entries
+            p.sure = scratch + L.sure + (size_t)r * L.nb;
+            p.offset = scratch + L.boff + (size_t)r * L.nb;
+            __syncthreads();                                      // the LDS of the previous row's redo is free again
+            redo_row<DT>(hp + r * (int64_t)chunks * 16, Wv, chunks, V, k, p, SL, idx_out + r * k, rs);
+        }
+        __syncthreads();                                      // the list is rewritten by the next batch of flags
+    }
+}
+
 }  // namespace
 
 bool scores_supported(int chunks) { return chunks >= 1 && chunks <= 64; }
@@ -734,6 +1262,65 @@ size_t select_scratch_words(int64_t rows, int64_t V) {
 
 void select_zero_range(int64_t rows, int64_t V, size_t* words) {
     *words = (size_t)rows * sel_layout(V, rows).zero_words;
+}
+
+// ---- bracketed selection (many hidden rows, bf16): host side
+constexpr int64_t kSample = 8192;                        // sampled tokens per call
+constexpr int64_t kBracketMaxVocab = 393216;             // the row's bit mask (V / 8 bytes) lives in LDS: 48 KiB here
+
+// From 65 hidden rows on (measured: at 60 rows the path that materialises the 30 MB of scores, which then stay
+// in the last-level cache, takes 71 us against 80 us; at 512 rows 335 us against 160 us)
+constexpr int64_t kBracketMinRows = 65;
+bool bracket_select_supported(int dt, int64_t rows, int64_t V, int64_t k) {
+    (void)k;
+    return dt == DT_BF16 && rows >= kBracketMinRows && V >= 4 * kSample && V <= kBracketMaxVocab;
+}
+
+size_t bracket_scratch_words(int64_t rows, int64_t V) {
+    return bracket_layout(V, (int)rows, bracket_tile_items((int)rows), kSample).total;
+}
+
+void bracket_sample(int64_t rows, int64_t V, uint32_t* scratch, int32_t** ids, int64_t* m, float** samp) {
+    const BracketLayout L = bracket_layout(V, (int)rows, bracket_tile_items((int)rows), kSample);
+    *ids = reinterpret_cast<int32_t*>(scratch + L.ids);
+    *m = L.m;
+    *samp = reinterpret_cast<float*>(scratch + L.samp);
+}
+
+hipError_t launch_bracket_select(const BracketArgs& a, hipStream_t stream) {
+    const int tn = bracket_tile_items(a.rows);
+    const BracketLayout L = bracket_layout(a.V, a.rows, tn, kSample);
+    // ranks of the bracket in the sample: the number of sampled tokens among the row's k best is
+    // hypergeometric with mean m k / V; 6 standard deviations and 8 more on either side
+    const double q = (double)a.k / (double)a.V, mean = (double)L.m * q;
+    const double sd = sqrt((double)L.m * q * (1.0 - q));
+    const int64_t rank_hi = (int64_t)floor(mean - 6.0 * sd - 8.0), rank_lo = (int64_t)ceil(mean + 6.0 * sd + 8.0);
+    float* thr = reinterpret_cast<float*>(a.scratch + L.thr);
+    hipLaunchKernelGGL(bracket_kernel, dim3((unsigned)a.rows), dim3(kRbThreads), 0, stream,
+                       reinterpret_cast<const float*>(a.scratch + L.samp), L.m, rank_hi, rank_lo, thr);
+    // classify: the full product, nothing stored but bits and candidates
+    GemvArgs g{};
+    g.x = a.hp;
+    g.x_row_bytes = (int64_t)a.chunks * 16;
+    g.M = a.Wv;
+    g.m_row_bytes = (int64_t)a.chunks * 16;
+    g.n_items = a.V;
+    g.chunks = a.chunks;
+    g.rows = a.rows;
+    BracketEpi ep{};
+    ep.thr = thr;
+    ep.bits = a.scratch + L.bits;
+    ep.words_per_row = L.words;
+    ep.cand = reinterpret_cast<uint64_t*>(a.scratch + L.cand);
+    ep.cnt = a.scratch + L.cnt;
+    ep.item_tiles = L.tiles;
+    hipError_t e = launch_tile_mfma_bracket(g, ep, stream);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(resolve_emit_kernel, dim3((unsigned)a.rows), dim3(kRbThreads), (size_t)L.words * 4, stream, a.V,
+                       a.rows, tn, L.m, a.k, a.scratch, a.idx_out);
+    hipLaunchKernelGGL(redo_bracket_kernel<DT_BF16>, dim3((unsigned)(a.rows < kRedoBlocks ? a.rows : kRedoBlocks)),
+                       dim3(kSelThreads), 0, stream, a.V, a.rows, tn, L.m, a.k, a.scratch, a.idx_out, a.hp, a.Wv, a.chunks);
+    return hipGetLastError();
 }
 
 hipError_t launch_scores_hist(int dt, const ScoresArgs& a, uint32_t* scratch, hipStream_t stream) {

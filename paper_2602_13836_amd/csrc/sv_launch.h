@@ -39,9 +39,22 @@ struct GemvArgs {
     int64_t out_row_stride;
     uint32_t* zero_ptr;      // optional: words cleared by the same launch (scratch of a later kernel)
     size_t zero_words;
+    int32_t* spread_ptr;     // optional: spread_n evenly spaced ids of [0, spread_V) written by the same launch,
+    int64_t spread_n;        // spread_ptr[j] = floor(j * spread_V / spread_n)  (the sample of the bracketed selection)
+    int64_t spread_V;
     const uint32_t* n_items_dev;   // optional (matrix-core kernel only): the item count lives on the
                                    // device; n_items is then an upper bound that sizes the grid
 };
+// what a launch does for later kernels besides its product: every thread of the grid calls this once
+__device__ __forceinline__ void prepare_scratch(const GemvArgs& a) {
+    if (a.zero_words == 0 && a.spread_n == 0) return;
+    const size_t nthr = (size_t)gridDim.x * gridDim.y * blockDim.x;
+    const size_t me = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x;
+    for (size_t i = me; i < a.zero_words; i += nthr) a.zero_ptr[i] = 0u;
+    for (size_t j = me; j < (size_t)a.spread_n; j += nthr)
+        a.spread_ptr[j] = (int32_t)((uint64_t)j * (uint64_t)a.spread_V / (uint64_t)a.spread_n);   // j * V < 2^63
+}
+
 // (the row-gather kernels behind launch_gemv accept idx entries of -1 = no token: such a slot reads
 // row 0 and gets -inf in a float32 output; the matrix-core and union paths need lists without them)
 hipError_t launch_gemv(int dt, const GemvArgs& a, hipStream_t stream);
@@ -61,8 +74,25 @@ hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream);
 // also supports out_bf16 and zero_ptr
 bool ksplit_rows_supported(int dt, const GemvArgs& a);
 hipError_t launch_ksplit_rows(const GemvArgs& a, hipStream_t stream);
-// more than 64 rows of x: LDS-tiled product (launch_skinny_mfma forwards to it)
-hipError_t launch_tile_mfma(const GemvArgs& a, hipStream_t stream);
+// more than 64 rows of x: LDS-tiled product (launch_skinny_mfma forwards to it); small_tiles: 128 x 128 tiles
+// whatever the row count (few items: more workgroups matter more than operand reuse)
+hipError_t launch_tile_mfma(const GemvArgs& a, hipStream_t stream, bool small_tiles = false);
+
+// The tiled product with the epilogue of the bracketed selection instead of a store: nothing of the product
+// is written; per hidden row r and item j the score f = out[r, j] is compared with the row's bracket
+// (thr[r] = {hi, lo}):  f > hi -> bit j of the row's bit mask;  lo <= f <= hi -> (key, id) appended to the
+// candidate region of (r, item tile), whose entry count goes to cnt.  Every word of bits and every cnt entry
+// is written.  Any row count >= 1.
+struct BracketEpi {
+    const float* thr;        // [rows][2]
+    uint32_t* bits;          // [rows][words_per_row], words_per_row = item_tiles * tile_items / 32
+    int64_t words_per_row;
+    uint64_t* cand;          // [rows][item_tiles][tile_items]   ((ordered key << 32) | ~id)
+    uint32_t* cnt;           // [rows][item_tiles]
+    int64_t item_tiles;
+};
+int bracket_tile_items(int rows);      // items per tile of the instance launch_tile_mfma_bracket picks
+hipError_t launch_tile_mfma_bracket(const GemvArgs& a, const BracketEpi& ep, hipStream_t stream);
 
 // in place: s[r, :] <- log softmax(s[r, :]) for rows of V float32 scores; partial: log_softmax_ws_floats floats
 size_t log_softmax_ws_floats(int64_t rows, int64_t V);
@@ -113,6 +143,26 @@ int64_t select_max_vocab();
 size_t select_scratch_words(int64_t rows, int64_t V);
 void select_zero_range(int64_t rows, int64_t V, size_t* words);
 hipError_t launch_topk_of_scores(const RadixArgs& a, hipStream_t stream);
+
+// Exact top-k of every row for a batch of hidden rows WITHOUT the score matrix in memory (bf16): the scores of a
+// sample of the vocabulary bracket each row's k-th score, the full product is classified against the bracket
+// in the epilogue of the matrix-core kernel, and the few scores inside the bracket are resolved exactly.
+// Order of use: bracket_sample() says where the sample's ids and scores live in the scratch (the caller has
+// the ids written -- GemvArgs::spread_* -- and the sample scores computed), then launch_bracket_select().
+struct BracketArgs {
+    const char* hp;        // [rows x d'] bf16
+    const char* Wv;        // [V x d'] bf16, dense rows
+    int chunks;            // d' * 2 / 16
+    int64_t V;
+    int rows;
+    int64_t k;
+    int32_t* idx_out;      // [rows x k]
+    uint32_t* scratch;     // bracket_scratch_words(rows, V) words; nothing needs clearing
+};
+bool bracket_select_supported(int dt, int64_t rows, int64_t V, int64_t k);
+size_t bracket_scratch_words(int64_t rows, int64_t V);
+void bracket_sample(int64_t rows, int64_t V, uint32_t* scratch, int32_t** ids, int64_t* m, float** samp);
+hipError_t launch_bracket_select(const BracketArgs& a, hipStream_t stream);
 
 // subset softmax + top-kd
 struct TopkArgs {

@@ -25,12 +25,15 @@
 #include "sv_device.h"
 #include "sv_launch.h"
 
+#include <type_traits>
+
 namespace sv {
 
 namespace {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kTK = 64;                  // reduction elements per slice (128 bytes of a row)
 constexpr int kRowB = kTK * 2 + 16;      // padded LDS row (144 B = 36 words)
@@ -51,10 +54,48 @@ __device__ __forceinline__ void sched_pattern() {
     if constexpr (I + 1 < M) sched_pattern<M, R, W, I + 1>();
 }
 
+// loops whose index must be a compile-time constant inside the body (an instruction's immediate operand)
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// dst with lanes LO and HI replaced by the two halves of the wavefront-uniform mask m (two v_writelane_b32).
+// The mask comes straight from a vector comparison: on this architecture a vector instruction that reads a
+// scalar register written by the vector instruction just before it needs two wait states in between; the
+// compiler inserts them for its own instructions, not for the operands of an asm block, hence the s_nop.
+template <int LO, int HI>
+__device__ __forceinline__ uint32_t write_lanes(uint32_t dst, uint64_t m) {
+    static_assert(LO >= 0 && LO < 64 && HI >= 0 && HI < 64, "lanes of a 64-wide wavefront");
+    asm("s_nop 1\n\tv_writelane_b32 %0, %1, %3\n\tv_writelane_b32 %0, %2, %4"
+        : "+v"(dst)
+        : "s"((uint32_t)m), "s"((uint32_t)(m >> 32)), "n"(LO), "n"(HI));
+    return dst;
+}
+
+// 2 x + (this lane's bit of the wavefront-wide mask m): one add-with-carry whose carry-in is the mask.  The mask
+// must come from a scalar instruction (see write_lanes for why not straight from a vector comparison).
+__device__ __forceinline__ uint32_t shift_in_lane_bit(uint32_t x, uint64_t m) {
+    uint64_t carry_out;
+    asm volatile("v_addc_co_u32_e64 %0, %1, %0, %0, %2" : "+v"(x), "=s"(carry_out) : "s"(m));
+    return x;
+}
+
+// LDS the bracket epilogue needs (it reuses the operand buffers after the main loop): per tile row the
+// bracket and a candidate counter (16 bytes reserved), per wavefront the scores of one 32-row band
+template <int GM, int GN, int WM, int WN>
+constexpr size_t bracket_lds_bytes() {
+    return (size_t)32 * GM * WM * 16 + (size_t)GM * GN * (16 * WN * 64) * 4;
+}
+
 // GM x GN wavefronts; each owns WM x WN MFMA tiles of 32 x 32: TM = 32 GM WM hidden rows, TN = 32 GN WN items.
-// PIPE selects the hand-ordered main loop.
-template <int GM, int GN, int WM, int WN, bool PIPE>
-__global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs a) {
+// PIPE selects the hand-ordered main loop.  EPI: instead of storing the product, the epilogue of the
+// bracketed selection (Section 3.3 Step 2 for a batch of hidden rows) classifies it.
+template <int GM, int GN, int WM, int WN, bool PIPE, bool EPI>
+__global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs a, const BracketEpi ep) {
     constexpr int kThreads = 64 * GM * GN;
     constexpr int kRowsPerPass = kThreads / 8;           // loader: 8 threads per 128-byte row slice
     constexpr int TM = 32 * GM * WM, TN = 32 * GN * WN;
@@ -251,6 +292,127 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
     // D[i][j]: j = lane % 32 (item), i = 8 (e / 4) + 4 (lane / 32) + e % 4 (hidden row) for element e
     const int64_t item0 = it * TN + wc * 32 * WN + (lane & 31);
     const int row0 = rt * TM + wr * 32 * WM + 4 * (lane >> 5);
+    if constexpr (EPI) {
+        // Nothing of the product is stored.  Per accumulator register (64 scores: 32 items of two hidden rows)
+        // two comparisons with the rows' brackets give two lane masks:
+        //   above hi  -> 2 x 32 bits of the rows' bit masks, gathered lane = row so that one store per wavefront
+        //                and 64 rows writes them;
+        //   in band   -> the (rare) lanes append (score, position) to a wavefront-private LDS list, which is
+        //                emptied after every 32-row band by a dense loop that turns each entry into
+        //                (key, id) in the candidate region of its (row, item tile).
+        static_assert(WM % 2 == 0, "a lane collects the words of rows lane, lane + 64, ...");
+        static_assert(16 * WN == 32, "the registers of a 32-row band map to the 32 bits of one word per lane");
+        static_assert(bracket_lds_bytes<GM, GN, WM, WN>() <= (size_t)2 * kStage, "the epilogue reuses the operand buffers");
+        float2* s_thr = reinterpret_cast<float2*>(smem);                          // [TM] {hi, lo}
+        uint32_t* s_cnt = reinterpret_cast<uint32_t*>(smem + (size_t)TM * 8);     // [TM] candidates of the row in this tile
+        // per wavefront: the scores of one 32-row band, [16 WN / 4 register quads][64 lanes][4 floats]
+        f32x4_t* s_dump = reinterpret_cast<f32x4_t*>(smem + (size_t)TM * 16) + (size_t)wave * (4 * WN * 64);
+        __syncthreads();                                   // every wavefront is out of the operand buffers
+        for (int t = tid; t < TM; t += kThreads) {
+            const int row = rt * TM + t;
+            // rows past the end: nothing is above +inf, nothing reaches +inf
+            s_thr[t] = row < a.rows ? reinterpret_cast<const float2*>(ep.thr)[row] : float2{INFINITY, INFINITY};
+            s_cnt[t] = 0u;
+        }
+        if (it == IT - 1) {                                // items past the end compare false with everything
+#pragma unroll
+            for (int n = 0; n < WN; ++n)
+                if (item0 + 32 * n >= n_items) {
+#pragma unroll
+                    for (int m = 0; m < WM; ++m)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) acc[m][n][e] = __builtin_nanf("");
+                }
+        }
+        __syncthreads();
+        uint32_t words[WM / 2][WN];
+#pragma unroll
+        for (int j = 0; j < WM / 2; ++j)
+#pragma unroll
+            for (int n = 0; n < WN; ++n) words[j][n] = 0u;
+        // candidate regions of this tile's rows: region of tile row t at cand_tile + t * row_stride (32-bit
+        // arithmetic below: 64-bit multiplications per candidate cost more than everything else there)
+        uint64_t* cand_tile = ep.cand + ((int64_t)rt * TM * ep.item_tiles + it) * TN;
+        const uint32_t row_stride = (uint32_t)(ep.item_tiles * TN);          // < 2^24 (the vocabulary, padded)
+        static_for<0, WM>([&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            constexpr int kHalfRows = 4;                   // lanes 32..63 hold the row four below
+            float2 th[16];                                 // the brackets of this band's rows: one batch of LDS reads
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                th[e] = s_thr[wr * 32 * WM + 32 * m + 8 * (e >> 2) + (e & 3) + kHalfRows * (lane >> 5)];
+            // the band's scores go to LDS as they are (the few lanes inside a bracket fetch theirs from there below)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+                for (int n = 0; n < WN; ++n)
+                    s_dump[(q4 * WN + n) * 64 + lane] = f32x4_t{acc[m][n][4 * q4], acc[m][n][4 * q4 + 1], acc[m][n][4 * q4 + 2], acc[m][n][4 * q4 + 3]};
+            uint32_t inside = 0u;                          // per lane: bit 31 - (e WN + n) <=> score inside its row's bracket
+            static_for<0, 16>([&](auto ec) {
+                constexpr int e = decltype(ec)::value;
+                constexpr int rlo = 32 * m + 8 * (e >> 2) + (e & 3);      // row within the wavefront's rows, lanes 0..31
+                static_for<0, WN>([&](auto nc) {
+                    constexpr int n = decltype(nc)::value;
+                    const float f = acc[m][n][e];
+                    const uint64_t ma = __builtin_amdgcn_ballot_w64(f > th[e].x);
+                    const uint64_t mi = __builtin_amdgcn_ballot_w64(f >= th[e].y);
+                    static_assert(rlo / 64 == (rlo + kHalfRows) / 64, "both rows of a register belong to the same lane group");
+                    words[rlo / 64][n] = write_lanes<rlo % 64, (rlo + kHalfRows) % 64>(words[rlo / 64][n], ma);
+                    // inside = 2 inside + (this lane's bit of the mask): one add-with-carry whose carry-in is the mask
+                    inside = shift_in_lane_bit(inside, mi & ~ma);
+                });
+            });
+            // The lanes with scores inside their bracket (about one per lane and band) take them out, up to four
+            // per round with the four LDS reads, the four slot reservations and the four stores each issued
+            // together: one round is the common case, and its latencies are paid once instead of per score.
+            while (__builtin_amdgcn_ballot_w64(inside != 0u)) {
+                constexpr int kPer = 4;
+                int q[kPer];
+                bool has[kPer];
+#pragma unroll
+                for (int u = 0; u < kPer; ++u) {
+                    has[u] = inside != 0u;
+                    q[u] = has[u] ? __clz((int)inside) : 0;               // e WN + n of the highest set bit
+                    inside &= ~(0x80000000u >> q[u]);                     // (clears bit 31 of a word that is already 0)
+                }
+                float f[kPer];
+                int row_t[kPer];
+#pragma unroll
+                for (int u = 0; u < kPer; ++u) {
+                    const int e = q[u] / WN, n = q[u] % WN;
+                    f[u] = reinterpret_cast<const float*>(s_dump)[(((e >> 2) * WN + n) * 64 + lane) * 4 + (e & 3)];
+                    row_t[u] = wr * 32 * WM + 32 * m + 8 * (e >> 2) + (e & 3) + 4 * (lane >> 5);
+                }
+                uint32_t slot[kPer];
+#pragma unroll
+                for (int u = 0; u < kPer; ++u) slot[u] = has[u] ? atomicAdd(&s_cnt[row_t[u]], 1u) : 0u;   // < TN
+#pragma unroll
+                for (int u = 0; u < kPer; ++u) {
+                    if (has[u]) {
+                        const uint32_t item = (uint32_t)item0 + 32u * (uint32_t)(q[u] % WN);
+                        cand_tile[__umul24((uint32_t)row_t[u], row_stride) + slot[u]] =
+                            ((uint64_t)f32_to_ord(f[u]) << 32) | (uint32_t)(~item);
+                    }
+                }
+            }
+        });
+        // lane l stores the words of the wavefront's rows l, l + 64, ...
+#pragma unroll
+        for (int j = 0; j < WM / 2; ++j) {
+            const int row = rt * TM + wr * 32 * WM + 64 * j + lane;
+            if (row < a.rows) {
+                uint32_t* o = ep.bits + (int64_t)row * ep.words_per_row + it * (TN / 32) + wc * WN;
+#pragma unroll
+                for (int n = 0; n < WN; ++n) o[n] = words[j][n];
+            }
+        }
+        __syncthreads();                                   // all candidates of the tile are counted
+        for (int t = tid; t < TM; t += kThreads) {
+            const int row = rt * TM + t;
+            if (row < a.rows) ep.cnt[(int64_t)row * ep.item_tiles + it] = s_cnt[t];
+        }
+        return;
+    }
 #pragma unroll
     for (int m = 0; m < WM; ++m)
 #pragma unroll
@@ -269,15 +431,15 @@ template <int GM, int GN, int WM, int WN>
 constexpr size_t tile_lds_bytes() { return (size_t)2 * (32 * GM * WM + 32 * GN * WN) * kRowB; }
 
 // more than 64 KiB of dynamic LDS needs an explicit opt-in per kernel instance and device
-template <int GM, int GN, int WM, int WN, bool PIPE>
+template <int GM, int GN, int WM, int WN, bool PIPE, bool EPI>
 hipError_t opt_in_lds() {
     if (tile_lds_bytes<GM, GN, WM, WN>() <= 64 * 1024) return hipSuccess;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&tile_mfma_kernel<GM, GN, WM, WN, PIPE>),
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&tile_mfma_kernel<GM, GN, WM, WN, PIPE, EPI>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)tile_lds_bytes<GM, GN, WM, WN>());
 }
 
-template <int GM, int GN, int WM, int WN, bool PIPE>
-hipError_t launch_tile(const GemvArgs& a, hipStream_t stream) {
+template <int GM, int GN, int WM, int WN, bool PIPE, bool EPI = false>
+hipError_t launch_tile(const GemvArgs& a, hipStream_t stream, const BracketEpi& ep = BracketEpi{}) {
     constexpr int TM = 32 * GM * WM, TN = 32 * GN * WN;
     const int64_t RT = (a.rows + TM - 1) / TM;
     const int64_t IT = (a.n_items + TN - 1) / TN;
@@ -285,7 +447,8 @@ hipError_t launch_tile(const GemvArgs& a, hipStream_t stream) {
     const int64_t bx = groups * RT * kXcds;
     if (bx > 0x7fffffffLL) return hipErrorInvalidValue;         // more tiles than a grid dimension holds
     const size_t lds = tile_lds_bytes<GM, GN, WM, WN>();     // above 64 KiB: opted in by configure_tile_mfma_lds()
-    hipLaunchKernelGGL((tile_mfma_kernel<GM, GN, WM, WN, PIPE>), dim3((unsigned)bx), dim3(64 * GM * GN), lds, stream, a);
+    hipLaunchKernelGGL((tile_mfma_kernel<GM, GN, WM, WN, PIPE, EPI>), dim3((unsigned)bx), dim3(64 * GM * GN), lds, stream,
+                       a, ep);
     return hipGetLastError();
 }
 
@@ -294,14 +457,36 @@ hipError_t launch_tile(const GemvArgs& a, hipStream_t stream) {
 // every instance launch_tile_mfma can pick, on the current device (called once per device, outside any
 // stream capture, by the library's device set-up)
 hipError_t configure_tile_mfma_lds() {
-    hipError_t e = opt_in_lds<2, 2, 2, 2, false>();
-    if (e == hipSuccess) e = opt_in_lds<2, 4, 4, 2, true>();
-    if (e == hipSuccess) e = opt_in_lds<2, 2, 2, 2, true>();
+    hipError_t e = opt_in_lds<2, 2, 2, 2, false, false>();
+    if (e == hipSuccess) e = opt_in_lds<2, 4, 4, 2, true, false>();
+    if (e == hipSuccess) e = opt_in_lds<2, 2, 2, 2, true, false>();
+    if (e == hipSuccess) e = opt_in_lds<2, 2, 2, 2, false, true>();
+    if (e == hipSuccess) e = opt_in_lds<2, 4, 4, 2, true, true>();
+    if (e == hipSuccess) e = opt_in_lds<2, 2, 2, 2, true, true>();
     return e;
 }
 
-hipError_t launch_tile_mfma(const GemvArgs& a, hipStream_t stream) {
+// the same choice of instance as launch_tile_mfma, so that both compute bit-identical products
+static int tile_instance(int rows) {
+    if (rows <= 128) return 0;                                 // 128 x 128, compiler-ordered loop
+    const int pad256 = (rows + 255) / 256 * 256, pad128 = (rows + 127) / 128 * 128;
+    return pad256 == pad128 ? 2 : 1;                           // 256 x 256 / 128 x 128, hand-ordered loop
+}
+
+int bracket_tile_items(int rows) { return tile_instance(rows) == 2 ? 256 : 128; }
+
+hipError_t launch_tile_mfma_bracket(const GemvArgs& a, const BracketEpi& ep, hipStream_t stream) {
     if (a.n_items <= 0 || a.rows <= 0) return hipSuccess;
+    switch (tile_instance(a.rows)) {
+        case 0: return launch_tile<2, 2, 2, 2, false, true>(a, stream, ep);
+        case 1: return launch_tile<2, 2, 2, 2, true, true>(a, stream, ep);
+        default: return launch_tile<2, 4, 4, 2, true, true>(a, stream, ep);
+    }
+}
+
+hipError_t launch_tile_mfma(const GemvArgs& a, hipStream_t stream, bool small_tiles) {
+    if (a.n_items <= 0 || a.rows <= 0) return hipSuccess;
+    if (small_tiles) return a.rows <= 128 ? launch_tile<2, 2, 2, 2, false>(a, stream) : launch_tile<2, 2, 2, 2, true>(a, stream);
     // Up to 128 hidden rows the work is bound by streaming M once: small tiles, two workgroups per
     // CU.  Beyond that the 256 x 256 tile halves the operand traffic per multiply-add -- unless rounding
     // the row count up to 256s would add a whole idle half-tile that 128-row tiles avoid.

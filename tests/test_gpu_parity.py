@@ -685,6 +685,89 @@ def test_exact_selector_reduces_to_dense_topk():
         check_selected_set(idx[r].cpu().numpy(), z_ref[r], ref, k, "bf16")
 
 
+# ---------------------------------------------------------------- selection for a batch without the score matrix
+BATCH_SELECT_SHAPES = [
+    # rows, d,  d',  V,     k        (bf16, 65 rows or more, V >= 32768, no scores output: the bracketed selection)
+    (65, 256, 32, 32768, 100),       # 128-row tiles, one of them half empty; the smallest vocabulary of the path
+    (70, 256, 32, 33000, 500),
+    (100, 1024, 256, 50001, 4096),   # ragged last item tile
+    (128, 256, 40, 40007, 1),        # k = 1
+    (130, 256, 64, 36000, 18000),    # two 128-row tiles with the hand-ordered loop, half the vocabulary selected
+    (300, 256, 64, 50001, 5000),     # three 128-row tiles
+    (512, 512, 256, 40000, 2048),    # 256 x 256 tiles
+    (257, 256, 128, 70001, 70001),   # k = V: everything is selected
+    (90, 256, 24, 45000, 44999),     # k = V - 1
+    (66, 256, 32, 140000, 8192),     # more item tiles than the resolve step holds in registers
+    (12, 512, 64, 40000, 3000),      # below 65 rows: the path that materialises the scores (a control)
+]
+
+
+@pytest.mark.parametrize("rows,d,dp,V,k", BATCH_SELECT_SHAPES)
+def test_select_batch_without_score_matrix(rows, d, dp, V, k):
+    """65 or more bf16 rows and no scores output: the selection that never writes s.  Checked against the
+    oracle (band rule) and bit for bit against the path that materialises s (asking for the scores selects it;
+    both compute s with the same matrix-core kernel)."""
+    say(f"batch select rows={rows} d={d} d'={dp} V={V} k={k}")
+    rng = np.random.default_rng(rows * 7 + V + k)
+    h = rand(rng, (rows, d), 1.0, "bf16")
+    Wd = rand(rng, (dp, d), 0.05, "bf16")
+    Wv = rand(rng, (V, dp), 0.05, "bf16")
+    th, tWd, tWv = to_dev(h), to_dev(Wd), to_dev(Wv)
+    idx, _ = sv.select(th, tWd, tWv, k)
+    idx_s, sc = sv.select(th, tWd, tWv, k, want_scores=True)      # asks for scores: the materialising path
+    assert torch.equal(idx, idx_s)
+    idx = idx.cpu().numpy()
+    check_rows = range(rows) if rows <= 70 else range(0, rows, 7)
+    for r in check_rows:
+        ref_idx, _, s_ref, _ = oracle.select(h[r:r + 1], Wd, Wv, k, full=True)
+        check_selected_set(idx[r], s_ref[0], ref_idx[0], k, "bf16")
+    assert np.all(np.diff(idx, axis=1) > 0) and idx.min() >= 0 and idx.max() < V
+
+
+def _adversarial_selector(rng, V, dp, sign):
+    """W_vocab whose sampled rows (ids floor(j V / SELECT_SAMPLE)) are all zero while every other row scores
+    sign * (positive integer) against an all-ones h': the sample says nothing about the rest."""
+    Wv = (sign * rng.integers(1, 4, (V, dp))).astype(np.float32)
+    sampled = (np.arange(sv.SELECT_SAMPLE, dtype=np.int64) * V) // sv.SELECT_SAMPLE
+    Wv[sampled] = 0.0
+    return f32_to_bf16_bits(Wv), sampled
+
+
+@pytest.mark.parametrize("rows,V,k", [(65, 40000, 2000), (70, 65536, 8192), (130, 33001, 33001)])
+def test_select_batch_redoes_rows_whose_bracket_missed(rows, V, k):
+    """Inputs built to defeat the sample: every sampled token scores 0, every other token scores high, so far
+    more than k scores lie above the bracket and every row is redone by the exact one-workgroup path.
+    Integer-valued, hence exact: ids must equal the oracle's."""
+    say(f"batch select with a useless sample rows={rows} V={V} k={k}")
+    rng = np.random.default_rng(V + rows)
+    dp, d = 16, 24
+    Wv, _ = _adversarial_selector(rng, V, dp, +1)
+    h = np.zeros((rows, d), np.float32)
+    h[:, :dp] = rng.integers(1, 3, (rows, dp))
+    h = f32_to_bf16_bits(h)
+    Wd = np.zeros((dp, d), np.float32)
+    Wd[np.arange(dp), np.arange(dp)] = 1.0
+    Wd = f32_to_bf16_bits(Wd)
+    idx, _ = sv.select(to_dev(h), to_dev(Wd), to_dev(Wv), k)
+    ref_idx = oracle.select(h, Wd, Wv, k)[0]
+    assert np.array_equal(idx.cpu().numpy(), ref_idx)
+
+
+def test_select_batch_when_the_sample_holds_all_the_best():
+    """The mirror case: every token outside the sample scores below it, so the k best are sampled tokens with
+    exactly tied scores (all 0): the bracket holds, the tie rule decides among thousands of candidates."""
+    say("batch select, the best tokens are exactly the sampled ones")
+    rng = np.random.default_rng(4242)
+    rows, V, k, dp, d = 67, 50000, 3000, 16, 16
+    Wv, sampled = _adversarial_selector(rng, V, dp, -1)
+    h = f32_to_bf16_bits(rng.integers(1, 3, (rows, d)).astype(np.float32))
+    Wd = f32_to_bf16_bits(np.eye(dp, d, dtype=np.float32))
+    idx, _ = sv.select(to_dev(h), to_dev(Wd), to_dev(Wv), k)
+    assert np.array_equal(idx.cpu().numpy(), np.tile(np.sort(sampled)[:k].astype(np.int32), (rows, 1)))
+    assert np.array_equal(idx.cpu().numpy(), oracle.select(h, Wd, Wv, k)[0])
+
+
+
 # ---------------------------------------------------------------- whole draft step, config 1
 def test_config1_all_steps():
     c = CONFIGS[1]
