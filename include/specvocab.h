@@ -41,7 +41,7 @@
  * Ties.     Wherever "largest" decides, equal values are ordered by smaller token id first.
  * Threads.  Entry points may be called from several host threads; the library keeps no per-call
  *           state on the host (only the per-device set-up, done once under a lock and read-only
- *           afterwards).
+ *           afterwards).  specvocab_select_static is the exception: see there.
  */
 #ifndef SPECVOCAB_H
 #define SPECVOCAB_H
@@ -102,7 +102,7 @@ typedef enum {
 int specvocab_version(void);
 
 /* One-time set-up of the current HIP device: device attributes, the opt-in of the kernels that use more
- * than 64 KiB of LDS.
+ * than 64 KiB of LDS, and the device address of the static scratch array of specvocab_select_static.
  * Every entry point does this by itself on its first call on a device; call specvocab_init explicitly,
  * once per device and outside any stream capture, when that first call would otherwise happen while a
  * stream is being captured.  Idempotent and thread-safe.  Returns SV_OK or SV_ERR_HIP. */
@@ -139,6 +139,23 @@ int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh,
                      int dt, int64_t k,
                      int32_t* idx_out, float* scores_out,
                      void* ws, size_t ws_bytes, void* stream);
+
+/* specvocab_select for callers that cannot allocate device memory or pass a workspace: code running under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * kernels as specvocab_select, but the scratch memory is a static device array inside the library
+ * (SPECVOCAB_STATIC_SCRATCH_BYTES per GPU the library runs on, held until the process ends) instead of a
+ * workspace argument; the call allocates nothing and frees nothing.  Shapes whose
+ * specvocab_workspace_bytes(SV_OP_SELECT, ...) exceeds SPECVOCAB_STATIC_SCRATCH_BYTES return
+ * SV_ERR_WORKSPACE (8 MiB holds one hidden row at V up to about 600000, or four rows at V = 128256).
+ * All calls on one GPU share that GPU's array, which keeps the previous call's contents (the kernels
+ * clear what must start at zero): calls that overlap on one GPU -- different streams or host threads
+ * without ordering between them -- race; order them on one stream. */
+#define SPECVOCAB_STATIC_SCRATCH_BYTES (8u << 20)
+int specvocab_select_static(const void* h, int64_t rows, int64_t d, int64_t ldh,
+                            const void* W_down, int64_t d_prime,
+                            const void* W_vocab, int64_t V,
+                            int dt, int64_t k,
+                            int32_t* idx_out, float* scores_out, void* stream);
 
 /* specvocab_select with a score threshold: of the k best tokens of a row only those with
  * s[r, v] >= tau stay; the others become padding slots in place (idx_out = -1, scores_out = -inf),

@@ -31,6 +31,7 @@ EXPORTS = (
     "specvocab_status_string",
     "specvocab_workspace_bytes",
     "specvocab_select",
+    "specvocab_select_static",
     "specvocab_select_threshold",
     "specvocab_subset_logits",
     "specvocab_draft_topk",
@@ -75,6 +76,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
                                      ctypes.c_size_t, vp]
     lib.specvocab_init.restype = ci
     lib.specvocab_init.argtypes = []
+    lib.specvocab_select_static.restype = ci
+    lib.specvocab_select_static.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, ci, i64, vp, vp, vp]
     lib.specvocab_select_threshold.restype = ci
     lib.specvocab_select_threshold.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, ci, i64, ctypes.c_float, vp, vp,
                                                vp, ctypes.c_size_t, vp]
@@ -97,6 +100,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     if path is None:
         _lib = lib
     return lib
+
+
+STATIC_SCRATCH_BYTES = 8 << 20       # SPECVOCAB_STATIC_SCRATCH_BYTES
 
 
 def init() -> None:
@@ -205,6 +211,27 @@ def select(h: torch.Tensor, W_down: torch.Tensor, W_vocab: torch.Tensor, k: int,
                                                          _ptr(scores_out), _ptr(ws),
                                                          0 if ws is None else ws.numel(), _stream(stream)),
                "specvocab_select_threshold")
+    return idx_out, scores_out
+
+
+def select_static(h: torch.Tensor, W_down: torch.Tensor, W_vocab: torch.Tensor, k: int,
+                  idx_out: torch.Tensor, scores_out: Optional[torch.Tensor] = None,
+                  stream: Optional[torch.cuda.Stream] = None):
+    """specvocab_select_static: specvocab_select on the library's static device scratch.  Allocates nothing:
+    the caller passes the outputs."""
+    rows, d, ldh = _mat(h, "h")
+    dp, d2, ldd = _mat(W_down, "W_down")
+    V, dp2, ldv = _mat(W_vocab, "W_vocab")
+    if d2 != d or dp2 != dp or ldd != d or ldv != dp:
+        raise ValueError("W_down must be a dense [d' x d] and W_vocab a dense [V x d']")
+    dt = _dt(h)
+    if _dt(W_down) != dt or _dt(W_vocab) != dt:
+        raise TypeError("h, W_down and W_vocab must share a dtype")
+    if idx_out.shape != (rows, k) or idx_out.dtype != torch.int32 or not idx_out.is_contiguous():
+        raise ValueError("idx_out must be a contiguous [rows x k] int32 GPU tensor")
+    _check(load_library().specvocab_select_static(_ptr(h), rows, d, ldh, _ptr(W_down), dp, _ptr(W_vocab), V, dt, k,
+                                                  _ptr(idx_out), _ptr(scores_out), _stream(stream)),
+           "specvocab_select_static")
     return idx_out, scores_out
 
 

@@ -12,15 +12,21 @@
 #include <atomic>
 #include <mutex>
 
+// Device scratch of the entry point that takes no workspace (specvocab_select_static): one array per GPU the
+// library runs on, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels and host calls use the per-device address kept in DeviceState.
+static __device__ __align__(256) unsigned char scratch[SPECVOCAB_STATIC_SCRATCH_BYTES];
+
 namespace sv {
 
 namespace {
 
 // Per-device set-up, done once under a lock and published with release/acquire: device attributes, the
-// and the opt-in of the kernels that use more than 64 KiB of LDS.
+// opt-in of the kernels that use more than 64 KiB of LDS, and this device's address of the scratch array.
 struct DeviceState {
     std::atomic<int> ready{0};
     int cus = 0;
+    void* scratch_ptr = nullptr;
 };
 constexpr int kMaxDevices = 64;
 DeviceState g_dev[kMaxDevices];
@@ -43,6 +49,10 @@ hipError_t device_state(const DeviceState** out) {
             if (e != hipSuccess) return e;
             e = configure_tile_mfma_lds();
             if (e != hipSuccess) return e;
+            void* p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess) return e;
+            st.scratch_ptr = p;
             st.ready.store(1, std::memory_order_release);
         }
     }
@@ -449,6 +459,20 @@ int specvocab_select(const void* h, int64_t rows, int64_t d, int64_t ldh, const 
 }
 
 int specvocab_init(void) { return ensure_device(); }
+
+int specvocab_select_static(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* W_down,
+                            int64_t d_prime, const void* W_vocab, int64_t V, int dt, int64_t k,
+                            int32_t* idx_out, float* scores_out, void* stream) {
+    // the same validation as specvocab_select, first the part that says whether the shape has a workspace size
+    if (!h || !W_down || !W_vocab || !idx_out) return SV_ERR_NULL;
+    const int st = check_select_shape(rows, d, V, k, d_prime, dt);
+    if (st != SV_OK) return st;
+    if (select_ws(rows, V, d_prime, k, dt).total > (size_t)SPECVOCAB_STATIC_SCRATCH_BYTES) return SV_ERR_WORKSPACE;
+    const sv::DeviceState* dev = nullptr;
+    if (sv::device_state(&dev) != hipSuccess) return SV_ERR_HIP;
+    return select_impl(h, rows, d, ldh, W_down, d_prime, W_vocab, V, dt, k, -INFINITY, idx_out, scores_out,
+                       dev->scratch_ptr, (size_t)SPECVOCAB_STATIC_SCRATCH_BYTES, stream);
+}
 
 int specvocab_select_threshold(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* W_down,
                                int64_t d_prime, const void* W_vocab, int64_t V, int dt, int64_t k, float tau,

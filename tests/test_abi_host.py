@@ -154,6 +154,22 @@ def test_dense_select_topk_reject_bad_arguments(lib):
     assert t(A, A, 3, 1, 100, 10, A, A, None, None, 0, None) == 3
 
 
+def test_select_static_rejects_before_touching_the_device(lib):
+    """The entry point without a workspace argument: the usual validation, and shapes whose scratch need
+    exceeds the static array are refused with the workspace status."""
+    f = lib.specvocab_select_static
+    assert f(None, 1, 256, 256, A, 32, A, 1000, 1, 10, A, None, None) == 1
+    assert f(A, 1, 256, 256, A, 32, A, 1000, 1, 10, None, None, None) == 1
+    assert f(A, 1, 256, 256, A, 32, A, 1000, 1, 1001, A, None, None) == 2                    # k > V
+    assert f(A, 1, 256, 256, A, 30, A, 1000, 1, 10, A, None, None) == 6                      # d' % 8
+    assert f(A, 1, 256, 256, A, 32, A, 1000, 9, 10, A, None, None) == 3
+    # config 2's shape fits the 8 MiB array, 16 rows of it do not
+    assert sv.workspace_bytes(sv.SV_OP_SELECT, 1, 4096, 128256, 8192, 256) <= sv.STATIC_SCRATCH_BYTES
+    assert sv.workspace_bytes(sv.SV_OP_SELECT, 16, 4096, 128256, 8192, 256) > sv.STATIC_SCRATCH_BYTES
+    assert f(A, 16, 4096, 4096, A, 256, A, 128256, 1, 8192, A, None, None) == 5
+    assert f(A, 1, 4096, 4096, A, 256, A, 4194304, 1, 8192, A, None, None) == 5
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     h = torch.zeros(1, 256, dtype=torch.bfloat16)
