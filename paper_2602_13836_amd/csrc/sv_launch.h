@@ -44,6 +44,8 @@ struct GemvArgs {
     int64_t spread_V;
     const uint32_t* n_items_dev;   // optional (matrix-core kernel only): the item count lives on the
                                    // device; n_items is then an upper bound that sizes the grid
+    const uint32_t* gate;          // optional (tiled matrix-core kernel only): the launch does nothing unless
+    uint32_t gate_run_if;          // *gate == gate_run_if (a device-side decision between two enqueued paths)
 };
 // what a launch does for later kernels besides its product: every thread of the grid calls this once
 __device__ __forceinline__ void prepare_scratch(const GemvArgs& a) {
@@ -93,6 +95,21 @@ struct BracketEpi {
 };
 int bracket_tile_items(int rows);      // items per tile of the instance launch_tile_mfma_bracket picks
 hipError_t launch_tile_mfma_bracket(const GemvArgs& a, const BracketEpi& ep, hipStream_t stream);
+
+// The tiled product over ALL rows of M (a.idx == nullptr, a.n_items = V) with the pick epilogue: only
+//     out[r, j] = < M[idx[r, j], :], x[r, :] >
+// is stored.  Every row's list must be sorted (non-decreasing); off[r, t] = first j with idx[r, j] >= t * tile
+// items (off[r, tiles] = k) says which slice of the list falls into item tile t.  The launch does nothing
+// unless *gate == 0 (the kernel that builds off also checks the order and raises the flag).
+struct PickEpi {
+    const uint32_t* off;     // [rows][off_stride]
+    int64_t off_stride;      // item tiles + 1
+    const int32_t* idx;      // [rows][k]
+    int64_t k;
+    float* out;              // [rows][k]
+};
+int pick_tile_items(int rows);
+hipError_t launch_tile_mfma_pick(const GemvArgs& a, const PickEpi& pk, hipStream_t stream);
 
 // in place: s[r, :] <- log softmax(s[r, :]) for rows of V float32 scores; partial: log_softmax_ws_floats floats
 size_t log_softmax_ws_floats(int64_t rows, int64_t V);

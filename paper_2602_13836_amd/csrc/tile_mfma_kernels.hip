@@ -92,10 +92,15 @@ constexpr size_t bracket_lds_bytes() {
 }
 
 // GM x GN wavefronts; each owns WM x WN MFMA tiles of 32 x 32: TM = 32 GM WM hidden rows, TN = 32 GN WN items.
-// PIPE selects the hand-ordered main loop.  EPI: instead of storing the product, the epilogue of the
-// bracketed selection (Section 3.3 Step 2 for a batch of hidden rows) classifies it.
-template <int GM, int GN, int WM, int WN, bool PIPE, bool EPI>
-__global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs a, const BracketEpi ep) {
+// PIPE selects the hand-ordered main loop.  EPI: what happens to the product --
+//   EPI_STORE    it is stored;
+//   EPI_BRACKET  the epilogue of the bracketed selection (Section 3.3 Step 2 for a batch of hidden rows)
+//                classifies it, nothing is stored;
+//   EPI_PICK     Section 3.3 Step 3 for a batch of hidden rows with one sorted index list each: only the entries
+//                a row asks for are stored, straight to their place in logits_out.
+enum { EPI_STORE = 0, EPI_BRACKET = 1, EPI_PICK = 2 };
+template <int GM, int GN, int WM, int WN, bool PIPE, int EPI>
+__global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs a, const BracketEpi ep, const PickEpi pk) {
     constexpr int kThreads = 64 * GM * GN;
     constexpr int kRowsPerPass = kThreads / 8;           // loader: 8 threads per 128-byte row slice
     constexpr int TM = 32 * GM * WM, TN = 32 * GN * WN;
@@ -109,6 +114,7 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
     const int wr = wave / GN, wc = wave % GN;
     const int C = a.chunks;
     const int nk = (C + 7) / 8;
+    if (a.gate && *a.gate != a.gate_run_if) return;      // a launch that an earlier kernel of the call switched off
     const int64_t n_items = a.n_items_dev ? (int64_t)*a.n_items_dev : a.n_items;
     const int RT = (a.rows + TM - 1) / TM;
     const int64_t IT = (n_items + TN - 1) / TN;
@@ -292,7 +298,43 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
     // D[i][j]: j = lane % 32 (item), i = 8 (e / 4) + 4 (lane / 32) + e % 4 (hidden row) for element e
     const int64_t item0 = it * TN + wc * 32 * WN + (lane & 31);
     const int row0 = rt * TM + wr * 32 * WM + 4 * (lane >> 5);
-    if constexpr (EPI) {
+    if constexpr (EPI == EPI_PICK) {
+        // Band by band (the 32 GM rows that the wavefronts hold in the same accumulator group) the product goes
+        // to LDS as a [32 GM x TN] tile; then 8 (4) threads per row walk the slice of the row's sorted index list
+        // that falls into this item tile -- pk.off[r, it] .. pk.off[r, it + 1] -- and store the asked entries.
+        constexpr int kBandRows = 32 * GM;
+        constexpr int kPerRow = kThreads / kBandRows;
+        static_assert((size_t)kBandRows * TN * 4 <= (size_t)2 * kStage, "the band tile reuses the operand buffers");
+        float* s_band = reinterpret_cast<float*>(smem);
+        const int br = tid / kPerRow, sub = tid % kPerRow;                // this thread's row of the band
+        const int tile_row0 = (br / 32) * 32 * WM + (br % 32);            // + 32 m: its row of the tile
+#pragma unroll
+        for (int m = 0; m < WM; ++m) {
+            const int r = rt * TM + tile_row0 + 32 * m;
+            // the slice bounds are requested before the barrier: their latency overlaps the copy to LDS
+            uint32_t ja = 0u, jb = 0u;
+            if (r < a.rows) {
+                ja = pk.off[(int64_t)r * pk.off_stride + it];
+                jb = pk.off[(int64_t)r * pk.off_stride + it + 1];
+            }
+            __syncthreads();                               // the band tile (or, first, the operand buffers) is free
+#pragma unroll
+            for (int n = 0; n < WN; ++n)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    s_band[(wr * 32 + 8 * (e >> 2) + (e & 3) + 4 * (lane >> 5)) * TN + wc * 32 * WN + 32 * n + (lane & 31)] =
+                        acc[m][n][e];
+            __syncthreads();
+            const int32_t* list = pk.idx + (int64_t)r * pk.k;
+            float* o = pk.out + (int64_t)r * pk.k;
+            for (uint32_t j = ja + sub; j < jb; j += kPerRow) {
+                const uint32_t col = (uint32_t)(list[j] - (int32_t)(it * TN));
+                if (col < (uint32_t)TN) o[j] = s_band[br * TN + col];     // always true for a consistent table
+            }
+        }
+        return;
+    }
+    if constexpr (EPI == EPI_BRACKET) {
         // Nothing of the product is stored.  Per accumulator register (64 scores: 32 items of two hidden rows)
         // two comparisons with the rows' brackets give two lane masks:
         //   above hi  -> 2 x 32 bits of the rows' bit masks, gathered lane = row so that one store per wavefront
@@ -431,15 +473,16 @@ template <int GM, int GN, int WM, int WN>
 constexpr size_t tile_lds_bytes() { return (size_t)2 * (32 * GM * WM + 32 * GN * WN) * kRowB; }
 
 // more than 64 KiB of dynamic LDS needs an explicit opt-in per kernel instance and device
-template <int GM, int GN, int WM, int WN, bool PIPE, bool EPI>
+template <int GM, int GN, int WM, int WN, bool PIPE, int EPI>
 hipError_t opt_in_lds() {
     if (tile_lds_bytes<GM, GN, WM, WN>() <= 64 * 1024) return hipSuccess;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(&tile_mfma_kernel<GM, GN, WM, WN, PIPE, EPI>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)tile_lds_bytes<GM, GN, WM, WN>());
 }
 
-template <int GM, int GN, int WM, int WN, bool PIPE, bool EPI = false>
-hipError_t launch_tile(const GemvArgs& a, hipStream_t stream, const BracketEpi& ep = BracketEpi{}) {
+template <int GM, int GN, int WM, int WN, bool PIPE, int EPI = EPI_STORE>
+hipError_t launch_tile(const GemvArgs& a, hipStream_t stream, const BracketEpi& ep = BracketEpi{},
+                       const PickEpi& pk = PickEpi{}) {
     constexpr int TM = 32 * GM * WM, TN = 32 * GN * WN;
     const int64_t RT = (a.rows + TM - 1) / TM;
     const int64_t IT = (a.n_items + TN - 1) / TN;
@@ -448,7 +491,7 @@ hipError_t launch_tile(const GemvArgs& a, hipStream_t stream, const BracketEpi& 
     if (bx > 0x7fffffffLL) return hipErrorInvalidValue;         // more tiles than a grid dimension holds
     const size_t lds = tile_lds_bytes<GM, GN, WM, WN>();     // above 64 KiB: opted in by configure_tile_mfma_lds()
     hipLaunchKernelGGL((tile_mfma_kernel<GM, GN, WM, WN, PIPE, EPI>), dim3((unsigned)bx), dim3(64 * GM * GN), lds, stream,
-                       a, ep);
+                       a, ep, pk);
     return hipGetLastError();
 }
 
@@ -457,12 +500,15 @@ hipError_t launch_tile(const GemvArgs& a, hipStream_t stream, const BracketEpi& 
 // every instance launch_tile_mfma can pick, on the current device (called once per device, outside any
 // stream capture, by the library's device set-up)
 hipError_t configure_tile_mfma_lds() {
-    hipError_t e = opt_in_lds<2, 2, 2, 2, false, false>();
-    if (e == hipSuccess) e = opt_in_lds<2, 4, 4, 2, true, false>();
-    if (e == hipSuccess) e = opt_in_lds<2, 2, 2, 2, true, false>();
-    if (e == hipSuccess) e = opt_in_lds<2, 2, 2, 2, false, true>();
-    if (e == hipSuccess) e = opt_in_lds<2, 4, 4, 2, true, true>();
-    if (e == hipSuccess) e = opt_in_lds<2, 2, 2, 2, true, true>();
+    hipError_t e = opt_in_lds<2, 2, 2, 2, false, EPI_STORE>();
+    if (e == hipSuccess) e = opt_in_lds<2, 4, 4, 2, true, EPI_STORE>();
+    if (e == hipSuccess) e = opt_in_lds<2, 2, 2, 2, true, EPI_STORE>();
+    if (e == hipSuccess) e = opt_in_lds<2, 2, 2, 2, false, EPI_BRACKET>();
+    if (e == hipSuccess) e = opt_in_lds<2, 4, 4, 2, true, EPI_BRACKET>();
+    if (e == hipSuccess) e = opt_in_lds<2, 2, 2, 2, true, EPI_BRACKET>();
+    if (e == hipSuccess) e = opt_in_lds<2, 2, 2, 2, false, EPI_PICK>();
+    if (e == hipSuccess) e = opt_in_lds<2, 4, 4, 2, true, EPI_PICK>();
+    if (e == hipSuccess) e = opt_in_lds<2, 2, 2, 2, true, EPI_PICK>();
     return e;
 }
 
@@ -478,9 +524,20 @@ int bracket_tile_items(int rows) { return tile_instance(rows) == 2 ? 256 : 128; 
 hipError_t launch_tile_mfma_bracket(const GemvArgs& a, const BracketEpi& ep, hipStream_t stream) {
     if (a.n_items <= 0 || a.rows <= 0) return hipSuccess;
     switch (tile_instance(a.rows)) {
-        case 0: return launch_tile<2, 2, 2, 2, false, true>(a, stream, ep);
-        case 1: return launch_tile<2, 2, 2, 2, true, true>(a, stream, ep);
-        default: return launch_tile<2, 4, 4, 2, true, true>(a, stream, ep);
+        case 0: return launch_tile<2, 2, 2, 2, false, EPI_BRACKET>(a, stream, ep);
+        case 1: return launch_tile<2, 2, 2, 2, true, EPI_BRACKET>(a, stream, ep);
+        default: return launch_tile<2, 4, 4, 2, true, EPI_BRACKET>(a, stream, ep);
+    }
+}
+
+int pick_tile_items(int rows) { return bracket_tile_items(rows); }
+
+hipError_t launch_tile_mfma_pick(const GemvArgs& a, const PickEpi& pk, hipStream_t stream) {
+    if (a.n_items <= 0 || a.rows <= 0) return hipSuccess;
+    switch (tile_instance(a.rows)) {
+        case 0: return launch_tile<2, 2, 2, 2, false, EPI_PICK>(a, stream, BracketEpi{}, pk);
+        case 1: return launch_tile<2, 2, 2, 2, true, EPI_PICK>(a, stream, BracketEpi{}, pk);
+        default: return launch_tile<2, 4, 4, 2, true, EPI_PICK>(a, stream, BracketEpi{}, pk);
     }
 }
 

@@ -119,6 +119,42 @@ def test_strided_rows(rows, d, V, k):
     assert_logits_close(zs, oracle.subset_logits(hw[:, :d], Uw[:, :d], idx[0]), "bf16")
 
 
+@pytest.mark.parametrize("rows,d,V,k,kind", [
+    (70, 512, 3000, 900, "sorted"),          # 128-row tiles, compiler-ordered loop
+    (150, 512, 5000, 900, "sorted"),         # two 128-row tiles, hand-ordered loop, ragged last item tile
+    (300, 264, 3000, 3000, "sorted"),        # k = V, ragged reduction slice
+    (512, 256, 9000, 4000, "sorted"),        # 256 x 256 tiles
+    (512, 64, 2000, 10, "sorted"),           # sparse lists: most item tiles ask for nothing from a row
+    (200, 256, 4000, 1500, "repeats"),       # sorted with repeated ids
+    (130, 256, 4000, 1500, "one_descent"),   # one list out of order: the whole call takes the general path
+    (256, 128, 1000, 1000, "clustered"),     # every id of a row inside one item tile
+])
+def test_subset_logits_many_rows_sorted_lists(rows, d, V, k, kind):
+    """More than 64 hidden rows with their own SORTED lists that together cover the vocabulary: the product over
+    all of U whose epilogue stores only the asked entries; one descent anywhere sends the call down the general
+    path instead.  Element by element against the oracle either way."""
+    say(f"many rows, own lists ({kind}) rows={rows} d={d} V={V} k={k}")
+    rng = np.random.default_rng(rows + V + k)
+    U, h = rand(rng, (V, d), 0.02, "bf16"), rand(rng, (rows, d), 1.0, "bf16")
+    if kind == "repeats":
+        idx = np.sort(rng.integers(0, V, (rows, k)), axis=1).astype(np.int32)
+    elif kind == "clustered":
+        base = rng.integers(0, V - 100, (rows, 1))
+        idx = np.sort(base + rng.integers(0, 100, (rows, k)), axis=1).astype(np.int32)
+    else:
+        idx = np.stack([np.sort(rng.permutation(V)[:k]) for _ in range(rows)]).astype(np.int32)
+    if kind == "one_descent":
+        idx[rows // 2, [5, 6]] = idx[rows // 2, [6, 5]]
+    tU, th, tidx = to_dev(U), to_dev(h), torch.from_numpy(idx).to(DEV)
+    z = sv.subset_logits(th, tU, tidx).cpu().numpy()
+    assert_logits_close(z, oracle.subset_logits(h, U, idx), "bf16")
+    z2, tok, prob, _ = sv.draft_step(th, tU, tidx, min(10, k))
+    assert np.array_equal(z2.cpu().numpy(), z)
+    if kind != "repeats":                                   # draft tokens need unique ids within a row
+        tok_ref, _ = oracle.softmax_topk(z, idx, min(10, k))
+        assert np.array_equal(tok.cpu().numpy(), tok_ref)
+
+
 def test_duplicate_and_unsorted_indices_are_just_gathered():
     say("duplicate indices")
     rng = np.random.default_rng(6)
