@@ -34,7 +34,8 @@
  *           every call that takes an index list then first runs a range check over it, waits for
  *           the stream (so the call is no longer asynchronous nor capturable), and returns
  *           SV_ERR_INDEX without launching the operation if an entry lies outside [0, V) (a padding
- *           slot, -1, is accepted in lists passed with SV_IDX_PADDED).
+ *           slot, -1, is accepted in lists passed with SV_IDX_PADDED) or if a list declared with
+ *           SV_IDX_SORTED descends.
  * Precision.Products of the stored values are accumulated in float32 (order unspecified).
  *           With SV_BF16 storage the intermediate h' of the selector is rounded to bfloat16
  *           (round-to-nearest-even) before the second projection; with SV_F32 it stays float32.
@@ -84,6 +85,15 @@ typedef enum { SV_IDX_PER_ROW = 0, SV_IDX_PER_STEP = 1 } sv_idx_mode;
  * (specvocab_workspace_bytes with the flagged idx_mode) and two small extra launches.  Lists
  * without the flag must not contain -1. */
 #define SV_IDX_PADDED 4
+
+/* OR this flag into idx_mode to DECLARE that every list is sorted by ascending id (repeats allowed), which is how
+ * specvocab_select emits its lists.  A declaration, not a request: the library does not sort, and a list that is
+ * not sorted then gives wrong logits (never an access out of bounds; the debug mode reports SV_ERR_INDEX).  It
+ * matters for a large batch: with more than 64 bf16 hidden rows, one list per row and rows * k >= 2 V -- sets that
+ * together cover the vocabulary -- the gathering calls read all of U once, tile by tile, and store only the
+ * entries each row asks for, instead of forming the union in the workspace and picking from a
+ * [rows x |union|] product.  Ignored together with SV_IDX_PADDED and wherever it makes no difference. */
+#define SV_IDX_SORTED 8
 
 typedef enum {
     SV_OP_SELECT = 0,
@@ -245,6 +255,12 @@ int specvocab_aux_log_softmax(const void* h, int64_t rows, int64_t d, int64_t ld
                               const void* W_vocab, int64_t V, int dt,
                               float* logq_out,
                               void* ws, size_t ws_bytes, void* stream);
+
+/* Measurement aid, not part of the method: one plain streaming read of buf (device, 16-byte aligned, `bytes` a
+ * multiple of 16): every lane loads 16 bytes per instruction, consecutive lanes consecutive addresses, nothing
+ * is written.  Timed over a buffer much larger than the caches it gives the read bandwidth a kernel can reach on
+ * the machine, which the benchmark quotes beside the published HBM peak.  ws: 262144 bytes of device scratch. */
+int specvocab_stream_read_probe(const void* buf, size_t bytes, void* ws, size_t ws_bytes, void* stream);
 
 /* Section 3.1, the full-vocabulary baseline:  logits_out[r, v] = < U[v, :], h[r, :] >.
  * logits_out: device [rows x V] float32. */

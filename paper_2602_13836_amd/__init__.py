@@ -22,6 +22,7 @@ SV_OP_SELECT, SV_OP_SUBSET_LOGITS, SV_OP_DRAFT_TOPK, SV_OP_DENSE_LOGITS, SV_OP_D
 SV_OP_INDEXED_HEAD_NAIVE = 5
 SV_OP_AUX_LOG_SOFTMAX = 6
 SV_IDX_PADDED = 4        # OR into idx_mode: the list may hold padding slots (-1)
+SV_IDX_SORTED = 8        # OR into idx_mode: every list is sorted by ascending id (what select emits)
 MAX_KD = 64
 SELECT_SAMPLE = 8192     # sampled tokens of the batch selection: ids floor(j * V / SELECT_SAMPLE)
 
@@ -39,6 +40,7 @@ EXPORTS = (
     "specvocab_indexed_head_naive",
     "specvocab_pack_rows",
     "specvocab_aux_log_softmax",
+    "specvocab_stream_read_probe",
     "specvocab_dense_logits",
 )
 
@@ -95,6 +97,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.specvocab_draft_step.restype = ci
     lib.specvocab_draft_step.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, i64, ci, i64, vp, vp, vp, vp, vp,
                                          ctypes.c_size_t, vp]
+    lib.specvocab_stream_read_probe.restype = ci
+    lib.specvocab_stream_read_probe.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
     lib.specvocab_dense_logits.restype = ci
     lib.specvocab_dense_logits.argtypes = [vp, i64, i64, i64, vp, i64, i64, ci, vp, vp, ctypes.c_size_t, vp]
     if path is None:
@@ -237,9 +241,11 @@ def select_static(h: torch.Tensor, W_down: torch.Tensor, W_vocab: torch.Tensor, 
 
 def subset_logits(h: torch.Tensor, U: torch.Tensor, idx: torch.Tensor,
                   out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
-                  stream: Optional[torch.cuda.Stream] = None, padded: bool = False) -> torch.Tensor:
+                  stream: Optional[torch.cuda.Stream] = None, padded: bool = False,
+                  sorted_lists: bool = False) -> torch.Tensor:
     """specvocab_subset_logits: out[r, j] = <U[idx(r, j)], h_r>, [rows x k] float32.
-    padded=True: idx may hold padding slots (-1), whose logit is -inf."""
+    padded=True: idx may hold padding slots (-1), whose logit is -inf.
+    sorted_lists=True: the caller declares every list sorted by ascending id (SV_IDX_SORTED)."""
     rows, d, ldh = _mat(h, "h")
     V, d2, ldu = _mat(U, "U")
     if d2 != d:
@@ -250,6 +256,8 @@ def subset_logits(h: torch.Tensor, U: torch.Tensor, idx: torch.Tensor,
     mode, k = _idx(idx, rows)
     if padded:
         mode |= SV_IDX_PADDED
+    if sorted_lists:
+        mode |= SV_IDX_SORTED
     if out is None:
         out = torch.empty((rows, k), dtype=torch.float32, device=h.device)
     nbytes = workspace_bytes(SV_OP_SUBSET_LOGITS, rows, d, V, k, 0, 0, dt, mode)
@@ -358,7 +366,7 @@ def draft_step(h: torch.Tensor, U: torch.Tensor, idx: torch.Tensor, kd: int,
                logits_out: Optional[torch.Tensor] = None, tok_out: Optional[torch.Tensor] = None,
                prob_out: Optional[torch.Tensor] = None, probs_full_out: Optional[torch.Tensor] = None,
                want_probs: bool = False, ws: Optional[torch.Tensor] = None,
-               stream: Optional[torch.cuda.Stream] = None, padded: bool = False):
+               stream: Optional[torch.cuda.Stream] = None, padded: bool = False, sorted_lists: bool = False):
     """specvocab_draft_step: subset logits, then subset softmax and top-kd tokens of every row,
     enqueued back to back. Returns (logits [rows x k], tok [rows x kd], prob [rows x kd],
     q_K [rows x k] or None)."""
@@ -372,6 +380,8 @@ def draft_step(h: torch.Tensor, U: torch.Tensor, idx: torch.Tensor, kd: int,
     mode, k = _idx(idx, rows)
     if padded:
         mode |= SV_IDX_PADDED
+    if sorted_lists:
+        mode |= SV_IDX_SORTED
     dev = h.device
     if logits_out is None:
         logits_out = torch.empty((rows, k), dtype=torch.float32, device=dev)
@@ -389,6 +399,15 @@ def draft_step(h: torch.Tensor, U: torch.Tensor, idx: torch.Tensor, kd: int,
                                                _stream(stream)),
            "specvocab_draft_step")
     return logits_out, tok_out, prob_out, probs_full_out
+
+
+def stream_read_probe(buf: torch.Tensor, ws: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """specvocab_stream_read_probe: one plain streaming read of buf (measurement aid)."""
+    if not buf.is_cuda or not buf.is_contiguous() or not ws.is_cuda or ws.dtype != torch.uint8:
+        raise ValueError("buf and ws must be contiguous GPU tensors (ws uint8)")
+    nbytes = buf.numel() * buf.element_size()
+    _check(load_library().specvocab_stream_read_probe(_ptr(buf), nbytes - nbytes % 16, _ptr(ws), ws.numel(),
+                                                      _stream(stream)), "specvocab_stream_read_probe")
 
 
 def dense_logits(h: torch.Tensor, U: torch.Tensor, out: Optional[torch.Tensor] = None,

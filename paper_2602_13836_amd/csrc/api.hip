@@ -82,9 +82,11 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline size_t round256(size_t n) { return (n + 255u) & ~static_cast<size_t>(255u); }
 inline int esize_of(int dt) { return dt == SV_BF16 ? 2 : 4; }
 inline bool dtype_ok(int dt) { return dt == SV_F32 || dt == SV_BF16; }
-inline bool mode_ok(int m) { return (m & ~SV_IDX_PADDED) == SV_IDX_PER_ROW || (m & ~SV_IDX_PADDED) == SV_IDX_PER_STEP; }
+constexpr int kModeFlags = SV_IDX_PADDED | SV_IDX_SORTED;
+inline bool mode_ok(int m) { return (m & ~kModeFlags) == SV_IDX_PER_ROW || (m & ~kModeFlags) == SV_IDX_PER_STEP; }
 inline bool is_padded(int m) { return (m & SV_IDX_PADDED) != 0; }
-inline int base_mode(int m) { return m & ~SV_IDX_PADDED; }
+inline bool is_sorted(int m) { return (m & SV_IDX_SORTED) != 0 && !is_padded(m); }   // a padded list is not sorted once cleaned
+inline int base_mode(int m) { return m & ~kModeFlags; }
 
 // a row of `n` elements must be a whole number of 16-byte units, and so must its stride
 inline int check_row(int64_t n, int64_t ld, int dt) {
@@ -120,11 +122,12 @@ SelectWs select_ws(int64_t rows, int64_t V, int64_t d_prime, int64_t k, int dt) 
 }
 
 // Debug mode (environment variable SPECVOCAB_VALIDATE=1): range-check an index list before using it.
-int validate_indices(const int32_t* idx, int64_t n, int64_t V, hipStream_t s, bool padded = false) {
+int validate_indices(const int32_t* idx, int64_t n, int64_t V, hipStream_t s, bool padded = false,
+                     int64_t sorted_row_len = 0) {
     const char* v = getenv("SPECVOCAB_VALIDATE");
     if (!v || strcmp(v, "1") != 0) return SV_OK;
     unsigned bad = 0;
-    if (sv::count_bad_indices(idx, n, V, padded, s, &bad) != hipSuccess) return SV_ERR_HIP;
+    if (sv::count_bad_indices(idx, n, V, padded, sorted_row_len, s, &bad) != hipSuccess) return SV_ERR_HIP;
     return bad ? SV_ERR_INDEX : SV_OK;
 }
 
@@ -173,10 +176,16 @@ size_t pad_ws_bytes(int64_t rows, int64_t k, int idx_mode, int dt, const sv::Gem
     return round256((size_t)sets * (size_t)k * sizeof(int32_t));
 }
 
+// what the product itself needs from the workspace: the slice table of the sorted-lists path, or the union
+size_t product_ws_bytes(int dt, const sv::GemvArgs& g, int64_t rows, int64_t V, int64_t k, int idx_mode) {
+    if (is_sorted(idx_mode) && sv::sorted_pick_wanted(dt, g, V)) return sv::sorted_pick_ws_bytes(rows, V);
+    return sv::union_path_wanted(dt, g) ? sv::union_ws_bytes(rows, V, k) : 0;
+}
+
 size_t gather_ws_bytes(int64_t rows, int64_t d, int64_t V, int64_t k, int dt, int idx_mode) {
     sv::GemvArgs g = gather_args(nullptr, rows, d, d, nullptr, d, dt, reinterpret_cast<const int32_t*>(16), k,
                                  idx_mode, nullptr);
-    return pad_ws_bytes(rows, k, idx_mode, dt, g) + (sv::union_path_wanted(dt, g) ? sv::union_ws_bytes(rows, V, k) : 0);
+    return pad_ws_bytes(rows, k, idx_mode, dt, g) + product_ws_bytes(dt, g, rows, V, k, idx_mode);
 }
 
 // Gathered logits for an index list that may carry padding slots (SV_IDX_PADDED).  The row-gather
@@ -193,16 +202,18 @@ int launch_gather(int dt, const void* h, int64_t rows, int64_t d, int64_t ldh, c
     // checked here, before the first launch
     const bool copy = padded && padded_needs_copy(dt, g0);
     const size_t pb = copy ? pad_ws_bytes(rows, k, idx_mode, dt, g0) : 0;
-    const size_t need = pb + (sv::union_path_wanted(dt, g0) ? sv::union_ws_bytes(rows, V, k) : 0);
+    const size_t need = pb + product_ws_bytes(dt, g0, rows, V, k, idx_mode);
     if (need) {
         if (!ws || ws_bytes < need) return SV_ERR_WORKSPACE;
         if (!aligned16(ws)) return SV_ERR_ALIGN;
     }
     sv::DeviceInfo di;
     if (sv::device_info(&di) != hipSuccess) return SV_ERR_HIP;       // device set-up, if this is the first call
-    int st = validate_indices(idx, sets * k, V, s, padded);
+    int st = validate_indices(idx, sets * k, V, s, padded, is_sorted(idx_mode) ? k : 0);
     if (st != SV_OK) return st;
     if (padded && !copy) return sv::launch_gemv(dt, g0, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
+    if (is_sorted(idx_mode) && sv::sorted_pick_wanted(dt, g0, V))
+        return sv::launch_sorted_pick_logits(g0, V, ws, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
     const int32_t* use = idx;
     char* rest = static_cast<char*>(ws);
     size_t rest_bytes = ws_bytes;
@@ -325,7 +336,7 @@ int specvocab_workspace_bytes(int op, int64_t rows, int64_t d, int64_t V, int64_
             if (!dtype_ok(dt) || !mode_ok(idx_mode)) return SV_ERR_DTYPE;
             if (rows < 1 || rows > kMaxRows || k < 1 || d < 1) return SV_ERR_SHAPE;
             if (is_padded(idx_mode)) return SV_ERR_UNSUPPORTED;
-            const int64_t sets = idx_mode == SV_IDX_PER_ROW ? rows : 1;
+            const int64_t sets = base_mode(idx_mode) == SV_IDX_PER_ROW ? rows : 1;
             *bytes_out = round256((size_t)sets * (size_t)k * (size_t)d * (size_t)esize_of(dt));
             return SV_OK;
         }
@@ -546,7 +557,7 @@ int specvocab_indexed_head_naive(const void* h, int64_t rows, int64_t d, int64_t
     if (st != SV_OK) return st;
     if (!aligned16(h) || !aligned16(U) || !aligned16(ws)) return SV_ERR_ALIGN;
     const int es = esize_of(dt);
-    const int64_t sets = idx_mode == SV_IDX_PER_ROW ? rows : 1;
+    const int64_t sets = base_mode(idx_mode) == SV_IDX_PER_ROW ? rows : 1;
     const size_t need = (size_t)sets * (size_t)k * (size_t)d * (size_t)es;
     if (!ws || ws_bytes < need) return SV_ERR_WORKSPACE;
     if (ensure_device() != SV_OK) return SV_ERR_HIP;
@@ -563,7 +574,7 @@ int specvocab_indexed_head_naive(const void* h, int64_t rows, int64_t d, int64_t
         sv::GemvArgs g{};
         g.x = static_cast<const char*>(h) + r * ldh * es;
         g.x_row_bytes = ldh * es;
-        g.M = static_cast<const char*>(ws) + (idx_mode == SV_IDX_PER_ROW ? (size_t)r * k * d * es : 0);
+        g.M = static_cast<const char*>(ws) + (base_mode(idx_mode) == SV_IDX_PER_ROW ? (size_t)r * k * d * es : 0);
         g.m_row_bytes = d * es;
         g.idx = nullptr;
         g.n_items = k;
@@ -651,6 +662,18 @@ int specvocab_draft_step(const void* h, int64_t rows, int64_t d, int64_t ldh, co
     if (st != SV_OK) return st;
     if (sv::launch_softmax_topk(t, s) != hipSuccess) return SV_ERR_HIP;
     return SV_OK;
+}
+
+int specvocab_stream_read_probe(const void* buf, size_t bytes, void* ws, size_t ws_bytes, void* stream) {
+    if (!buf || !ws) return SV_ERR_NULL;
+    if (bytes < 16 || bytes % 16 != 0) return SV_ERR_SHAPE;
+    if (!aligned16(buf) || !aligned16(ws)) return SV_ERR_ALIGN;
+    sv::DeviceInfo di;
+    if (sv::device_info(&di) != hipSuccess) return SV_ERR_HIP;
+    if (ws_bytes < (size_t)sv::stream_read_blocks(di.cus) * sizeof(uint32_t)) return SV_ERR_WORKSPACE;
+    return sv::launch_stream_read(buf, bytes, static_cast<uint32_t*>(ws), static_cast<hipStream_t>(stream)) == hipSuccess
+               ? SV_OK
+               : SV_ERR_HIP;
 }
 
 int specvocab_dense_logits(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* U, int64_t V,

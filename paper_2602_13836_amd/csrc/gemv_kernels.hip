@@ -184,11 +184,12 @@ __global__ __launch_bounds__(256) void gemv_long_rows_kernel(const GemvArgs a) {
 __device__ unsigned int g_bad_indices;
 
 __global__ __launch_bounds__(256) void check_indices_kernel(const int32_t* idx, int64_t n, int64_t V,
-                                                            int64_t lowest) {
+                                                            int64_t lowest, int64_t sorted_row_len) {
     unsigned bad = 0;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
         const int64_t v = idx[i];
         bad += (v < lowest) || (v >= V);
+        if (sorted_row_len > 0 && i % sorted_row_len != 0) bad += v < (int64_t)idx[i - 1];   // a declared order
     }
     if (bad) atomicAdd(&g_bad_indices, bad);
 }
@@ -313,8 +314,8 @@ hipError_t launch_pad_mask(const int32_t* idx, int64_t idx_row_stride, int rows,
     return hipGetLastError();
 }
 
-hipError_t count_bad_indices(const int32_t* idx, int64_t n, int64_t V, bool padded, hipStream_t stream,
-                             unsigned* bad_out) {
+hipError_t count_bad_indices(const int32_t* idx, int64_t n, int64_t V, bool padded, int64_t sorted_row_len,
+                             hipStream_t stream, unsigned* bad_out) {
     const unsigned zero = 0;
     hipError_t e = hipMemcpyToSymbolAsync(HIP_SYMBOL(g_bad_indices), &zero, sizeof zero, 0, hipMemcpyHostToDevice,
                                           stream);
@@ -323,7 +324,7 @@ hipError_t count_bad_indices(const int32_t* idx, int64_t n, int64_t V, bool padd
     if (bx > 1024) bx = 1024;
     if (bx < 1) bx = 1;
     hipLaunchKernelGGL(check_indices_kernel, dim3((unsigned)bx), dim3(256), 0, stream, idx, n, V,
-                       (int64_t)(padded ? -1 : 0));
+                       (int64_t)(padded ? -1 : 0), sorted_row_len);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     e = hipMemcpyFromSymbolAsync(bad_out, HIP_SYMBOL(g_bad_indices), sizeof(unsigned), 0, hipMemcpyDeviceToHost,

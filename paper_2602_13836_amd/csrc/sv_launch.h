@@ -44,8 +44,6 @@ struct GemvArgs {
     int64_t spread_V;
     const uint32_t* n_items_dev;   // optional (matrix-core kernel only): the item count lives on the
                                    // device; n_items is then an upper bound that sizes the grid
-    const uint32_t* gate;          // optional (tiled matrix-core kernel only): the launch does nothing unless
-    uint32_t gate_run_if;          // *gate == gate_run_if (a device-side decision between two enqueued paths)
 };
 // what a launch does for later kernels besides its product: every thread of the grid calls this once
 __device__ __forceinline__ void prepare_scratch(const GemvArgs& a) {
@@ -61,9 +59,10 @@ __device__ __forceinline__ void prepare_scratch(const GemvArgs& a) {
 // row 0 and gets -inf in a float32 output; the matrix-core and union paths need lists without them)
 hipError_t launch_gemv(int dt, const GemvArgs& a, hipStream_t stream);
 
-// debug aid: number of entries of idx[0..n) outside [0, V) (padded: -1 is allowed); synchronises the stream
-hipError_t count_bad_indices(const int32_t* idx, int64_t n, int64_t V, bool padded, hipStream_t stream,
-                             unsigned* bad_out);
+// debug aid: number of entries of idx[0..n) outside [0, V) (padded: -1 is allowed) plus, if sorted_row_len > 0,
+// the number of descents inside the lists of that length; synchronises the stream
+hipError_t count_bad_indices(const int32_t* idx, int64_t n, int64_t V, bool padded, int64_t sorted_row_len,
+                             hipStream_t stream, unsigned* bad_out);
 
 // copies rows M[idx[j], :] (j < n_sets * k) into a dense [n_sets * k x chunks * 16 B] matrix
 hipError_t launch_materialize_rows(const char* M, int64_t m_row_bytes, const int32_t* idx, int64_t n_rows,
@@ -99,8 +98,7 @@ hipError_t launch_tile_mfma_bracket(const GemvArgs& a, const BracketEpi& ep, hip
 // The tiled product over ALL rows of M (a.idx == nullptr, a.n_items = V) with the pick epilogue: only
 //     out[r, j] = < M[idx[r, j], :], x[r, :] >
 // is stored.  Every row's list must be sorted (non-decreasing); off[r, t] = first j with idx[r, j] >= t * tile
-// items (off[r, tiles] = k) says which slice of the list falls into item tile t.  The launch does nothing
-// unless *gate == 0 (the kernel that builds off also checks the order and raises the flag).
+// items (off[r, tiles] = k) says which slice of the list falls into item tile t.
 struct PickEpi {
     const uint32_t* off;     // [rows][off_stride]
     int64_t off_stride;      // item tiles + 1
@@ -124,6 +122,11 @@ hipError_t launch_pad_mask(const int32_t* idx, int64_t idx_row_stride, int rows,
 // Per-row index sets for several hidden rows (a draft tree): the union of the sets is formed on the
 // device, every row of M in the union is read once and multiplied with all hidden rows on the matrix
 // cores, and each (row, j) picks its logit out of that product.
+// Several hidden rows with their own SORTED lists (the caller's declaration) that together are likely to cover
+// the vocabulary: the product over all rows of M with the pick epilogue; ws: sorted_pick_ws_bytes
+bool sorted_pick_wanted(int dt, const GemvArgs& a, int64_t V);
+size_t sorted_pick_ws_bytes(int64_t rows, int64_t V);
+hipError_t launch_sorted_pick_logits(const GemvArgs& a, int64_t V, void* ws, hipStream_t stream);
 bool union_path_wanted(int dt, const GemvArgs& a);
 size_t union_ws_bytes(int64_t rows, int64_t V, int64_t k);
 hipError_t launch_union_logits(const GemvArgs& a, int64_t V, void* ws, hipStream_t stream);
@@ -180,6 +183,10 @@ bool bracket_select_supported(int dt, int64_t rows, int64_t V, int64_t k);
 size_t bracket_scratch_words(int64_t rows, int64_t V);
 void bracket_sample(int64_t rows, int64_t V, uint32_t* scratch, int32_t** ids, int64_t* m, float** samp);
 hipError_t launch_bracket_select(const BracketArgs& a, hipStream_t stream);
+
+// measurement aid: a plain coalesced read of `bytes` (a multiple of 16) from buf; sink: stream_read_blocks() words
+inline int stream_read_blocks(int cus) { return cus * 64; }
+hipError_t launch_stream_read(const void* buf, size_t bytes, uint32_t* sink, hipStream_t stream);
 
 // subset softmax + top-kd
 struct TopkArgs {

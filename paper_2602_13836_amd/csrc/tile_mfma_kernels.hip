@@ -114,7 +114,6 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
     const int wr = wave / GN, wc = wave % GN;
     const int C = a.chunks;
     const int nk = (C + 7) / 8;
-    if (a.gate && *a.gate != a.gate_run_if) return;      // a launch that an earlier kernel of the call switched off
     const int64_t n_items = a.n_items_dev ? (int64_t)*a.n_items_dev : a.n_items;
     const int RT = (a.rows + TM - 1) / TM;
     const int64_t IT = (n_items + TN - 1) / TN;
@@ -316,6 +315,7 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
             if (r < a.rows) {
                 ja = pk.off[(int64_t)r * pk.off_stride + it];
                 jb = pk.off[(int64_t)r * pk.off_stride + it + 1];
+                if (jb > (uint32_t)pk.k) jb = (uint32_t)pk.k;             // (a table built from an unsorted list: stay in bounds)
             }
             __syncthreads();                               // the band tile (or, first, the operand buffers) is free
 #pragma unroll

@@ -15,12 +15,11 @@
 //
 // Many hidden rows whose sets together cover the vocabulary (a large batch, Section 3.5 "Inference"): the
 // union is (nearly) everything, so there is nothing to compact, and a [rows x |union|] scratch plus a pick
-// pass would move more bytes than U.  If every row's list is sorted -- what the selection emits -- the
-// slice of a list that falls into an item tile is contiguous:
-//   slices   off[r, t] = first j with idx[r, j] >= t * tile items, and a flag raised by any descent;
+// pass would move more bytes than U.  When the caller declares every row's list sorted -- what the selection
+// emits -- the slice of a list that falls into an item tile is contiguous:
+//   slices   off[r, t] = first j with idx[r, j] >= t * tile items;
 //   product  over ALL rows of U, tile by tile, whose epilogue stores only the asked entries, straight
-//            into logits_out (tile_mfma_kernels.hip) -- it runs only if the flag stayed down;
-//   the launches of the general path above follow, and run only if the flag went up.
+//            into logits_out (tile_mfma_kernels.hip).
 #include "sv_device.h"
 #include "sv_launch.h"
 
@@ -56,25 +55,18 @@ inline UnionWs carve(void* ws, int64_t rows, int64_t V, int64_t k) {
     return w;
 }
 
-// gate != nullptr: the launch does nothing unless *gate == run_if
-__device__ __forceinline__ bool gated_off(const uint32_t* gate, uint32_t run_if) { return gate && *gate != run_if; }
-
-__global__ __launch_bounds__(256) void clear_kernel(uint32_t* p, size_t n, const uint32_t* gate, uint32_t run_if) {
-    if (gated_off(gate, run_if)) return;
+__global__ __launch_bounds__(256) void clear_kernel(uint32_t* p, size_t n) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
         p[i] = 0u;
 }
 
-__global__ __launch_bounds__(256) void mark_kernel(const int32_t* idx, int64_t pairs, uint32_t* flag,
-                                                   const uint32_t* gate, uint32_t run_if) {
-    if (gated_off(gate, run_if)) return;
+__global__ __launch_bounds__(256) void mark_kernel(const int32_t* idx, int64_t pairs, uint32_t* flag) {
     for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < pairs; p += (int64_t)gridDim.x * blockDim.x)
         flag[idx[p]] = 1u;
 }
 
 __global__ __launch_bounds__(kUThreads) void compact_kernel(uint32_t* pos, int64_t V, int32_t* ulist,
-                                                            uint32_t* counter, const uint32_t* gate, uint32_t run_if) {
-    if (gated_off(gate, run_if)) return;
+                                                            uint32_t* counter) {
     __shared__ uint32_t s_w[kUWaves];
     __shared__ uint32_t s_base;
     const int tid = threadIdx.x;
@@ -104,9 +96,7 @@ __global__ __launch_bounds__(kUThreads) void compact_kernel(uint32_t* pos, int64
 }
 
 __global__ __launch_bounds__(256) void pick_kernel(const int32_t* idx, int64_t k, int64_t pairs, const uint32_t* pos,
-                                                   const float* zu, int64_t zu_stride, float* out,
-                                                   const uint32_t* gate, uint32_t run_if) {
-    if (gated_off(gate, run_if)) return;
+                                                   const float* zu, int64_t zu_stride, float* out) {
     for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < pairs; p += (int64_t)gridDim.x * blockDim.x) {
         const int64_t r = p / k;
         out[p] = zu[r * zu_stride + pos[idx[p]]];
@@ -115,19 +105,19 @@ __global__ __launch_bounds__(256) void pick_kernel(const int32_t* idx, int64_t k
 
 // off[r, t] for t = 0 .. tiles (see the overview), one thread per list entry: the entry at j fills the table
 // for every tile that starts after its predecessor and not after itself; the last entry also closes the row.
-// *unsorted (zero before the launch) is raised if a list descends anywhere or holds a negative entry: the table
-// is then meaningless and the general path takes over.
+// A list that is not sorted (the caller's contract) leaves entries of the table unwritten or inconsistent; the
+// product's epilogue clamps what it reads from it, so the result is then wrong but every access stays in bounds.
 __global__ __launch_bounds__(256) void slice_table_kernel(const int32_t* idx, int64_t k, int tile_items, int64_t tiles,
-                                                          uint32_t* off, uint32_t* unsorted) {
+                                                          uint32_t* off) {
     const int64_t r = blockIdx.y;
     const int32_t* list = idx + r * k;
     uint32_t* o = off + r * (tiles + 1);
     for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < k; j += (int64_t)gridDim.x * blockDim.x) {
         const int32_t v = list[j];
         const int32_t prev = j > 0 ? list[j - 1] : 0;
-        if (v < prev || v < 0) *unsorted = 1u;                // benign race: every writer stores the same value
         const int64_t t_first = j > 0 ? (int64_t)prev / tile_items + 1 : 0;   // tiles that start after the predecessor
         int64_t t_last = v >= 0 ? (int64_t)v / tile_items : -1;
+        if (prev < 0 || t_first < 0) continue;                // (negative ids: outside the contract)
         if (t_last > tiles - 1) t_last = tiles - 1;           // (an id past the vocabulary: the caller's contract)
         for (int64_t t = t_first; t <= t_last; ++t) o[t] = (uint32_t)j;
         if (j == k - 1)
@@ -150,17 +140,41 @@ bool union_path_wanted(int dt, const GemvArgs& a) {
     return pairs >= 16384 && (a.rows >= 16 || naive_bytes >= ((int64_t)512 << 20));
 }
 
-// the sorted-lists path for many rows: worth it when the sets are likely to cover most of the vocabulary
-static bool dense_pick_wanted(int64_t rows, int64_t V, int64_t k) { return rows > 64 && rows * k >= 2 * V; }
-static size_t slice_table_words(int64_t rows, int64_t V) {
+// The sorted-lists path for many rows: worth it when the sets are likely to cover most of the vocabulary
+// (rows k >= 2 V), where reading all of U costs no more than reading the union.
+bool sorted_pick_wanted(int dt, const GemvArgs& a, int64_t V) {
+    return dt == DT_BF16 && a.rows > 64 && a.idx != nullptr && a.idx_row_stride != 0 && a.out_bf16 == nullptr &&
+           (int64_t)a.rows * a.n_items >= 2 * V;
+}
+size_t sorted_pick_ws_bytes(int64_t rows, int64_t V) {
     const int64_t tiles = (V + pick_tile_items((int)rows) - 1) / pick_tile_items((int)rows);
-    return ((size_t)rows * (size_t)(tiles + 1) + 3) & ~(size_t)3;
+    return (((size_t)rows * (size_t)(tiles + 1) + 3) & ~(size_t)3) * sizeof(uint32_t);
+}
+
+hipError_t launch_sorted_pick_logits(const GemvArgs& a, int64_t V, void* ws, hipStream_t stream) {
+    const int64_t k = a.n_items;
+    const int tn = pick_tile_items(a.rows);
+    const int64_t tiles = (V + tn - 1) / tn;
+    uint32_t* table = static_cast<uint32_t*>(ws);
+    const unsigned sb = (unsigned)((k + 1023) / 1024);
+    hipLaunchKernelGGL(slice_table_kernel, dim3(sb, (unsigned)a.rows), dim3(256), 0, stream, a.idx, k, tn, tiles, table);
+    GemvArgs dense = a;
+    dense.idx = nullptr;
+    dense.idx_row_stride = 0;
+    dense.n_items = V;
+    dense.out_f32 = nullptr;
+    PickEpi pk{};
+    pk.off = table;
+    pk.off_stride = tiles + 1;
+    pk.idx = a.idx;
+    pk.k = k;
+    pk.out = a.out_f32;
+    return launch_tile_mfma_pick(dense, pk, stream);
 }
 
 size_t union_ws_bytes(int64_t rows, int64_t V, int64_t k) {
     const size_t vpad = ((size_t)V + 3) & ~(size_t)3;
-    const size_t table = dense_pick_wanted(rows, V, k) ? slice_table_words(rows, V) : 0;
-    return (4 + 2 * vpad + (size_t)rows * (size_t)union_cap(rows, V, k) + table) * sizeof(uint32_t);
+    return (4 + 2 * vpad + (size_t)rows * (size_t)union_cap(rows, V, k)) * sizeof(uint32_t);
 }
 
 hipError_t launch_union_logits(const GemvArgs& a, int64_t V, void* ws, hipStream_t stream) {
@@ -171,48 +185,15 @@ hipError_t launch_union_logits(const GemvArgs& a, int64_t V, void* ws, hipStream
     const int64_t pairs = (int64_t)a.rows * k;
     const UnionWs w = carve(ws, a.rows, V, k);
 
-    // Many rows whose sets together are likely to cover the vocabulary: the product over all of U with the
-    // pick epilogue, if every list turns out to be sorted; the general path below is enqueued as well and runs
-    // only if one is not (word 1 of the counter block is the flag; the down-pointing launches cost ~2 us each).
-    const uint32_t* gate = nullptr;
-    if (dense_pick_wanted(a.rows, V, k)) {
-        const int tn = pick_tile_items(a.rows);
-        const int64_t tiles = (V + tn - 1) / tn;
-        uint32_t* table = reinterpret_cast<uint32_t*>(w.zu) + (size_t)a.rows * (size_t)w.zu_stride;
-        uint32_t* flag = w.counter + 1;
-        hipLaunchKernelGGL(clear_kernel, dim3(1), dim3(256), 0, stream, w.counter, (size_t)4, nullptr, 0u);
-        unsigned sb = (unsigned)((k + 1023) / 1024);
-        hipLaunchKernelGGL(slice_table_kernel, dim3(sb, (unsigned)a.rows), dim3(256), 0, stream, a.idx, k, tn, tiles, table,
-                           flag);
-        GemvArgs dense = a;
-        dense.idx = nullptr;
-        dense.idx_row_stride = 0;
-        dense.n_items = V;
-        dense.out_f32 = nullptr;
-        dense.gate = flag;
-        dense.gate_run_if = 0u;
-        PickEpi pk{};
-        pk.off = table;
-        pk.off_stride = tiles + 1;
-        pk.idx = a.idx;
-        pk.k = k;
-        pk.out = a.out_f32;
-        e = launch_tile_mfma_pick(dense, pk, stream);
-        if (e != hipSuccess) return e;
-        gate = flag;                                      // the general path: only if the flag went up
-    }
-
-    // counter block + flags are contiguous; behind a gate the counter block is already clear and its word 1,
-    // the order flag, must stay as the slice kernel left it
-    const size_t nclear = gate ? (size_t)V : 4 + (size_t)V;
+    const size_t nclear = 4 + (size_t)V;                  // counter + flags (contiguous)
     unsigned cb = (unsigned)((nclear + 1023) / 1024);
     if (cb > (unsigned)di.cus * 4) cb = (unsigned)di.cus * 4;
-    hipLaunchKernelGGL(clear_kernel, dim3(cb), dim3(256), 0, stream, gate ? w.pos : w.counter, nclear, gate, 1u);
+    hipLaunchKernelGGL(clear_kernel, dim3(cb), dim3(256), 0, stream, w.counter, nclear);
     unsigned mb = (unsigned)((pairs + 1023) / 1024);
     if (mb > (unsigned)di.cus * 8) mb = (unsigned)di.cus * 8;
-    hipLaunchKernelGGL(mark_kernel, dim3(mb), dim3(256), 0, stream, a.idx, pairs, w.pos, gate, 1u);
+    hipLaunchKernelGGL(mark_kernel, dim3(mb), dim3(256), 0, stream, a.idx, pairs, w.pos);
     const unsigned vb = (unsigned)((V + kUThreads * kUEpt - 1) / (kUThreads * kUEpt));
-    hipLaunchKernelGGL(compact_kernel, dim3(vb), dim3(kUThreads), 0, stream, w.pos, V, w.ulist, w.counter, gate, 1u);
+    hipLaunchKernelGGL(compact_kernel, dim3(vb), dim3(kUThreads), 0, stream, w.pos, V, w.ulist, w.counter);
 
     GemvArgs u = a;                                       // product over the union list, all hidden rows
     u.idx = w.ulist;
@@ -221,13 +202,11 @@ hipError_t launch_union_logits(const GemvArgs& a, int64_t V, void* ws, hipStream
     u.n_items_dev = w.counter;
     u.out_f32 = w.zu;
     u.out_row_stride = w.zu_stride;
-    u.gate = gate;
-    u.gate_run_if = 1u;
     e = launch_skinny_mfma(u, stream);
     if (e != hipSuccess) return e;
 
     hipLaunchKernelGGL(pick_kernel, dim3(mb), dim3(256), 0, stream, a.idx, k, pairs, w.pos, w.zu, w.zu_stride,
-                       a.out_f32, gate, 1u);
+                       a.out_f32);
     return hipGetLastError();
 }
 

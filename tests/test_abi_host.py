@@ -74,7 +74,7 @@ def test_subset_logits_rejects_bad_arguments(lib):
     assert call(h=None) == 1 and call(U=None) == 1 and call(idx=None) == 1 and call(out=None) == 1
     assert call(rows=0) == 2 and call(k=0) == 2 and call(V=0) == 2
     assert call(ldh=128) == 2 and call(ldu=255) == 2
-    assert call(dt=7) == 3 and call(mode=2) == 3 and call(mode=9) == 3      # 4 and 5 are the padded modes
+    assert call(dt=7) == 3 and call(mode=2) == 3 and call(mode=3) == 3 and call(mode=16) == 3   # flags: 4 padded, 8 sorted
     assert call(d=252, ldh=252, ldu=252) == 6             # row not a whole number of 16-byte units
     assert call(ldu=260) == 4                              # stride not 16-byte aligned
     assert call(h=MIS) == 4 and call(U=MIS) == 4
@@ -125,6 +125,15 @@ def test_dense_select_topk_reject_bad_arguments(lib):
     assert lib.specvocab_subset_logits(A, 20, 256, 256, A, 5000, 256, 1, A, 1000, 4, A, MIS, both, None) == 4
     assert lib.specvocab_draft_step(A, 20, 256, 256, A, 5000, 256, 1, A, 1000, 4, 10, A, A, A, None, A, 80128,
                                     None) == 5
+
+    # many rows with lists declared sorted: the slice table instead of the union scratch
+    tab = sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 512, 4096, 151936, 8192, idx_mode=sv.SV_IDX_PER_ROW | sv.SV_IDX_SORTED)
+    uni = sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 512, 4096, 151936, 8192, idx_mode=sv.SV_IDX_PER_ROW)
+    assert 512 * 594 * 4 <= tab <= 512 * 600 * 4 and uni > 512 * 151936 * 4
+    assert lib.specvocab_subset_logits(A, 512, 256, 256, A, 151936, 256, 1, A, 8192, 8, A, A, tab - 1, None) == 5
+    # the declaration changes nothing where the general path is the better one anyway
+    assert sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 60, 4096, 128256, 4096, idx_mode=sv.SV_IDX_SORTED) == \
+        sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 60, 4096, 128256, 4096)
 
     q = lib.specvocab_aux_log_softmax
     assert q(A, 1, 256, 256, A, 32, A, 1000, 1, None, A, 1 << 30, None) == 1

@@ -126,14 +126,14 @@ def test_strided_rows(rows, d, V, k):
     (512, 256, 9000, 4000, "sorted"),        # 256 x 256 tiles
     (512, 64, 2000, 10, "sorted"),           # sparse lists: most item tiles ask for nothing from a row
     (200, 256, 4000, 1500, "repeats"),       # sorted with repeated ids
-    (130, 256, 4000, 1500, "one_descent"),   # one list out of order: the whole call takes the general path
     (256, 128, 1000, 1000, "clustered"),     # every id of a row inside one item tile
+    (100, 256, 30000, 100, "sorted"),        # too few pairs for the vocabulary: the declaration changes nothing
 ])
 def test_subset_logits_many_rows_sorted_lists(rows, d, V, k, kind):
-    """More than 64 hidden rows with their own SORTED lists that together cover the vocabulary: the product over
-    all of U whose epilogue stores only the asked entries; one descent anywhere sends the call down the general
-    path instead.  Element by element against the oracle either way."""
-    say(f"many rows, own lists ({kind}) rows={rows} d={d} V={V} k={k}")
+    """More than 64 hidden rows with their own lists, declared SORTED, that together cover the vocabulary: the
+    product over all of U whose epilogue stores only the asked entries.  Element by element against the oracle
+    and bit for bit against the same call without the declaration (the general path; same matrix-core kernel)."""
+    say(f"many rows, own sorted lists ({kind}) rows={rows} d={d} V={V} k={k}")
     rng = np.random.default_rng(rows + V + k)
     U, h = rand(rng, (V, d), 0.02, "bf16"), rand(rng, (rows, d), 1.0, "bf16")
     if kind == "repeats":
@@ -143,16 +143,40 @@ def test_subset_logits_many_rows_sorted_lists(rows, d, V, k, kind):
         idx = np.sort(base + rng.integers(0, 100, (rows, k)), axis=1).astype(np.int32)
     else:
         idx = np.stack([np.sort(rng.permutation(V)[:k]) for _ in range(rows)]).astype(np.int32)
-    if kind == "one_descent":
-        idx[rows // 2, [5, 6]] = idx[rows // 2, [6, 5]]
     tU, th, tidx = to_dev(U), to_dev(h), torch.from_numpy(idx).to(DEV)
-    z = sv.subset_logits(th, tU, tidx).cpu().numpy()
+    z = sv.subset_logits(th, tU, tidx, sorted_lists=True)
+    if rows * k >= 16384:                                   # both paths then multiply on the same matrix-core kernel
+        assert torch.equal(z, sv.subset_logits(th, tU, tidx))
+    z = z.cpu().numpy()
     assert_logits_close(z, oracle.subset_logits(h, U, idx), "bf16")
-    z2, tok, prob, _ = sv.draft_step(th, tU, tidx, min(10, k))
+    z2, tok, prob, _ = sv.draft_step(th, tU, tidx, min(10, k), sorted_lists=True)
     assert np.array_equal(z2.cpu().numpy(), z)
     if kind != "repeats":                                   # draft tokens need unique ids within a row
         tok_ref, _ = oracle.softmax_topk(z, idx, min(10, k))
         assert np.array_equal(tok.cpu().numpy(), tok_ref)
+
+
+def test_debug_mode_checks_a_declared_order(monkeypatch):
+    """SPECVOCAB_VALIDATE=1: a list declared sorted that descends is reported, nothing is launched."""
+    say("debug mode: declared order")
+    rng = np.random.default_rng(81)
+    rows, d, V, k = 70, 256, 2000, 500
+    U, h = to_dev(rand(rng, (V, d), 0.02, "bf16")), to_dev(rand(rng, (rows, d), 1.0, "bf16"))
+    idx = np.stack([np.sort(rng.permutation(V)[:k]) for _ in range(rows)]).astype(np.int32)
+    good = torch.from_numpy(idx).to(DEV)
+    idx[33, [5, 6]] = idx[33, [6, 5]]
+    bad = torch.from_numpy(idx).to(DEV)
+    monkeypatch.setenv("SPECVOCAB_VALIDATE", "1")
+    out = torch.full((rows, k), 7.0, dtype=torch.float32, device=DEV)
+    with pytest.raises(sv.SpecVocabError) as e:
+        sv.subset_logits(h, U, bad, out=out, sorted_lists=True)
+    assert e.value.status == 7
+    torch.cuda.synchronize()
+    assert bool((out == 7.0).all())
+    z = sv.subset_logits(h, U, bad)                         # without the declaration any order is fine
+    assert torch.equal(sv.subset_logits(h, U, good, sorted_lists=True), sv.subset_logits(h, U, good))
+    monkeypatch.delenv("SPECVOCAB_VALIDATE")
+    assert z.shape == (rows, k)
 
 
 def test_duplicate_and_unsorted_indices_are_just_gathered():
@@ -955,7 +979,7 @@ def test_config5_full_step_with_selection():
     say("config 5 select")
     sel, _ = sv.select(th, tWd, tWv, c.k)
     say("config 5 subset logits")
-    z = sv.subset_logits(th, tU, sel)
+    z = sv.subset_logits(th, tU, sel, sorted_lists=True)       # the selection emits ascending ids
     say("config 5 draft top-kd")
     tok, prob, _ = sv.draft_topk(z, sel, c.kd)
     torch.cuda.synchronize()
