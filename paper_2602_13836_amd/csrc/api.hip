@@ -49,6 +49,8 @@ hipError_t device_state(const DeviceState** out) {
             if (e != hipSuccess) return e;
             e = configure_tile_mfma_lds();
             if (e != hipSuccess) return e;
+            e = configure_select_lds();
+            if (e != hipSuccess) return e;
             void* p = nullptr;
             e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
             if (e != hipSuccess) return e;

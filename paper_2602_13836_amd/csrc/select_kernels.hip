@@ -776,7 +776,7 @@ struct BracketLayout {
     int64_t m;           // sample size
     int64_t nb;          // 4096-id vocabulary blocks (the redo path)
     // offsets in uint32 words from the scratch base (all multiples of 4: 16-byte aligned)
-    size_t ids, samp, thr, flag, bits, cnt, sure, boff, state, cand, total;
+    size_t ids, samp, thr, flag, bits, cnt, sure, boff, state, first, cand, total;
 };
 __host__ __device__ inline size_t quad4(size_t n) { return (n + 3) & ~(size_t)3; }
 __host__ __device__ inline BracketLayout bracket_layout(int64_t V, int rows, int tn, int64_t m) {
@@ -798,6 +798,7 @@ __host__ __device__ inline BracketLayout bracket_layout(int64_t V, int rows, int
     L.sure = o;   o += quad4((size_t)rows * L.nb);
     L.boff = o;   o += quad4((size_t)rows * L.nb);
     L.state = o;  o += (size_t)rows * 8;
+    L.first = o;  o += (size_t)rows * L.tiles * kCandFirst * 2;
     L.cand = o;   o += (size_t)rows * L.tiles * tn * 2;
     L.total = o;
     return L;
@@ -985,10 +986,19 @@ __device__ __forceinline__ void redo_row(const char* hp_row, const char* Wv, int
 
 // One workgroup of 256 threads per row (small workgroups: several rows per CU overlap their memory round trips
 // and barriers are cheap): see the overview above.  The row's bit mask lives in LDS from the first step to
-// the last, so the selected candidates join it there and the ids are written straight from it.
+// the last, so the selected candidates join it there and the ids are written from it.
+// Dynamic LDS: [words] bit mask | [cand_cap] candidates (8 bytes each).
+// A row with at most cand_cap candidates packs them into LDS once and every later walk reads that dense list
+// (a few balanced iterations per thread); a row with more (ties by the thousand) walks the registers and the
+// memory regions instead.
 constexpr int kRbTiles = 4;                              // item tiles per thread whose candidates are held in registers
-constexpr int kRbSpec = 8;                               // ... candidates per such tile; the rest are re-read per pass
+constexpr int kRbSpec = kCandFirst;                      // ... candidates per such tile: the compact array (mean 8, 99th
+                                                         // percentile 16 at the usual shapes); the rest are re-read
 constexpr int kRbBins = 2048;
+constexpr int kRbBitBatch = 24;                          // words of the bit mask per thread requested at once
+// dynamic LDS of a resolve workgroup: with its 9 KB of static LDS two of them share a CU's 160 KB (a launch
+// of 512 rows is then one round of workgroups on 256 CUs)
+constexpr size_t kResolveLdsBytes = 69 * 1024;
 struct ResolveEmitSmem {
     uint32_t hist[kRbBins];
     uint32_t w[kRbWaves];
@@ -999,73 +1009,83 @@ struct ResolveEmitSmem {
 };
 
 __global__ __launch_bounds__(kRbThreads) void resolve_emit_kernel(int64_t V, int rows, int tn, int64_t m, int64_t k,
-                                                                  uint32_t* scratch, int32_t* idx_out) {
-    extern __shared__ __attribute__((aligned(16))) uint32_t s_bits[];         // [words]
+                                                                  uint32_t* scratch, int32_t* idx_out,
+                                                                  uint32_t cand_cap) {
+    extern __shared__ __attribute__((aligned(16))) uint32_t s_bits[];         // [words], then the candidate list
     __shared__ ResolveEmitSmem sm;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int64_t r = blockIdx.x;
     const BracketLayout L = bracket_layout(V, rows, tn, m);
+    uint64_t* s_cand = reinterpret_cast<uint64_t*>(s_bits + L.words);         // words is a multiple of 4
     const uint32_t* bits = scratch + L.bits + (size_t)r * L.words;
     const uint32_t* cnt = scratch + L.cnt + (size_t)r * L.tiles;
     const uint64_t* cand = reinterpret_cast<const uint64_t*>(scratch + L.cand) + (size_t)r * L.tiles * tn;
-    // everything independent is requested up front: the bracket, the candidate counts of this thread's tiles
-    // and the first candidates of each (before their count is known)
+    const uint64_t* first = reinterpret_cast<const uint64_t*>(scratch + L.first) + (size_t)r * L.tiles * kCandFirst;
+    // everything independent is requested up front, in the order of use: the bracket, the candidate counts of
+    // this thread's tiles, the first words of the bit mask, the first candidates of each tile (before their
+    // count is known)
     const float hi = reinterpret_cast<const float*>(scratch + L.thr)[2 * r];
     const float lo = reinterpret_cast<const float*>(scratch + L.thr)[2 * r + 1];
     uint32_t tc[kRbTiles];
-    uint64_t reg[kRbTiles][kRbSpec];
 #pragma unroll
     for (int j = 0; j < kRbTiles; ++j) {
         const int64_t t = tid + (int64_t)j * kRbThreads;
         tc[j] = t < L.tiles ? cnt[t] : 0u;
-        const uint64_t* p = cand + (t < L.tiles ? t : 0) * (int64_t)tn;
+    }
+    uint32_t wv[kRbBitBatch];
 #pragma unroll
-        for (int i = 0; i < kRbSpec; ++i) reg[j][i] = p[i];                   // a region has tn >= 128 entries
+    for (int u = 0; u < kRbBitBatch; ++u) {
+        const int64_t w = (int64_t)u * kRbThreads + tid;
+        wv[u] = bits[w < L.words ? w : L.words - 1];
+    }
+    uint64_t reg[kRbTiles][kRbSpec];
+#pragma unroll
+    for (int j = 0; j < kRbTiles; ++j) {
+        const int64_t t = tid + (int64_t)j * kRbThreads;
+        const uint64_t* p = first + (t < L.tiles ? t : 0) * (int64_t)kCandFirst;
+#pragma unroll
+        for (int i = 0; i < kRbSpec; ++i) reg[j][i] = p[i];
     }
     if (tid == 0) sm.nfew = 0u;
-    // the row's bits above hi: into LDS, counted on the way (eight loads in flight per thread)
+    // the row's bits above hi: into LDS, counted on the way
     uint32_t mine = 0u;
-    constexpr int kBatch = 8;
-    for (int64_t w0 = 0; w0 < L.words; w0 += (int64_t)kBatch * kRbThreads) {
-        uint32_t wv[kBatch];
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            const int64_t w = w0 + (int64_t)u * kRbThreads + tid;
-            wv[u] = bits[w < L.words ? w : L.words - 1];
-        }
-#pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            const int64_t w = w0 + (int64_t)u * kRbThreads + tid;
-            if (w < L.words) {
-                s_bits[w] = wv[u];
-                mine += (uint32_t)__popc(wv[u]);
-            }
+    for (int u = 0; u < kRbBitBatch; ++u) {
+        const int64_t w = (int64_t)u * kRbThreads + tid;
+        if (w < L.words) {
+            s_bits[w] = wv[u];
+            mine += (uint32_t)__popc(wv[u]);
         }
     }
-    uint32_t band = 0u;
+    for (int64_t w = (int64_t)kRbBitBatch * kRbThreads + tid; w < L.words; w += kRbThreads) {   // very large V
+        const uint32_t x = bits[w];
+        s_bits[w] = x;
+        mine += (uint32_t)__popc(x);
+    }
+    uint32_t band_mine = 0u;
 #pragma unroll
-    for (int j = 0; j < kRbTiles; ++j) band += tc[j];
-    for (int64_t t = tid + (int64_t)kRbTiles * kRbThreads; t < L.tiles; t += kRbThreads) band += cnt[t];
+    for (int j = 0; j < kRbTiles; ++j) band_mine += tc[j];
+    for (int64_t t = tid + (int64_t)kRbTiles * kRbThreads; t < L.tiles; t += kRbThreads) band_mine += cnt[t];
     mine = wave_sum_u32(mine);
-    band = wave_sum_u32(band);
-    if (lane == 0) {
-        sm.w[wave] = mine;
-        sm.tot[wave] = band;
-    }
+    const uint32_t band_incl = wave_prefix_inclusive_u32(band_mine);
+    if (lane == 0) sm.w[wave] = mine;
+    if (lane == 63) sm.tot[wave] = band_incl;
     __syncthreads();
-    uint32_t n_above = 0u, n_band = 0u;
+    uint32_t n_above = 0u, n_band = 0u, band_before = 0u;
 #pragma unroll
     for (int w = 0; w < kRbWaves; ++w) {
         n_above += sm.w[w];
         n_band += sm.tot[w];
+        band_before += w < wave ? sm.tot[w] : 0u;
     }
     const bool miss = n_above > (uint32_t)k || (uint32_t)k - n_above > n_band;
     if (tid == 0) scratch[L.flag + r] = miss ? 1u : 0u;
     if (miss) return;                                         // uniform: the redo launch handles this row
     uint32_t remain = (uint32_t)k - n_above;                  // candidates to select, 0 <= remain <= n_band
 
-    auto for_each_candidate = [&](auto&& f) {
+    // candidates of this thread's tiles, from the registers and (crowded or far tiles) from memory
+    auto for_each_own = [&](auto&& f) {
 #pragma unroll
         for (int j = 0; j < kRbTiles; ++j) {
 #pragma unroll
@@ -1078,8 +1098,22 @@ __global__ __launch_bounds__(kRbThreads) void resolve_emit_kernel(int64_t V, int
         }
         for (int64_t t = tid + (int64_t)kRbTiles * kRbThreads; t < L.tiles; t += kRbThreads) {   // very large V
             const uint32_t n = cnt[t];
+            const uint64_t* p0 = first + t * kCandFirst;
             const uint64_t* p = cand + t * tn;
-            for (uint32_t i = 0; i < n; ++i) f(p[i]);
+            for (uint32_t i = 0; i < n; ++i) f(i < (uint32_t)kCandFirst ? p0[i] : p[i]);
+        }
+    };
+    const bool dense = remain > 0u && n_band <= cand_cap;     // uniform
+    if (dense) {
+        uint32_t pos = band_before + band_incl - band_mine;
+        for_each_own([&](uint64_t x) { s_cand[pos++] = x; });
+        __syncthreads();
+    }
+    auto for_each_candidate = [&](auto&& f) {
+        if (dense) {
+            for (uint32_t i = tid; i < n_band; i += kRbThreads) f(s_cand[i]);
+        } else {
+            for_each_own(f);
         }
     };
     if (remain > 0u) {                                        // uniform
@@ -1172,9 +1206,11 @@ __global__ __launch_bounds__(kRbThreads) void resolve_emit_kernel(int64_t V, int
             });
         }
     }
-    __syncthreads();
+    __syncthreads();                                          // the mask is final
     // ids of the set bits, ascending: wavefront w owns the word pairs [w * ppw, w * ppw + ppw) and walks them 64 at
-    // a time with a running output position (no workgroup barrier inside the walk)
+    // a time with a running output position (no workgroup barrier inside the walk).  The ids go straight to
+    // memory: gathering them in LDS first and writing whole lines afterwards was measured slower -- all rows
+    // reach that point together, and the stores of the walk overlap its arithmetic instead
     const uint64_t* s_pairs = reinterpret_cast<const uint64_t*>(s_bits);      // words is a multiple of 4
     const int64_t pairs = L.words / 2;
     const int64_t ppw = (pairs + kRbWaves - 1) / kRbWaves;
@@ -1253,6 +1289,13 @@ __global__ __launch_bounds__(kSelThreads) void redo_bracket_kernel(int64_t V, in
 
 bool scores_supported(int chunks) { return chunks >= 1 && chunks <= 64; }
 
+// more than 64 KiB of dynamic LDS needs an explicit opt-in per kernel and device (called once per device,
+// outside any stream capture, by the library's device set-up)
+hipError_t configure_select_lds() {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&resolve_emit_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kResolveLdsBytes);
+}
+
 int64_t select_max_vocab() { return (int64_t)kSelThreads * kMaxBlocksPerRow * kEpt; }
 
 size_t select_scratch_words(int64_t rows, int64_t V) {
@@ -1311,13 +1354,20 @@ hipError_t launch_bracket_select(const BracketArgs& a, hipStream_t stream) {
     ep.thr = thr;
     ep.bits = a.scratch + L.bits;
     ep.words_per_row = L.words;
+    ep.cand_first = reinterpret_cast<uint64_t*>(a.scratch + L.first);
     ep.cand = reinterpret_cast<uint64_t*>(a.scratch + L.cand);
     ep.cnt = a.scratch + L.cnt;
     ep.item_tiles = L.tiles;
     hipError_t e = launch_tile_mfma_bracket(g, ep, stream);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(resolve_emit_kernel, dim3((unsigned)a.rows), dim3(kRbThreads), (size_t)L.words * 4, stream, a.V,
-                       a.rows, tn, L.m, a.k, a.scratch, a.idx_out);
+    // LDS of a resolve workgroup: the bit mask, then as many candidate slots as keep two workgroups on a CU
+    const size_t bits_bytes = (size_t)L.words * 4;
+    const size_t room = kResolveLdsBytes > bits_bytes ? kResolveLdsBytes - bits_bytes : 0;
+    uint32_t cand_cap = (uint32_t)(room / 8);
+    if (cand_cap < 1024u) cand_cap = 0u;                      // not worth a packing pass
+    const size_t lds = bits_bytes + (size_t)cand_cap * 8;
+    hipLaunchKernelGGL(resolve_emit_kernel, dim3((unsigned)a.rows), dim3(kRbThreads), lds, stream, a.V, a.rows, tn, L.m,
+                       a.k, a.scratch, a.idx_out, cand_cap);
     hipLaunchKernelGGL(redo_bracket_kernel<DT_BF16>, dim3((unsigned)(a.rows < kRedoBlocks ? a.rows : kRedoBlocks)),
                        dim3(kSelThreads), 0, stream, a.V, a.rows, tn, L.m, a.k, a.scratch, a.idx_out, a.hp, a.Wv, a.chunks);
     return hipGetLastError();

@@ -18,6 +18,7 @@ hipError_t device_info(DeviceInfo* out);
 // opt-in of the kernel instances that need more than 64 KiB of LDS, on the current device
 hipError_t configure_skinny_mfma_lds();
 hipError_t configure_tile_mfma_lds();
+hipError_t configure_select_lds();
 
 // out[r, j] = < M[row(r, j), :], x[r, :] >  for j in [0, n_items)
 //   row(r, j) = j                       if idx == nullptr   (dense)
@@ -84,11 +85,15 @@ hipError_t launch_tile_mfma(const GemvArgs& a, hipStream_t stream, bool small_ti
 // (thr[r] = {hi, lo}):  f > hi -> bit j of the row's bit mask;  lo <= f <= hi -> (key, id) appended to the
 // candidate region of (r, item tile), whose entry count goes to cnt.  Every word of bits and every cnt entry
 // is written.  Any row count >= 1.
+// Candidates of a (row, item tile): the first kCandFirst in a compact array (a row's are contiguous: the
+// resolve pass streams them), any further ones (tied scores) in the tile-sized region of the pair.
+constexpr int kCandFirst = 16;
 struct BracketEpi {
     const float* thr;        // [rows][2]
     uint32_t* bits;          // [rows][words_per_row], words_per_row = item_tiles * tile_items / 32
     int64_t words_per_row;
-    uint64_t* cand;          // [rows][item_tiles][tile_items]   ((ordered key << 32) | ~id)
+    uint64_t* cand_first;    // [rows][item_tiles][kCandFirst]   ((ordered key << 32) | ~id)
+    uint64_t* cand;          // [rows][item_tiles][tile_items]   slots kCandFirst .. of the same list
     uint32_t* cnt;           // [rows][item_tiles]
     int64_t item_tiles;
 };

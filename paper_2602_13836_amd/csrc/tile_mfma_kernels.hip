@@ -376,6 +376,8 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
         // arithmetic below: 64-bit multiplications per candidate cost more than everything else there)
         uint64_t* cand_tile = ep.cand + ((int64_t)rt * TM * ep.item_tiles + it) * TN;
         const uint32_t row_stride = (uint32_t)(ep.item_tiles * TN);          // < 2^24 (the vocabulary, padded)
+        uint64_t* first_tile = ep.cand_first + ((int64_t)rt * TM * ep.item_tiles + it) * kCandFirst;
+        const uint32_t first_stride = (uint32_t)(ep.item_tiles * kCandFirst);
         static_for<0, WM>([&](auto mc) {
             constexpr int m = decltype(mc)::value;
             constexpr int kHalfRows = 4;                   // lanes 32..63 hold the row four below
@@ -432,8 +434,10 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
                 for (int u = 0; u < kPer; ++u) {
                     if (has[u]) {
                         const uint32_t item = (uint32_t)item0 + 32u * (uint32_t)(q[u] % WN);
-                        cand_tile[__umul24((uint32_t)row_t[u], row_stride) + slot[u]] =
-                            ((uint64_t)f32_to_ord(f[u]) << 32) | (uint32_t)(~item);
+                        uint64_t* dst = slot[u] < (uint32_t)kCandFirst
+                                            ? first_tile + (__umul24((uint32_t)row_t[u], first_stride) + slot[u])
+                                            : cand_tile + (__umul24((uint32_t)row_t[u], row_stride) + slot[u]);
+                        *dst = ((uint64_t)f32_to_ord(f[u]) << 32) | (uint32_t)(~item);
                     }
                 }
             }
