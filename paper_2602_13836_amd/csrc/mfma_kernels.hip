@@ -362,6 +362,12 @@ bool ksplit_rows_supported(int dt, const GemvArgs& a) {
 }
 
 hipError_t launch_ksplit_rows(const GemvArgs& a, hipStream_t stream) {
+    DeviceInfo di;
+    const hipError_t e = device_info(&di);
+    if (e != hipSuccess) return e;
+    // few workgroups: 16 hidden rows each (twice as many workgroups, each pulling a third less through its CU)
+    const int64_t tiles = (a.n_items + 15) / 16;
+    if (tiles * ((a.rows + 31) / 32) * 4 <= di.cus) return launch_ksplit<1>(a, 0, (a.rows + 15) / 16, stream);
     return launch_ksplit<2>(a, 0, (a.rows + 31) / 32, stream);
 }
 
