@@ -376,6 +376,7 @@ def main():
 
     def capture(fn, n):
         g = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()            # inputs are made on the default stream; the calls below run on another
         with torch.cuda.stream(stream):
             fn(0)                           # eager once: loads code objects before capture
             torch.cuda.synchronize()

@@ -405,6 +405,7 @@ def test_whole_step_replays_from_a_graph(rows, d, dp, V, k):
 
     stream = torch.cuda.Stream()
     g = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()                               # the inputs were made on the default stream
     with torch.cuda.stream(stream):
         run()
         torch.cuda.synchronize()
