@@ -107,19 +107,22 @@ __global__ __launch_bounds__(256) void pick_kernel(const int32_t* idx, int64_t k
 // for every tile that starts after its predecessor and not after itself; the last entry also closes the row.
 // A list that is not sorted (the caller's contract) leaves entries of the table unwritten or inconsistent; the
 // product's epilogue clamps what it reads from it, so the result is then wrong but every access stays in bounds.
-__global__ __launch_bounds__(256) void slice_table_kernel(const int32_t* idx, int64_t k, int tile_items, int64_t tiles,
+// (tile_items is a power of two, 1 << tile_shift: tile numbers by 32-bit shifts -- 64-bit divisions per entry
+// made this kernel several times slower than reading the lists takes)
+__global__ __launch_bounds__(256) void slice_table_kernel(const int32_t* idx, int64_t k, int tile_shift, int64_t tiles,
                                                           uint32_t* off) {
     const int64_t r = blockIdx.y;
     const int32_t* list = idx + r * k;
     uint32_t* o = off + r * (tiles + 1);
+    const int last_tile = (int)tiles - 1;
     for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < k; j += (int64_t)gridDim.x * blockDim.x) {
         const int32_t v = list[j];
         const int32_t prev = j > 0 ? list[j - 1] : 0;
-        const int64_t t_first = j > 0 ? (int64_t)prev / tile_items + 1 : 0;   // tiles that start after the predecessor
-        int64_t t_last = v >= 0 ? (int64_t)v / tile_items : -1;
-        if (prev < 0 || t_first < 0) continue;                // (negative ids: outside the contract)
-        if (t_last > tiles - 1) t_last = tiles - 1;           // (an id past the vocabulary: the caller's contract)
-        for (int64_t t = t_first; t <= t_last; ++t) o[t] = (uint32_t)j;
+        if (prev < 0) continue;                               // (negative ids: outside the contract)
+        const int t_first = j > 0 ? (prev >> tile_shift) + 1 : 0;             // tiles that start after the predecessor
+        int t_last = v >= 0 ? v >> tile_shift : -1;
+        if (t_last > last_tile) t_last = last_tile;           // (an id past the vocabulary: the caller's contract)
+        for (int t = t_first; t <= t_last; ++t) o[t] = (uint32_t)j;
         if (j == k - 1)
             for (int64_t t = (t_last < 0 ? 0 : t_last + 1); t <= tiles; ++t) o[t] = (uint32_t)k;
     }
@@ -157,7 +160,11 @@ hipError_t launch_sorted_pick_logits(const GemvArgs& a, int64_t V, void* ws, hip
     const int64_t tiles = (V + tn - 1) / tn;
     uint32_t* table = static_cast<uint32_t*>(ws);
     const unsigned sb = (unsigned)((k + 1023) / 1024);
-    hipLaunchKernelGGL(slice_table_kernel, dim3(sb, (unsigned)a.rows), dim3(256), 0, stream, a.idx, k, tn, tiles, table);
+    int tile_shift = 0;
+    while ((1 << tile_shift) < tn) ++tile_shift;
+    if ((1 << tile_shift) != tn) return hipErrorInvalidValue;      // tiles are 128 or 256 items
+    hipLaunchKernelGGL(slice_table_kernel, dim3(sb, (unsigned)a.rows), dim3(256), 0, stream, a.idx, k, tile_shift, tiles,
+                       table);
     GemvArgs dense = a;
     dense.idx = nullptr;
     dense.idx_row_stride = 0;
