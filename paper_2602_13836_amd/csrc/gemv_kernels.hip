@@ -203,11 +203,12 @@ __global__ __launch_bounds__(256) void pad_clean_kernel(const int32_t* idx, int6
 }
 // ... and -inf for the logits of the padding slots afterwards
 __global__ __launch_bounds__(256) void pad_mask_kernel(const int32_t* idx, int64_t idx_row_stride, int64_t k,
-                                                       int64_t pairs, float* logits) {
-    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < pairs; p += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t r = p / k, j = p - r * k;
-        if (idx[r * idx_row_stride + j] < 0) logits[p] = -INFINITY;
-    }
+                                                       float* logits) {
+    const int64_t r = blockIdx.y;                         // (no division of a pair number by k per entry)
+    const int32_t* list = idx + r * idx_row_stride;
+    float* z = logits + r * k;
+    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < k; j += (int64_t)gridDim.x * blockDim.x)
+        if (list[j] < 0) z[j] = -INFINITY;
 }
 
 // dst[j, :] = M[idx[j], :]: one wavefront per row, 16 bytes per lane and step
@@ -305,11 +306,10 @@ hipError_t launch_pad_clean(const int32_t* idx, int64_t n, int32_t* clean, hipSt
 
 hipError_t launch_pad_mask(const int32_t* idx, int64_t idx_row_stride, int rows, int64_t k, float* logits,
                            hipStream_t stream) {
-    const int64_t pairs = (int64_t)rows * k;
-    int64_t bx = (pairs + 1023) / 1024;
-    if (bx > 2048) bx = 2048;
+    int64_t bx = (k + 1023) / 1024;
+    if (bx * rows > 4096) bx = (4096 + rows - 1) / rows;
     if (bx < 1) bx = 1;
-    hipLaunchKernelGGL(pad_mask_kernel, dim3((unsigned)bx), dim3(256), 0, stream, idx, idx_row_stride, k, pairs,
+    hipLaunchKernelGGL(pad_mask_kernel, dim3((unsigned)bx, (unsigned)rows), dim3(256), 0, stream, idx, idx_row_stride, k,
                        logits);
     return hipGetLastError();
 }

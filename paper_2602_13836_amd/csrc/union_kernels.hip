@@ -95,12 +95,15 @@ __global__ __launch_bounds__(kUThreads) void compact_kernel(uint32_t* pos, int64
     }
 }
 
-__global__ __launch_bounds__(256) void pick_kernel(const int32_t* idx, int64_t k, int64_t pairs, const uint32_t* pos,
-                                                   const float* zu, int64_t zu_stride, float* out) {
-    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < pairs; p += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t r = p / k;
-        out[p] = zu[r * zu_stride + pos[idx[p]]];
-    }
+// (hidden rows ride on gridDim.y: a division of the pair number by k per entry costs more than the entry's loads)
+__global__ __launch_bounds__(256) void pick_kernel(const int32_t* idx, int64_t k, const uint32_t* pos, const float* zu,
+                                                   int64_t zu_stride, float* out) {
+    const int64_t r = blockIdx.y;
+    const int32_t* list = idx + r * k;
+    const float* z = zu + r * zu_stride;
+    float* o = out + r * k;
+    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < k; j += (int64_t)gridDim.x * blockDim.x)
+        o[j] = z[pos[list[j]]];
 }
 
 // off[r, t] for t = 0 .. tiles (see the overview), one thread per list entry: the entry at j fills the table
@@ -212,7 +215,9 @@ hipError_t launch_union_logits(const GemvArgs& a, int64_t V, void* ws, hipStream
     e = launch_skinny_mfma(u, stream);
     if (e != hipSuccess) return e;
 
-    hipLaunchKernelGGL(pick_kernel, dim3(mb), dim3(256), 0, stream, a.idx, k, pairs, w.pos, w.zu, w.zu_stride,
+    unsigned pb = (unsigned)((k + 1023) / 1024);              // four entries per thread
+    if ((int64_t)pb * a.rows > (int64_t)di.cus * 16) pb = (unsigned)(((int64_t)di.cus * 16 + a.rows - 1) / a.rows);
+    hipLaunchKernelGGL(pick_kernel, dim3(pb, (unsigned)a.rows), dim3(256), 0, stream, a.idx, k, w.pos, w.zu, w.zu_stride,
                        a.out_f32);
     return hipGetLastError();
 }
