@@ -106,8 +106,8 @@ __global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(SV_HOT_PARAMS, co
             *reinterpret_cast<u32x4*>(base + (size_t)r * kXRowBytes + u * 16) = v;
         }
     };
-    auto store_x = [&](int slice, const u32x4 (&src)[kXPer]) {     // slice -> buffer slice % 2; zeros past the row
-        unsigned char* base = smem + (size_t)(slice & 1) * N * kXRowBytes;
+    auto store_x = [&](int slice, int buf, const u32x4 (&src)[kXPer]) {     // slice -> buffer buf; zeros past the row
+        unsigned char* base = smem + (size_t)buf * N * kXRowBytes;
 #pragma unroll
         for (int q = 0; q < kXPer; ++q) {
             const int p = q * kThreads + tid;
@@ -121,18 +121,25 @@ __global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(SV_HOT_PARAMS, co
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
+    // Workgroups walk the reduction in rotated order: rows of M a power of two apart put the same offset of
+    // every row on the same L2 channels, and workgroups that all start at offset 0 keep hitting the same few
+    // channels together.  Consecutive workgroups of one XCD (every eighth workgroup) start one slice apart.
+    // (Not for the product over a union of sets, whose list order varies from run to run: the order of the
+    // float32 additions of a token would vary with its place in the list.)
+    const int rot = a.n_items_dev ? 0 : (int)((blockIdx.x / 8) % (unsigned)nslices);
+    auto eff = [&](int slice) { const int e = slice + rot; return e >= nslices ? e - nslices : e; };
     u32x4 cur[kSteps], nxt[kSteps];
     u32x4 xr[kXPer];
-    load_a(0, cur);
-    stage_x(0, 0);
+    load_a(eff(0), cur);
+    stage_x(eff(0), 0);
     __syncthreads();
     for (int slice = 0; slice < nslices; ++slice) {
         const int buf = slice & 1;
         const bool more = slice + 1 < nslices;
         if (more) {
-            load_a(slice + 1, nxt);
-            if constexpr (kSplit) load_x(slice + 1, xr);
-            else stage_x(slice + 1, buf ^ 1);
+            load_a(eff(slice + 1), nxt);
+            if constexpr (kSplit) load_x(eff(slice + 1), xr);
+            else stage_x(eff(slice + 1), buf ^ 1);
         }
         const unsigned char* xb = smem + (size_t)buf * N * kXRowBytes + (size_t)i * kXRowBytes + g * 16;
 #pragma unroll
@@ -146,7 +153,7 @@ __global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(SV_HOT_PARAMS, co
             }
         }
         if constexpr (kSplit)
-            if (more) store_x(slice + 1, xr);     // the other buffer: nobody reads it during this slice
+            if (more) store_x(eff(slice + 1), buf ^ 1, xr);     // the other buffer: nobody reads it during this slice
         __syncthreads();                          // everyone is done with buf; buf^1 is complete
 #pragma unroll
         for (int s = 0; s < kSteps; ++s) cur[s] = nxt[s];

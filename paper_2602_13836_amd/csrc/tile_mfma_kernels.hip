@@ -144,8 +144,16 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
     // units of a ragged last slice that lie past the row are zeroed on their way into LDS, when the
     // data has arrived anyway): without branches between them the compiler can count the loads in
     // flight and wait for exactly the oldest slice.
+    // Workgroups walk the reduction in rotated order (slice ks of the walk is slice eff(ks) of the rows): rows a
+    // power of two apart put the same offset of every row on the same L2 channels, and workgroups that all
+    // start at offset 0 keep hitting the same channels together.  Consecutive workgroups of one XCD start one
+    // slice apart.
+    // (Short reductions have nothing to spread.  The product over a union of sets keeps the plain order: its
+    // list order varies from run to run, and the order of a token's float32 additions must not.)
+    const int rot = nk >= 16 && !a.n_items_dev ? (int)(slot % nk) : 0;
+    auto eff = [&](int ks) { const int e = min(ks, nk - 1) + rot; return e >= nk ? e - nk : e; };
     auto load = [&](int ks, u32x4 (&ga)[QA], u32x4 (&gb)[QB]) {
-        const int u = min(min(ks, nk - 1) * 8 + piece, C - 1);
+        const int u = min(eff(ks) * 8 + piece, C - 1);
 #pragma unroll
         for (int q = 0; q < QB; ++q) gb[q] = pb[q][u];
 #pragma unroll
@@ -153,7 +161,7 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
     };
     auto store = [&](int ks, const u32x4 (&ga)[QA], const u32x4 (&gb)[QB]) {      // slice ks -> buffer ks % 2
         unsigned char* base = smem + (size_t)(ks & 1) * kStage + (size_t)r0 * kRowB + piece * 16;
-        const bool past = ks * 8 + piece >= C;
+        const bool past = ks >= nk || eff(ks) * 8 + piece >= C;
 #pragma unroll
         for (int q = 0; q < QA; ++q)
             *reinterpret_cast<u32x4*>(base + (size_t)(kRowsPerPass * q) * kRowB) = past ? zero16() : ga[q];
@@ -220,7 +228,7 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
         static_assert(QA % 4 == 0 && QB % 4 == 0, "the staged slice is copied in four parts");
         constexpr int PA = QA / 4, PB = QB / 4;
         auto load_part = [&](int j, int ks) {
-            const int u = min(min(ks, nk - 1) * 8 + piece, C - 1);
+            const int u = min(eff(ks) * 8 + piece, C - 1);
 #pragma unroll
             for (int q = 0; q < PB; ++q) gb[j * PB + q] = pb[j * PB + q][u];
 #pragma unroll
@@ -228,7 +236,7 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
         };
         auto store_part = [&](int j, int ks) {
             unsigned char* base = smem + (size_t)(ks & 1) * kStage + (size_t)r0 * kRowB + piece * 16;
-            const bool past = ks * 8 + piece >= C;
+            const bool past = ks >= nk || eff(ks) * 8 + piece >= C;
 #pragma unroll
             for (int q = 0; q < PA; ++q)
                 *reinterpret_cast<u32x4*>(base + (size_t)(kRowsPerPass * (j * PA + q)) * kRowB) = past ? zero16() : ga[j * PA + q];
