@@ -124,9 +124,9 @@ __global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(SV_HOT_PARAMS, co
     // Workgroups walk the reduction in rotated order: rows of M a power of two apart put the same offset of
     // every row on the same L2 channels, and workgroups that all start at offset 0 keep hitting the same few
     // channels together.  Consecutive workgroups of one XCD (every eighth workgroup) start one slice apart.
-    // (Not for the product over a union of sets, whose list order varies from run to run: the order of the
-    // float32 additions of a token would vary with its place in the list.)
-    const int rot = a.n_items_dev ? 0 : (int)((blockIdx.x / 8) % (unsigned)nslices);
+    // (Not when the place of an item in the list may vary from run to run, a.plain_order: the order of the
+    // float32 additions of a token would vary with it.)
+    const int rot = a.plain_order ? 0 : (int)((blockIdx.x / 8) % (unsigned)nslices);
     auto eff = [&](int slice) { const int e = slice + rot; return e >= nslices ? e - nslices : e; };
     u32x4 cur[kSteps], nxt[kSteps];
     u32x4 xr[kXPer];

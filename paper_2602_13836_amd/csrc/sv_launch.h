@@ -45,6 +45,8 @@ struct GemvArgs {
     int64_t spread_V;
     const uint32_t* n_items_dev;   // optional (matrix-core kernel only): the item count lives on the
                                    // device; n_items is then an upper bound that sizes the grid
+    int plain_order;               // matrix-core kernels: every workgroup walks the reduction from offset 0 (set when
+                                   // the place of an item in the list may differ from run to run)
 };
 // what a launch does for later kernels besides its product: every thread of the grid calls this once
 __device__ __forceinline__ void prepare_scratch(const GemvArgs& a) {

@@ -148,9 +148,9 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
     // power of two apart put the same offset of every row on the same L2 channels, and workgroups that all
     // start at offset 0 keep hitting the same channels together.  Consecutive workgroups of one XCD start one
     // slice apart.
-    // (Short reductions have nothing to spread.  The product over a union of sets keeps the plain order: its
-    // list order varies from run to run, and the order of a token's float32 additions must not.)
-    const int rot = nk >= 16 && !a.n_items_dev ? (int)(slot % nk) : 0;
+    // (Short reductions have nothing to spread.  a.plain_order: the place of an item in the list may vary from
+    // run to run, and the order of a token's float32 additions must not.)
+    const int rot = nk >= 16 && !a.plain_order ? (int)(slot % nk) : 0;
     auto eff = [&](int ks) { const int e = min(ks, nk - 1) + rot; return e >= nk ? e - nk : e; };
     auto load = [&](int ks, u32x4 (&ga)[QA], u32x4 (&gb)[QB]) {
         const int u = min(eff(ks) * 8 + piece, C - 1);

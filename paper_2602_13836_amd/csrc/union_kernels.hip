@@ -4,9 +4,14 @@
 // Gathering per (row, j) pair would read a row of U once for every hidden row that wants it; the
 // sets of one step overlap heavily (a tree's rows share most of their likely tokens), so the bytes
 // that have to move are the UNIQUE rows of U.  Per step:
-//   mark     flag[v] = 1 for every token any row asks for                       (plain stores)
-//   compact  the flagged tokens become the union list, and flag[v] becomes the token's position
-//            in it (block-local prefix sums, one atomic per workgroup to reserve a range)
+//   mark     flag[v] = 1 (a byte) for every token any row asks for              (plain stores)
+//   compact  the flagged tokens become the union list, in token order, and pos[v] the token's position
+//            in it: a workgroup counts the flags in front of its 4096 tokens itself (4 KB of flag bytes per
+//            earlier workgroup) and prefix-sums its own, so the list is the same in every run -- with ranges
+//            reserved by atomics the order of the workgroups' ranges, and with it the tile and the order of
+//            the float32 additions of a token in the product, changed from run to run.  Very large
+//            vocabularies (more than kOrderedMaxBlocks workgroups) keep the atomics and the product then
+//            keeps its plain reduction order
 //   product  every row of U in the union x all hidden rows, on the matrix cores (mfma_kernels.hip),
 //            reading each needed row of U exactly once
 //   pick     logits[r, j] = product[r, pos[idx[r, j]]]
@@ -31,13 +36,16 @@ constexpr int kUThreads = 1024;
 constexpr int kUWaves = kUThreads / 64;
 constexpr int kUEpt = 4;
 
+constexpr int64_t kOrderedMaxBlocks = 128;          // vocabularies up to 524288 tokens: union list in token order
 struct UnionWs {
     uint32_t* counter;   // [4]  number of tokens in the union (word 0)
-    uint32_t* pos;       // [V]  flag, then position in the union list
-    int32_t* ulist;      // [V]  union list (any order)
+    uint8_t* flag;       // [V]  1 = some row asks for the token
+    uint32_t* pos;       // [V]  position in the union list
+    int32_t* ulist;      // [V]  union list
     float* zu;           // [rows][zu_stride] product
     int64_t zu_stride;
 };
+__host__ __device__ inline size_t flag_words(int64_t V) { return (((size_t)V + 15) / 16) * 4; }   // 16-byte multiple
 __host__ __device__ inline int64_t union_cap(int64_t rows, int64_t V, int64_t k) {
     const int64_t pairs = rows * k;
     const int64_t cap = pairs < V ? pairs : V;
@@ -48,9 +56,10 @@ inline UnionWs carve(void* ws, int64_t rows, int64_t V, int64_t k) {
     uint32_t* base = static_cast<uint32_t*>(ws);
     const size_t vpad = ((size_t)V + 3) & ~(size_t)3;
     w.counter = base;
-    w.pos = base + 4;
-    w.ulist = reinterpret_cast<int32_t*>(base + 4 + vpad);
-    w.zu = reinterpret_cast<float*>(base + 4 + 2 * vpad);
+    w.flag = reinterpret_cast<uint8_t*>(base + 4);
+    w.pos = base + 4 + flag_words(V);
+    w.ulist = reinterpret_cast<int32_t*>(base + 4 + flag_words(V) + vpad);
+    w.zu = reinterpret_cast<float*>(base + 4 + flag_words(V) + 2 * vpad);
     w.zu_stride = union_cap(rows, V, k);
     return w;
 }
@@ -60,31 +69,65 @@ __global__ __launch_bounds__(256) void clear_kernel(uint32_t* p, size_t n) {
         p[i] = 0u;
 }
 
-__global__ __launch_bounds__(256) void mark_kernel(const int32_t* idx, int64_t pairs, uint32_t* flag) {
+__global__ __launch_bounds__(256) void mark_kernel(const int32_t* idx, int64_t pairs, uint8_t* flag) {
     for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < pairs; p += (int64_t)gridDim.x * blockDim.x)
-        flag[idx[p]] = 1u;
+        flag[idx[p]] = 1;
 }
 
-__global__ __launch_bounds__(kUThreads) void compact_kernel(uint32_t* pos, int64_t V, int32_t* ulist,
-                                                            uint32_t* counter) {
+// ORDERED: the workgroup's first slot is the number of flags in front of its tokens, counted here (the flag
+// bytes are 0 or 1, so a word's population count is its number of flags); the last workgroup leaves the size
+// of the union in counter[0].  Otherwise: a range reserved with one atomic per workgroup, in any order.
+template <bool ORDERED>
+__global__ __launch_bounds__(kUThreads) void compact_kernel(const uint8_t* flag, uint32_t* pos, int64_t V,
+                                                            int32_t* ulist, uint32_t* counter) {
     __shared__ uint32_t s_w[kUWaves];
+    __shared__ uint32_t s_w2[kUWaves];
     __shared__ uint32_t s_base;
     const int tid = threadIdx.x;
     const int64_t v0 = ((int64_t)blockIdx.x * kUThreads + tid) * kUEpt;
+    static_assert(kUEpt == 4, "a thread's four flags are one 32-bit word");
+    const uint32_t* flag_w = reinterpret_cast<const uint32_t*>(flag);         // the array is a multiple of 16 bytes long
+    const uint32_t own = v0 < V ? flag_w[v0 / 4] : 0u;                        // (bytes past V are never set)
+    uint32_t before_me = 0u;
+    if constexpr (ORDERED) {
+        // words of the earlier workgroups: kUThreads per workgroup, this thread takes one of each, eight at a time
+        const int nb = (int)blockIdx.x;
+        for (int b0 = 0; b0 < nb; b0 += 8) {
+            uint32_t w[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) w[u] = flag_w[(int64_t)(b0 + u < nb ? b0 + u : nb - 1) * kUThreads + tid];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) before_me += b0 + u < nb ? (uint32_t)__popc(w[u]) : 0u;
+        }
+    }
     uint32_t f[kUEpt];
     uint32_t mine = 0;
 #pragma unroll
     for (int i = 0; i < kUEpt; ++i) {
-        f[i] = (v0 + i < V) ? pos[v0 + i] : 0u;
+        f[i] = (v0 + i < V) ? (own >> (8 * i)) & 1u : 0u;
         mine += f[i];
     }
     const uint32_t before = block_prefix_exclusive<kUWaves>(mine, s_w);
+    if constexpr (ORDERED) {
+        before_me = wave_sum_u32(before_me);
+        if ((tid & 63) == 0) s_w2[tid >> 6] = before_me;
+    }
     if (tid == kUThreads - 1) {
         const uint32_t total = before + mine;
-        s_base = total ? atomicAdd(counter, total) : 0u;
+        if constexpr (!ORDERED) s_base = total ? atomicAdd(counter, total) : 0u;
+        else s_base = total;                                   // (the last thread's inclusive sum: the workgroup's count)
     }
     __syncthreads();
-    uint32_t slot = s_base + before;
+    uint32_t slot;
+    if constexpr (ORDERED) {
+        uint32_t base = 0u;
+#pragma unroll
+        for (int w = 0; w < kUWaves; ++w) base += s_w2[w];
+        if (blockIdx.x == gridDim.x - 1 && tid == 0) counter[0] = base + s_base;
+        slot = base + before;
+    } else {
+        slot = s_base + before;
+    }
 #pragma unroll
     for (int i = 0; i < kUEpt; ++i) {
         if (f[i]) {
@@ -184,7 +227,7 @@ hipError_t launch_sorted_pick_logits(const GemvArgs& a, int64_t V, void* ws, hip
 
 size_t union_ws_bytes(int64_t rows, int64_t V, int64_t k) {
     const size_t vpad = ((size_t)V + 3) & ~(size_t)3;
-    return (4 + 2 * vpad + (size_t)rows * (size_t)union_cap(rows, V, k)) * sizeof(uint32_t);
+    return (4 + flag_words(V) + 2 * vpad + (size_t)rows * (size_t)union_cap(rows, V, k)) * sizeof(uint32_t);
 }
 
 hipError_t launch_union_logits(const GemvArgs& a, int64_t V, void* ws, hipStream_t stream) {
@@ -195,21 +238,28 @@ hipError_t launch_union_logits(const GemvArgs& a, int64_t V, void* ws, hipStream
     const int64_t pairs = (int64_t)a.rows * k;
     const UnionWs w = carve(ws, a.rows, V, k);
 
-    const size_t nclear = 4 + (size_t)V;                  // counter + flags (contiguous)
+    const size_t nclear = 4 + flag_words(V);              // counter + flag bytes (contiguous)
     unsigned cb = (unsigned)((nclear + 1023) / 1024);
     if (cb > (unsigned)di.cus * 4) cb = (unsigned)di.cus * 4;
     hipLaunchKernelGGL(clear_kernel, dim3(cb), dim3(256), 0, stream, w.counter, nclear);
     unsigned mb = (unsigned)((pairs + 1023) / 1024);
     if (mb > (unsigned)di.cus * 8) mb = (unsigned)di.cus * 8;
-    hipLaunchKernelGGL(mark_kernel, dim3(mb), dim3(256), 0, stream, a.idx, pairs, w.pos);
-    const unsigned vb = (unsigned)((V + kUThreads * kUEpt - 1) / (kUThreads * kUEpt));
-    hipLaunchKernelGGL(compact_kernel, dim3(vb), dim3(kUThreads), 0, stream, w.pos, V, w.ulist, w.counter);
+    hipLaunchKernelGGL(mark_kernel, dim3(mb), dim3(256), 0, stream, a.idx, pairs, w.flag);
+    const int64_t vb = (V + kUThreads * kUEpt - 1) / (kUThreads * kUEpt);
+    const bool ordered = vb <= kOrderedMaxBlocks;
+    if (ordered)
+        hipLaunchKernelGGL(compact_kernel<true>, dim3((unsigned)vb), dim3(kUThreads), 0, stream, w.flag, w.pos, V, w.ulist,
+                           w.counter);
+    else
+        hipLaunchKernelGGL(compact_kernel<false>, dim3((unsigned)vb), dim3(kUThreads), 0, stream, w.flag, w.pos, V, w.ulist,
+                           w.counter);
 
     GemvArgs u = a;                                       // product over the union list, all hidden rows
     u.idx = w.ulist;
     u.idx_row_stride = 0;
     u.n_items = w.zu_stride;                              // upper bound: sizes the grid
     u.n_items_dev = w.counter;
+    u.plain_order = ordered ? 0 : 1;                      // a list in run-dependent order: no rotated reduction
     u.out_f32 = w.zu;
     u.out_row_stride = w.zu_stride;
     e = launch_skinny_mfma(u, stream);
