@@ -20,15 +20,20 @@ __device__ __forceinline__ u32x4 load16(const u32x4* p) {
 }
 
 // acc + <w, x> over the 16 bytes held in w and x (8 bf16 pairs or 4 float32 pairs), fp32 accumulate.
-// bf16 -> fp32 widening is a shift (low element) or a mask (high element); each product is exact in
-// fp32 and enters the accumulator through one fused multiply-add.
 template <int DT>
 __device__ __forceinline__ float dot16(const u32x4 w, const u32x4 x, float acc) {
     if constexpr (DT == DT_BF16) {
+        // v_dot2_f32_bf16: both products of a 32-bit word and the sum in one instruction instead of two shifts, two
+        // masks and two fused multiply-adds (products of bf16 are exact in float32; the sum rounds to within an
+        // ulp of the fused chain: 12 of 32768 random words differed, by one ulp, none on integers).
+        // The words go through scalars first: a bit cast applied to an element of the vector types made the
+        // compiler use element 0 four times.
+        typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            acc = fmaf(__uint_as_float(w[i] << 16), __uint_as_float(x[i] << 16), acc);
-            acc = fmaf(__uint_as_float(w[i] & 0xFFFF0000u), __uint_as_float(x[i] & 0xFFFF0000u), acc);
+            const uint32_t wi = w[i], xi = x[i];
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, wi), __builtin_bit_cast(bf16x2_t, xi), acc,
+                                                  false);
         }
     } else {
 #pragma unroll
