@@ -103,15 +103,17 @@ __global__ __launch_bounds__(256) void gemv_rows_kernel(const GemvArgs a) {
 // long product simply streams workgroup after workgroup.  Loads are branch-free: units past the end of
 // a row are clamped to its last unit and meet zeros in the staged hidden row (FULL: rows of exactly
 // NL * 64 units, nothing to clamp -- the address arithmetic in front of the first requests is worth 1 %).
-constexpr int kOnceWaves = 4;       // measured: 2, 8 and 16 wavefronts per workgroup are all 1-5 % slower
+// Wavefronts per workgroup (WAVES): four, or eight for gathers of a few thousand to 16 K rows, where staging the
+// hidden row half as often is worth 0.5-1 % (k = 8192: 12.08 -> 11.99 us cold); with fewer rows eight leave
+// compute units idle (k = 512: 2.65 -> 3.04 us), with more they lose 1 %; two and sixteen lose everywhere.
 // The arguments the first requests need come first and one by one: plain leading arguments are preloaded
 // into scalar registers with the wavefront (a struct passed by value is fetched by the first instructions).
-template <int DT, int NL, bool OUT_BF16, bool FULL>
-__global__ __launch_bounds__(kOnceWaves * 64) void gemv_rows_once_kernel(
+template <int DT, int NL, bool OUT_BF16, bool FULL, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemv_rows_once_kernel(
     const char* __restrict__ x_base, const char* __restrict__ m_base, const int32_t* __restrict__ idx_base,
     const int64_t n, const int64_t x_row_bytes, const int64_t m_row_bytes, const int64_t idx_row_stride,
     const GemvArgs a) {
-    constexpr int kT = kOnceWaves * 64;
+    constexpr int kT = WAVES * 64;
     constexpr int kUnits = NL * 64;
     constexpr int kRounds = (kUnits + kT - 1) / kT;
     __shared__ u32x4 s_x[kUnits];
@@ -120,7 +122,7 @@ __global__ __launch_bounds__(kOnceWaves * 64) void gemv_rows_once_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t r = blockIdx.y;
     const int last = FULL ? kUnits - 1 : a.chunks - 1;
-    const int64_t it = (int64_t)blockIdx.x * kOnceWaves + wave;
+    const int64_t it = (int64_t)blockIdx.x * WAVES + wave;
 
     // request order as in gemv_rows_kernel: hidden row, scalar index, row of the matrix
     const u32x4* xp = reinterpret_cast<const u32x4*>(x_base + r * x_row_bytes);
@@ -244,12 +246,12 @@ hipError_t launch_rows(const GemvArgs& a, int cus, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int DT, int NL>
-hipError_t launch_once(const GemvArgs& a, hipStream_t stream) {
-    dim3 grid((unsigned)((a.n_items + kOnceWaves - 1) / kOnceWaves), (unsigned)a.rows, 1), block(kOnceWaves * 64, 1, 1);
+template <int DT, int NL, int WAVES>
+hipError_t launch_once_w(const GemvArgs& a, hipStream_t stream) {
+    dim3 grid((unsigned)((a.n_items + WAVES - 1) / WAVES), (unsigned)a.rows, 1), block(WAVES * 64, 1, 1);
     const bool full = a.chunks == NL * 64;
-#define SV_ONCE(OUT, FULLROW)                                                                                     \
-    hipLaunchKernelGGL((gemv_rows_once_kernel<DT, NL, OUT, FULLROW>), grid, block, 0, stream, a.x, a.M, a.idx,    \
+#define SV_ONCE(OUT, FULLROW)                                                                                       \
+    hipLaunchKernelGGL((gemv_rows_once_kernel<DT, NL, OUT, FULLROW, WAVES>), grid, block, 0, stream, a.x, a.M, a.idx, \
                        a.n_items, a.x_row_bytes, a.m_row_bytes, a.idx_row_stride, a)
     if (a.out_bf16) {
         if (full) SV_ONCE(true, true);
@@ -260,6 +262,11 @@ hipError_t launch_once(const GemvArgs& a, hipStream_t stream) {
     }
 #undef SV_ONCE
     return hipGetLastError();
+}
+template <int DT, int NL>
+hipError_t launch_once(const GemvArgs& a, hipStream_t stream) {
+    if (a.rows == 1 && a.n_items > 2048 && a.n_items <= 16384) return launch_once_w<DT, NL, 8>(a, stream);   // (measured at one row)
+    return launch_once_w<DT, NL, 4>(a, stream);
 }
 
 template <int DT>
