@@ -478,7 +478,7 @@ def main():
     # HBM-side bytes per launch: rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for a
     # 1 GiB plain copy, from the committed summary of `bench.py --counter-run` (None if that file is missing)
     roofline = {"bound": "hbm",
-                "kernel": "gemv_rows_once_kernel<bf16, 8 loads/lane, 1 row/wave>: row gather of 8192 rows of U "
+                "kernel": "gemv_rows_once_kernel<bf16, 8 loads/lane, 1 row/wave, 8 waves/workgroup>: row gather of 8192 rows of U "
                           "(specvocab_subset_logits), 1 of the 2 launches of a step",
                 "achieved": round(gather_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(gather_gbps / HBM_PEAK_GBPS, 4), "traffic": counter_summary_traffic(),
