@@ -10,6 +10,7 @@
 //   gemv_long_rows_kernel   longer rows, walked in 1 KiB pieces
 // An index of -1 (a padding slot of a padded list) reads row 0 and stores -inf: negative indices cost a
 // scalar maximum and a select, so all three kernels accept them whether the list is padded or not.
+#include <stddef.h>
 #include "sv_device.h"
 #include "sv_launch.h"
 
@@ -108,6 +109,25 @@ __global__ __launch_bounds__(256) void gemv_rows_kernel(const GemvArgs a) {
 // compute units idle (k = 512: 2.65 -> 3.04 us), with more they lose 1 %; two and sixteen lose everywhere.
 // The arguments the first requests need come first and one by one: plain leading arguments are preloaded
 // into scalar registers with the wavefront (a struct passed by value is fetched by the first instructions).
+// the kernel's argument segment as bytes (the host pass of the compiler only parses this)
+__device__ __forceinline__ const char* kernarg_bytes() {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return (const char*)__builtin_amdgcn_kernarg_segment_ptr();
+#else
+    return nullptr;
+#endif
+}
+// offset of the argument struct in the kernel's argument segment: three pointers and four 64-bit integers lie
+// in front of it (the segment is laid out like a struct of the arguments)
+struct OnceArgsLayout {
+    const char* x_base;
+    const char* m_base;
+    const int32_t* idx_base;
+    int64_t n, x_row_bytes, m_row_bytes, idx_row_stride;
+    GemvArgs a;
+};
+constexpr int kOnceStructOffset = (int)offsetof(OnceArgsLayout, a);
+static_assert(kOnceStructOffset == 56, "gemv_rows_once_kernel reads its last argument at this offset by hand");
 template <int DT, int NL, bool OUT_BF16, bool FULL, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void gemv_rows_once_kernel(
     const char* __restrict__ x_base, const char* __restrict__ m_base, const int32_t* __restrict__ idx_base,
@@ -143,6 +163,19 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_rows_once_kernel(
         w[c] = load16<true>(mp + (FULL || ch < last ? ch : last));
     }
     __builtin_amdgcn_sched_barrier(0);                 // every row request leaves before anything waits
+    // What the end of the kernel needs of the argument struct is fetched only now, by hand: argument loads
+    // that the compiler places at the kernel's entry are scalar loads like the one of the index, scalar loads
+    // return in any order, so the wait for the index would wait for that cold fetch as well (0.07 us of a
+    // 12 us launch).
+    const GemvArgs& late = *reinterpret_cast<const GemvArgs*>(kernarg_bytes() + kOnceStructOffset);
+    float* late_out_f32 = late.out_f32;
+    uint16_t* late_out_bf16 = late.out_bf16;
+    int64_t late_out_stride = late.out_row_stride;
+    size_t late_zero_words = late.zero_words;
+    int64_t late_spread_n = late.spread_n;
+    // (pinned to scalar registers here, or the compiler moves each load down to its first use)
+    asm volatile("" : "+s"(late_out_f32), "+s"(late_out_bf16), "+s"(late_out_stride), "+s"(late_zero_words), "+s"(late_spread_n));
+    __builtin_amdgcn_sched_barrier(0);                 // ... and these requests leave before the first wait too
 #pragma unroll
     for (int q = 0; q < kRounds; ++q) s_x[unit[q]] = FULL || unit[q] <= last ? xs[q] : zero16();
     __syncthreads();
@@ -151,10 +184,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemv_rows_once_kernel(
     for (int c = 0; c < NL; ++c) part[c & 3] = dot16<DT>(w[c], s_x[c * 64 + lane], part[c & 3]);
     const float acc = wave_sum((part[0] + part[1]) + (part[2] + part[3]));
     if (lane == 0 && it < n) {
-        if constexpr (OUT_BF16) a.out_bf16[r * a.out_row_stride + it] = f32_to_bf16_rne(acc);
-        else a.out_f32[r * a.out_row_stride + it] = row < 0 ? -INFINITY : acc;
+        if constexpr (OUT_BF16) late_out_bf16[r * late_out_stride + it] = f32_to_bf16_rne(acc);
+        else late_out_f32[r * late_out_stride + it] = row < 0 ? -INFINITY : acc;
     }
-    prepare_scratch(a);     // clear / fill a later kernel's scratch with this launch
+    if (late_zero_words != 0 || late_spread_n != 0) prepare_scratch(late);   // clear / fill a later kernel's scratch
 }
 
 // any row length: the row is walked in 1 KiB pieces, x is re-read (from L2) for every item
