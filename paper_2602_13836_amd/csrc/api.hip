@@ -148,7 +148,7 @@ int launch_rows_product(int dt, const sv::GemvArgs& g, int64_t V, void* ws, size
 }
 
 // the gather arguments shared by specvocab_subset_logits and specvocab_draft_step
-sv::GemvArgs gather_args(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* U, int64_t ldu, int dt,
+sv::GemvArgs gather_args(const void* h, int64_t rows, int64_t d, int64_t ldh, const void* U, int64_t V, int64_t ldu, int dt,
                          const int32_t* idx, int64_t k, int idx_mode, float* logits_out) {
     const int es = esize_of(dt);
     sv::GemvArgs g{};
@@ -163,6 +163,7 @@ sv::GemvArgs gather_args(const void* h, int64_t rows, int64_t d, int64_t ldh, co
     g.rows = (int)rows;
     g.out_f32 = logits_out;
     g.out_row_stride = k;
+    g.m_rows = V;
     return g;
 }
 
@@ -185,7 +186,7 @@ size_t product_ws_bytes(int dt, const sv::GemvArgs& g, int64_t rows, int64_t V, 
 }
 
 size_t gather_ws_bytes(int64_t rows, int64_t d, int64_t V, int64_t k, int dt, int idx_mode) {
-    sv::GemvArgs g = gather_args(nullptr, rows, d, d, nullptr, d, dt, reinterpret_cast<const int32_t*>(16), k,
+    sv::GemvArgs g = gather_args(nullptr, rows, d, d, nullptr, V, d, dt, reinterpret_cast<const int32_t*>(16), k,
                                  idx_mode, nullptr);
     return pad_ws_bytes(rows, k, idx_mode, dt, g) + product_ws_bytes(dt, g, rows, V, k, idx_mode);
 }
@@ -199,7 +200,7 @@ int launch_gather(int dt, const void* h, int64_t rows, int64_t d, int64_t ldh, c
                   size_t ws_bytes, hipStream_t s) {
     const bool padded = is_padded(idx_mode);
     const int64_t sets = base_mode(idx_mode) == SV_IDX_PER_ROW ? rows : 1;
-    const sv::GemvArgs g0 = gather_args(h, rows, d, ldh, U, ldu, dt, idx, k, idx_mode, logits_out);
+    const sv::GemvArgs g0 = gather_args(h, rows, d, ldh, U, V, ldu, dt, idx, k, idx_mode, logits_out);
     // everything the call will need from the workspace (clean copy of a padded list, union of the sets) is
     // checked here, before the first launch
     const bool copy = padded && padded_needs_copy(dt, g0);
@@ -225,7 +226,7 @@ int launch_gather(int dt, const void* h, int64_t rows, int64_t d, int64_t ldh, c
         rest += pb;
         rest_bytes -= pb;
     }
-    const sv::GemvArgs g = gather_args(h, rows, d, ldh, U, ldu, dt, use, k, idx_mode, logits_out);
+    const sv::GemvArgs g = gather_args(h, rows, d, ldh, U, V, ldu, dt, use, k, idx_mode, logits_out);
     st = launch_rows_product(dt, g, V, rest_bytes ? rest : nullptr, rest_bytes, s);
     if (st != SV_OK) return st;
     if (copy && sv::launch_pad_mask(idx, g.idx_row_stride, (int)rows, k, logits_out, s) != hipSuccess)

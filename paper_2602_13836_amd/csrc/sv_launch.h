@@ -47,6 +47,8 @@ struct GemvArgs {
                                    // device; n_items is then an upper bound that sizes the grid
     int plain_order;               // matrix-core kernels: every workgroup walks the reduction from offset 0 (set when
                                    // the place of an item in the list may differ from run to run)
+    int64_t m_rows;                // number of rows of M that idx may name, 0 if the caller does not say (a kernel that
+                                   // keeps row offsets in 32 bits is then not used with an index list)
 };
 // what a launch does for later kernels besides its product: every thread of the grid calls this once
 __device__ __forceinline__ void prepare_scratch(const GemvArgs& a) {

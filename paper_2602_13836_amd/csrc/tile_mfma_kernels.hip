@@ -15,13 +15,15 @@
 // one TN block) are given consecutive slots on the same XCD, so that M comes from HBM once and from
 // that die's L2 afterwards (measured: HBM traffic 1.27 x the size of M at 512 hidden rows).
 //
-// Two forms of the main loop.  The plain one leaves the order of loads, LDS traffic and MFMAs to the
+// Three forms of the main loop.  The plain one leaves the order of loads, LDS traffic and MFMAs to the
 // compiler and relies on two workgroups per CU to overlap them: best while the kernel is bound by
-// the one pass over M (up to 128 hidden rows).  The pipelined one is for 256 x 256 tiles, where a
-// SIMD holds one or two wavefronts and nothing else hides their waits: operand fragments are read
-// one 16-element step ahead, the LDS copy of the next slice is spread over the four steps of the
+// the one pass over M (up to 128 hidden rows).  The other two are for tiles whose SIMDs hold one or two
+// wavefronts and nothing else to hide their waits.  In the interleaved one every wavefront reads its operand
+// fragments one 16-element step ahead and spreads the LDS copy of the next slice over the four steps of the
 // current one (LDS writes run at a third of the read rate; a burst of them stalls the fragment
-// reads), and scheduling-group fences pin that order against the compiler's own scheduler.
+// reads), with scheduling-group fences pinning that order against the compiler's own scheduler.  In the
+// alternating one (256 x 256 tiles, rows of whole slices) the two wavefronts of a SIMD take turns between
+// multiplying and memory work, a barrier per turn: 5 % faster than the interleaved loop at 512 hidden rows.
 #include "sv_device.h"
 #include "sv_launch.h"
 
@@ -92,14 +94,14 @@ constexpr size_t bracket_lds_bytes() {
 }
 
 // GM x GN wavefronts; each owns WM x WN MFMA tiles of 32 x 32: TM = 32 GM WM hidden rows, TN = 32 GN WN items.
-// PIPE selects the hand-ordered main loop.  EPI: what happens to the product --
+// PIPE: 0 the plain main loop, 1 the interleaved, 2 the alternating one.  EPI: what happens to the product --
 //   EPI_STORE    it is stored;
 //   EPI_BRACKET  the epilogue of the bracketed selection (Section 3.3 Step 2 for a batch of hidden rows)
 //                classifies it, nothing is stored;
 //   EPI_PICK     Section 3.3 Step 3 for a batch of hidden rows with one sorted index list each: only the entries
 //                a row asks for are stored, straight to their place in logits_out.
 enum { EPI_STORE = 0, EPI_BRACKET = 1, EPI_PICK = 2 };
-template <int GM, int GN, int WM, int WN, bool PIPE, int EPI>
+template <int GM, int GN, int WM, int WN, int PIPE, int EPI>
 __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs a, const BracketEpi ep, const PickEpi pk) {
     constexpr int kThreads = 64 * GM * GN;
     constexpr int kRowsPerPass = kThreads / 8;           // loader: 8 threads per 128-byte row slice
@@ -200,7 +202,106 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
                     acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[m], bf[n], acc[m][n], 0, 0, 0);
         }
     };
-    if constexpr (PIPE) {
+    if constexpr (PIPE == 2) {
+        // Two wavefronts share a SIMD and take turns, a barrier ending every turn: while one multiplies a
+        // 16-element step (nothing but its MFMAs), the other issues its memory work -- the LDS reads of its NEXT
+        // step's fragments, a part of its share of the copy of the next slice into LDS, and the global loads that
+        // refill the registers just copied -- and waits for none of it: whatever a wavefront issues in a memory
+        // turn is known complete at the end of its following multiply turn (one s_waitcnt there, long satisfied).
+        // So the multiplying wavefront never queues behind a memory instruction.
+        //
+        // Both groups run the same program, the second (wavefronts 4..7) one turn behind the first.  Turns are
+        // numbered globally: slice s starts at turn b = 8 s, the first group has its memory turns at b + 2 m, the
+        // second at b + 2 m + 1 (m = 0..3).  In memory turn m of slice s a wavefront
+        //   reads the fragments of step m + 1 (m = 3: of step 0 of slice s + 1), and in m = 2 -- a slice's last
+        //     reads -- waits for them at once, so that slice s is read between turns b - 2 and b + 5;
+        //   copies part 1, 2 of slice s + 1 (m = 0, 1) or part 0 of slice s + 2 (m = 3): slice s is written in
+        //     turns b - 10 .. b - 5 and complete at the end of b - 4 -- after the last read of slice s - 2 in the
+        //     same buffer (b - 11), before its own first read (b - 2).
+        static_assert(GM * GN == 8, "eight wavefronts: two per SIMD");
+        constexpr int NOPS = QA + QB;                        // 16-byte units per thread and slice: first M, then x
+        constexpr int PER = (NOPS + 2) / 3;                  // ... copied in three parts
+        u32x4 g[NOPS];
+        bf16x8_t fa[2][WM], fb[2][WN];
+        // Rows are whole slices here (the launcher sends other lengths to the other loop), so no unit is ever past
+        // a row's end.  A unit's address is a wavefront-uniform base (matrix + the slice's offset, kept in scalar
+        // registers) plus a per-thread offset in 16-byte units that never changes: one register per unit.
+        uint32_t off16[NOPS];
+#pragma unroll
+        for (int o = 0; o < NOPS; ++o)
+            off16[o] = (uint32_t)(((o < QB ? reinterpret_cast<const char*>(pb[o]) - a.M : reinterpret_cast<const char*>(pa[o - QB]) - a.x) >> 4) + piece);
+        // wavefronts w and w + 4 of a workgroup run on the same SIMD (the dispatcher deals them round robin; a
+        // machine that dealt them otherwise would make the turns collide, which costs time and nothing else)
+        const bool second = __builtin_amdgcn_readfirstlane(wave) >= 4;
+        auto turn_ends = [&]() { asm volatile("s_barrier" ::: "memory"); };
+        auto read_frags = [&](int buf, int kk, bf16x8_t (&A)[WM], bf16x8_t (&B)[WN]) {
+            const unsigned char* sa = smem + (size_t)buf * kStage + a_off + kk * 32;
+            const unsigned char* sb = smem + (size_t)buf * kStage + b_off + kk * 32;
+#pragma unroll
+            for (int m = 0; m < WM; ++m)
+                A[m] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4*>(sa + (size_t)(32 * m) * kRowB));
+#pragma unroll
+            for (int n = 0; n < WN; ++n)
+                B[n] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4*>(sb + (size_t)(32 * n) * kRowB));
+        };
+        auto request = [&](auto oc, int ks) {               // unit o of slice ks (slices past the end: the last one again)
+            constexpr int o = decltype(oc)::value;
+            const char* base = (o < QB ? a.M : a.x) + (size_t)eff(ks) * (kTK * 2);
+            uint32_t t = off16[o];
+            asm volatile("" : "+v"(t));      // the 64-bit form of the offset is made here, not kept in registers
+            g[o] = *reinterpret_cast<const u32x4*>(base + ((size_t)t << 4));
+        };
+        // part P of slice ks: registers -> LDS buffer ks % 2, then the same registers <- slice ks + 1
+        auto copy_part = [&](auto pc, int ks) {
+            constexpr int P = decltype(pc)::value;
+            constexpr int lo = P * PER, hi = (P + 1) * PER < NOPS ? (P + 1) * PER : NOPS;
+            unsigned char* base = smem + (size_t)(ks & 1) * kStage + (size_t)r0 * kRowB + piece * 16;
+            static_for<lo, hi>([&](auto oc) {
+                constexpr int o = decltype(oc)::value;
+                constexpr int row = o < QB ? TM + kRowsPerPass * o : kRowsPerPass * (o - QB);
+                *reinterpret_cast<u32x4*>(base + (size_t)row * kRowB) = g[o];
+            });
+            static_for<lo, hi>([&](auto oc) { request(oc, ks + 1); });
+        };
+        auto memory_turn = [&](auto mc, int ks) {
+            constexpr int m = decltype(mc)::value;
+            if constexpr (m < 3) read_frags(ks & 1, m + 1, fa[(m + 1) & 1], fb[(m + 1) & 1]);
+            else read_frags((ks + 1) & 1, 0, fa[0], fb[0]);
+            if constexpr (m == 3) copy_part(std::integral_constant<int, 0>{}, ks + 2);
+            else if constexpr (m < 2) copy_part(std::integral_constant<int, m + 1>{}, ks + 1);
+            else __builtin_amdgcn_s_waitcnt(0xC07F);         // the slice's last reads: done before this turn ends
+            turn_ends();
+        };
+        auto multiply_turn = [&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int n = 0; n < WN; ++n)
+                    acc[i][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m & 1][i], fb[m & 1][n], acc[i][n], 0, 0, 0);
+            __builtin_amdgcn_s_setprio(0);
+            __builtin_amdgcn_s_waitcnt(0xC07F);              // lgkmcnt(0): what the last memory turn issued is done
+            turn_ends();
+        };
+        // slice 0 -> buffer 0, slice 1 -> registers; then memory turn 3 of "slice -1"
+        static_for<0, NOPS>([&](auto oc) { request(oc, 0); });
+        copy_part(std::integral_constant<int, 0>{}, 0);
+        copy_part(std::integral_constant<int, 1>{}, 0);
+        copy_part(std::integral_constant<int, 2>{}, 0);
+        copy_part(std::integral_constant<int, 0>{}, 1);
+        __syncthreads();
+        read_frags(0, 0, fa[0], fb[0]);
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        if (second) turn_ends();               // the second group starts one turn later ...
+        for (int ks = 0; ks < nk; ++ks) {
+            static_for<0, 4>([&](auto mc) {
+                memory_turn(mc, ks);
+                multiply_turn(mc);
+            });
+        }
+        if (!second) turn_ends();              // ... and the first ends one turn earlier: the same count for all
+    } else if constexpr (PIPE == 1) {
         // the slice is walked in four 16-element steps with the operand fragments of the next step
         // already on their way from LDS while the current step multiplies
         u32x4 ga[QA], gb[QB];
@@ -485,14 +586,14 @@ template <int GM, int GN, int WM, int WN>
 constexpr size_t tile_lds_bytes() { return (size_t)2 * (32 * GM * WM + 32 * GN * WN) * kRowB; }
 
 // more than 64 KiB of dynamic LDS needs an explicit opt-in per kernel instance and device
-template <int GM, int GN, int WM, int WN, bool PIPE, int EPI>
+template <int GM, int GN, int WM, int WN, int PIPE, int EPI>
 hipError_t opt_in_lds() {
     if (tile_lds_bytes<GM, GN, WM, WN>() <= 64 * 1024) return hipSuccess;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(&tile_mfma_kernel<GM, GN, WM, WN, PIPE, EPI>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)tile_lds_bytes<GM, GN, WM, WN>());
 }
 
-template <int GM, int GN, int WM, int WN, bool PIPE, int EPI = EPI_STORE>
+template <int GM, int GN, int WM, int WN, int PIPE, int EPI = EPI_STORE>
 hipError_t launch_tile(const GemvArgs& a, hipStream_t stream, const BracketEpi& ep = BracketEpi{},
                        const PickEpi& pk = PickEpi{}) {
     constexpr int TM = 32 * GM * WM, TN = 32 * GN * WN;
@@ -512,16 +613,27 @@ hipError_t launch_tile(const GemvArgs& a, hipStream_t stream, const BracketEpi& 
 // every instance launch_tile_mfma can pick, on the current device (called once per device, outside any
 // stream capture, by the library's device set-up)
 hipError_t configure_tile_mfma_lds() {
-    hipError_t e = opt_in_lds<2, 2, 2, 2, false, EPI_STORE>();
-    if (e == hipSuccess) e = opt_in_lds<2, 4, 4, 2, true, EPI_STORE>();
-    if (e == hipSuccess) e = opt_in_lds<2, 2, 2, 2, true, EPI_STORE>();
-    if (e == hipSuccess) e = opt_in_lds<2, 2, 2, 2, false, EPI_BRACKET>();
-    if (e == hipSuccess) e = opt_in_lds<2, 4, 4, 2, true, EPI_BRACKET>();
-    if (e == hipSuccess) e = opt_in_lds<2, 2, 2, 2, true, EPI_BRACKET>();
-    if (e == hipSuccess) e = opt_in_lds<2, 2, 2, 2, false, EPI_PICK>();
-    if (e == hipSuccess) e = opt_in_lds<2, 4, 4, 2, true, EPI_PICK>();
-    if (e == hipSuccess) e = opt_in_lds<2, 2, 2, 2, true, EPI_PICK>();
+    hipError_t e = hipSuccess;
+    auto all_epilogues = [&](auto fn) {
+        if (e == hipSuccess) e = fn(std::integral_constant<int, EPI_STORE>{});
+        if (e == hipSuccess) e = fn(std::integral_constant<int, EPI_BRACKET>{});
+        if (e == hipSuccess) e = fn(std::integral_constant<int, EPI_PICK>{});
+    };
+    all_epilogues([](auto ec) { return opt_in_lds<2, 2, 2, 2, 0, decltype(ec)::value>(); });
+    all_epilogues([](auto ec) { return opt_in_lds<2, 2, 2, 2, 1, decltype(ec)::value>(); });
+    all_epilogues([](auto ec) { return opt_in_lds<2, 4, 4, 2, 1, decltype(ec)::value>(); });
+    all_epilogues([](auto ec) { return opt_in_lds<2, 4, 4, 2, 2, decltype(ec)::value>(); });
     return e;
+}
+
+// The loop in which two wavefronts of a SIMD take turns handles rows that are whole 64-element slices (a short
+// reduction such as the selector's 256 elements runs equally fast in either loop).  Both loops add a token's
+// products in the same order, so the choice never changes a result.
+static bool turns_fit(const GemvArgs& a) {
+    // ... and keeps every row's offset from its matrix in 32 bits of 16-byte units
+    const int64_t m_rows = a.idx ? a.m_rows : a.n_items;
+    constexpr int64_t kSpan = (int64_t)1 << 36;
+    return a.chunks % 8 == 0 && m_rows > 0 && m_rows <= kSpan / a.m_row_bytes && a.rows <= kSpan / a.x_row_bytes;
 }
 
 // the same choice of instance as launch_tile_mfma, so that both compute bit-identical products
@@ -536,9 +648,11 @@ int bracket_tile_items(int rows) { return tile_instance(rows) == 2 ? 256 : 128; 
 hipError_t launch_tile_mfma_bracket(const GemvArgs& a, const BracketEpi& ep, hipStream_t stream) {
     if (a.n_items <= 0 || a.rows <= 0) return hipSuccess;
     switch (tile_instance(a.rows)) {
-        case 0: return launch_tile<2, 2, 2, 2, false, EPI_BRACKET>(a, stream, ep);
-        case 1: return launch_tile<2, 2, 2, 2, true, EPI_BRACKET>(a, stream, ep);
-        default: return launch_tile<2, 4, 4, 2, true, EPI_BRACKET>(a, stream, ep);
+        case 0: return launch_tile<2, 2, 2, 2, 0, EPI_BRACKET>(a, stream, ep);
+        case 1: return launch_tile<2, 2, 2, 2, 1, EPI_BRACKET>(a, stream, ep);
+        default:
+            return turns_fit(a) ? launch_tile<2, 4, 4, 2, 2, EPI_BRACKET>(a, stream, ep)
+                                : launch_tile<2, 4, 4, 2, 1, EPI_BRACKET>(a, stream, ep);
     }
 }
 
@@ -547,22 +661,25 @@ int pick_tile_items(int rows) { return bracket_tile_items(rows); }
 hipError_t launch_tile_mfma_pick(const GemvArgs& a, const PickEpi& pk, hipStream_t stream) {
     if (a.n_items <= 0 || a.rows <= 0) return hipSuccess;
     switch (tile_instance(a.rows)) {
-        case 0: return launch_tile<2, 2, 2, 2, false, EPI_PICK>(a, stream, BracketEpi{}, pk);
-        case 1: return launch_tile<2, 2, 2, 2, true, EPI_PICK>(a, stream, BracketEpi{}, pk);
-        default: return launch_tile<2, 4, 4, 2, true, EPI_PICK>(a, stream, BracketEpi{}, pk);
+        case 0: return launch_tile<2, 2, 2, 2, 0, EPI_PICK>(a, stream, BracketEpi{}, pk);
+        case 1: return launch_tile<2, 2, 2, 2, 1, EPI_PICK>(a, stream, BracketEpi{}, pk);
+        default:
+            return turns_fit(a) ? launch_tile<2, 4, 4, 2, 2, EPI_PICK>(a, stream, BracketEpi{}, pk)
+                                : launch_tile<2, 4, 4, 2, 1, EPI_PICK>(a, stream, BracketEpi{}, pk);
     }
 }
 
 hipError_t launch_tile_mfma(const GemvArgs& a, hipStream_t stream, bool small_tiles) {
     if (a.n_items <= 0 || a.rows <= 0) return hipSuccess;
-    if (small_tiles) return a.rows <= 128 ? launch_tile<2, 2, 2, 2, false>(a, stream) : launch_tile<2, 2, 2, 2, true>(a, stream);
+    if (small_tiles) return a.rows <= 128 ? launch_tile<2, 2, 2, 2, 0>(a, stream) : launch_tile<2, 2, 2, 2, 1>(a, stream);
     // Up to 128 hidden rows the work is bound by streaming M once: small tiles, two workgroups per
     // CU.  Beyond that the 256 x 256 tile halves the operand traffic per multiply-add -- unless rounding
     // the row count up to 256s would add a whole idle half-tile that 128-row tiles avoid.
-    if (a.rows <= 128) return launch_tile<2, 2, 2, 2, false>(a, stream);
-    const int pad256 = (a.rows + 255) / 256 * 256, pad128 = (a.rows + 127) / 128 * 128;
-    if (pad256 == pad128) return launch_tile<2, 4, 4, 2, true>(a, stream);
-    return launch_tile<2, 2, 2, 2, true>(a, stream);
+    switch (tile_instance(a.rows)) {
+        case 0: return launch_tile<2, 2, 2, 2, 0>(a, stream);
+        case 1: return launch_tile<2, 2, 2, 2, 1>(a, stream);
+        default: return turns_fit(a) ? launch_tile<2, 4, 4, 2, 2>(a, stream) : launch_tile<2, 4, 4, 2, 1>(a, stream);
+    }
 }
 
 }  // namespace sv
