@@ -72,6 +72,8 @@ LOGIT_SHAPES = [
     ("bf16", 256, 1024, 1500, 1500, "per_step"), # 256 x 256 tiles, hand-ordered main loop
     ("bf16", 300, 264, 700, 300, "per_step"),    # 128-row tiles with the hand-ordered loop, ragged last slice
     ("bf16", 500, 1000, 2100, 2100, "per_step"), # two 256-row tiles (last one 244 rows), odd slice count
+    ("bf16", 256, 1088, 1200, 1200, "per_step"), # 256 x 256 tiles, 17 whole slices: the loop of alternating wavefronts, rotated walk
+    ("bf16", 512, 448, 900, 700, "per_step"),    # the same loop on 7 slices (no rotation), two row tiles, a gathered list
     ("bf16", 1, 3840, 9000, 4000, "per_row"),    # one row, a few thousand items: eight-wavefront workgroups, clamped loads
     ("f32", 1, 1536, 6000, 3001, "per_row"),     # the same in float32, odd item count
     ("bf16", 16, 64, 600000, 300, "per_row"),    # a vocabulary beyond the ordered union: ranges reserved by atomics
