@@ -181,7 +181,7 @@ size_t pad_ws_bytes(int64_t rows, int64_t k, int idx_mode, int dt, const sv::Gem
 
 // what the product itself needs from the workspace: the slice table of the sorted-lists path, or the union
 size_t product_ws_bytes(int dt, const sv::GemvArgs& g, int64_t rows, int64_t V, int64_t k, int idx_mode) {
-    if (is_sorted(idx_mode) && sv::sorted_pick_wanted(dt, g, V)) return sv::sorted_pick_ws_bytes(rows, V);
+    if (sv::pick_path_wanted(dt, g, V, is_sorted(idx_mode))) return sv::pick_ws_bytes(rows, V, k, is_sorted(idx_mode));
     return sv::union_path_wanted(dt, g) ? sv::union_ws_bytes(rows, V, k) : 0;
 }
 
@@ -215,8 +215,6 @@ int launch_gather(int dt, const void* h, int64_t rows, int64_t d, int64_t ldh, c
     int st = validate_indices(idx, sets * k, V, s, padded, is_sorted(idx_mode) ? k : 0);
     if (st != SV_OK) return st;
     if (padded && !copy) return sv::launch_gemv(dt, g0, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
-    if (is_sorted(idx_mode) && sv::sorted_pick_wanted(dt, g0, V))
-        return sv::launch_sorted_pick_logits(g0, V, ws, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
     const int32_t* use = idx;
     char* rest = static_cast<char*>(ws);
     size_t rest_bytes = ws_bytes;
@@ -227,7 +225,10 @@ int launch_gather(int dt, const void* h, int64_t rows, int64_t d, int64_t ldh, c
         rest_bytes -= pb;
     }
     const sv::GemvArgs g = gather_args(h, rows, d, ldh, U, V, ldu, dt, use, k, idx_mode, logits_out);
-    st = launch_rows_product(dt, g, V, rest_bytes ? rest : nullptr, rest_bytes, s);
+    if (sv::pick_path_wanted(dt, g, V, is_sorted(idx_mode)))
+        st = sv::launch_pick_logits(g, V, is_sorted(idx_mode), rest, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
+    else
+        st = launch_rows_product(dt, g, V, rest_bytes ? rest : nullptr, rest_bytes, s);
     if (st != SV_OK) return st;
     if (copy && sv::launch_pad_mask(idx, g.idx_row_stride, (int)rows, k, logits_out, s) != hipSuccess)
         return SV_ERR_HIP;

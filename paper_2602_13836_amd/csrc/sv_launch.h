@@ -111,6 +111,7 @@ hipError_t launch_tile_mfma_bracket(const GemvArgs& a, const BracketEpi& ep, hip
 struct PickEpi {
     const uint32_t* off;     // [rows][off_stride]
     int64_t off_stride;      // item tiles + 1
+    const uint32_t* perm;    // [rows][k]: list positions grouped by item tile; null: the lists are ascending
     const int32_t* idx;      // [rows][k]
     int64_t k;
     float* out;              // [rows][k]
@@ -131,11 +132,11 @@ hipError_t launch_pad_mask(const int32_t* idx, int64_t idx_row_stride, int rows,
 // Per-row index sets for several hidden rows (a draft tree): the union of the sets is formed on the
 // device, every row of M in the union is read once and multiplied with all hidden rows on the matrix
 // cores, and each (row, j) picks its logit out of that product.
-// Several hidden rows with their own SORTED lists (the caller's declaration) that together are likely to cover
-// the vocabulary: the product over all rows of M with the pick epilogue; ws: sorted_pick_ws_bytes
-bool sorted_pick_wanted(int dt, const GemvArgs& a, int64_t V);
-size_t sorted_pick_ws_bytes(int64_t rows, int64_t V);
-hipError_t launch_sorted_pick_logits(const GemvArgs& a, int64_t V, void* ws, hipStream_t stream);
+// Many hidden rows with their own lists that together are likely to cover the vocabulary: the product over all
+// rows of M with the pick epilogue (sorted: the caller declared the lists ascending); ws: pick_ws_bytes
+bool pick_path_wanted(int dt, const GemvArgs& a, int64_t V, bool sorted);
+size_t pick_ws_bytes(int64_t rows, int64_t V, int64_t k, bool sorted);
+hipError_t launch_pick_logits(const GemvArgs& a, int64_t V, bool sorted, void* ws, hipStream_t stream);
 bool union_path_wanted(int dt, const GemvArgs& a);
 size_t union_ws_bytes(int64_t rows, int64_t V, int64_t k);
 hipError_t launch_union_logits(const GemvArgs& a, int64_t V, void* ws, hipStream_t stream);

@@ -98,7 +98,7 @@ constexpr size_t bracket_lds_bytes() {
 //   EPI_STORE    it is stored;
 //   EPI_BRACKET  the epilogue of the bracketed selection (Section 3.3 Step 2 for a batch of hidden rows)
 //                classifies it, nothing is stored;
-//   EPI_PICK     Section 3.3 Step 3 for a batch of hidden rows with one sorted index list each: only the entries
+//   EPI_PICK     Section 3.3 Step 3 for a batch of hidden rows with one index list each: only the entries
 //                a row asks for are stored, straight to their place in logits_out.
 enum { EPI_STORE = 0, EPI_BRACKET = 1, EPI_PICK = 2 };
 template <int GM, int GN, int WM, int WN, int PIPE, int EPI>
@@ -408,8 +408,9 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
     const int row0 = rt * TM + wr * 32 * WM + 4 * (lane >> 5);
     if constexpr (EPI == EPI_PICK) {
         // Band by band (the 32 GM rows that the wavefronts hold in the same accumulator group) the product goes
-        // to LDS as a [32 GM x TN] tile; then 8 (4) threads per row walk the slice of the row's sorted index list
-        // that falls into this item tile -- pk.off[r, it] .. pk.off[r, it + 1] -- and store the asked entries.
+        // to LDS as a [32 GM x TN] tile; then 8 (4) threads per row walk the entries of the row's index list that
+        // fall into this item tile -- places pk.off[r, it] .. pk.off[r, it + 1] of the list itself if it is
+        // ascending, of pk.perm[r] (the list's positions grouped by tile) if not -- and store the asked entries.
         constexpr int kBandRows = 32 * GM;
         constexpr int kPerRow = kThreads / kBandRows;
         static_assert((size_t)kBandRows * TN * 4 <= (size_t)2 * kStage, "the band tile reuses the operand buffers");
@@ -436,7 +437,9 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
             __syncthreads();
             const int32_t* list = pk.idx + (int64_t)r * pk.k;
             float* o = pk.out + (int64_t)r * pk.k;
-            for (uint32_t j = ja + sub; j < jb; j += kPerRow) {
+            const uint32_t* grouped = pk.perm ? pk.perm + (int64_t)r * pk.k : nullptr;
+            for (uint32_t q = ja + sub; q < jb; q += kPerRow) {
+                const uint32_t j = grouped ? grouped[q] : q;              // (a position below k either way)
                 const uint32_t col = (uint32_t)(list[j] - (int32_t)(it * TN));
                 if (col < (uint32_t)TN) o[j] = s_band[br * TN + col];     // always true for a consistent table
             }

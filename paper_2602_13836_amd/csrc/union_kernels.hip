@@ -174,6 +174,53 @@ __global__ __launch_bounds__(256) void slice_table_kernel(const int32_t* idx, in
     }
 }
 
+// The same table for lists in ANY order, plus perm[r, :]: the positions j of row r's list grouped by item tile
+// (off[r, t] .. off[r, t + 1] are the places in perm of the entries that fall into tile t).  One workgroup per
+// hidden row: count per tile in LDS, scan, scatter.  The order inside a tile's group depends on the run; every
+// position appears exactly once, which is all the epilogue needs.  Ids outside [0, V) (the caller's contract)
+// are counted into the first or last tile, where the epilogue finds no column for them and stores nothing.
+constexpr int kBucketThreads = 1024;
+constexpr int kBucketMaxTiles = 8192;                        // two LDS arrays of that many words
+__global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t* idx, int64_t k, int tile_shift, int tiles,
+                                                               uint32_t* off, uint32_t* perm) {
+    extern __shared__ uint32_t s_tiles[];                    // [tiles] counts, [tiles] cursors
+    __shared__ uint32_t s_w[kBucketThreads / 64];
+    uint32_t* s_cnt = s_tiles;
+    uint32_t* s_cur = s_tiles + tiles;
+    const int tid = threadIdx.x;
+    const int64_t r = blockIdx.x;
+    const int32_t* list = idx + r * k;
+    uint32_t* o = off + r * ((int64_t)tiles + 1);
+    uint32_t* p = perm + r * k;
+    for (int t = tid; t < tiles; t += kBucketThreads) s_cnt[t] = 0u;
+    __syncthreads();
+    auto tile_of = [&](int32_t v) {
+        const int t = v >= 0 ? v >> tile_shift : 0;
+        return t < tiles ? t : tiles - 1;
+    };
+    for (int64_t j = tid; j < k; j += kBucketThreads) atomicAdd(&s_cnt[tile_of(list[j])], 1u);
+    __syncthreads();
+    const int per = (tiles + kBucketThreads - 1) / kBucketThreads;           // consecutive tiles per thread
+    uint32_t sum = 0u;
+    for (int c = 0; c < per; ++c) {
+        const int t = tid * per + c;
+        if (t < tiles) sum += s_cnt[t];
+    }
+    uint32_t base = block_prefix_exclusive<kBucketThreads / 64>(sum, s_w);
+    for (int c = 0; c < per; ++c) {
+        const int t = tid * per + c;
+        if (t < tiles) {
+            const uint32_t n = s_cnt[t];
+            s_cur[t] = base;
+            o[t] = base;
+            base += n;
+        }
+    }
+    if (tid == 0) o[tiles] = (uint32_t)k;
+    __syncthreads();
+    for (int64_t j = tid; j < k; j += kBucketThreads) p[atomicAdd(&s_cur[tile_of(list[j])], 1u)] = (uint32_t)j;
+}
+
 }  // namespace
 
 // bf16, one index set per row, at least two rows, and enough gathered bytes that reading only the
@@ -189,28 +236,42 @@ bool union_path_wanted(int dt, const GemvArgs& a) {
     return pairs >= 16384 && (a.rows >= 16 || naive_bytes >= ((int64_t)512 << 20));
 }
 
-// The sorted-lists path for many rows: worth it when the sets are likely to cover most of the vocabulary
-// (rows k >= 2 V), where reading all of U costs no more than reading the union.
-bool sorted_pick_wanted(int dt, const GemvArgs& a, int64_t V) {
+// Many rows whose sets are likely to cover most of the vocabulary (rows k >= 2 V), where reading all of U costs
+// no more than reading the union: the product over all of U whose epilogue stores only the asked entries.  Lists
+// declared ascending need only the table of slices; lists in any order are grouped by tile first, which needs
+// the tile counters of a row in LDS.
+static int64_t pick_tiles(int rows, int64_t V) { return (V + pick_tile_items(rows) - 1) / pick_tile_items(rows); }
+bool pick_path_wanted(int dt, const GemvArgs& a, int64_t V, bool sorted) {
     return dt == DT_BF16 && a.rows > 64 && a.idx != nullptr && a.idx_row_stride != 0 && a.out_bf16 == nullptr &&
-           (int64_t)a.rows * a.n_items >= 2 * V;
+           (int64_t)a.rows * a.n_items >= 2 * V && (sorted || pick_tiles(a.rows, V) <= kBucketMaxTiles);
 }
-size_t sorted_pick_ws_bytes(int64_t rows, int64_t V) {
-    const int64_t tiles = (V + pick_tile_items((int)rows) - 1) / pick_tile_items((int)rows);
-    return (((size_t)rows * (size_t)(tiles + 1) + 3) & ~(size_t)3) * sizeof(uint32_t);
+static size_t pick_table_words(int64_t rows, int64_t V) {
+    return ((size_t)rows * (size_t)(pick_tiles((int)rows, V) + 1) + 3) & ~(size_t)3;
+}
+size_t pick_ws_bytes(int64_t rows, int64_t V, int64_t k, bool sorted) {
+    return (pick_table_words(rows, V) + (sorted ? 0 : (size_t)rows * (size_t)k)) * sizeof(uint32_t);
 }
 
-hipError_t launch_sorted_pick_logits(const GemvArgs& a, int64_t V, void* ws, hipStream_t stream) {
+hipError_t launch_pick_logits(const GemvArgs& a, int64_t V, bool sorted, void* ws, hipStream_t stream) {
     const int64_t k = a.n_items;
     const int tn = pick_tile_items(a.rows);
-    const int64_t tiles = (V + tn - 1) / tn;
+    const int64_t tiles = pick_tiles(a.rows, V);
     uint32_t* table = static_cast<uint32_t*>(ws);
-    const unsigned sb = (unsigned)((k + 1023) / 1024);
+    uint32_t* perm = sorted ? nullptr : table + pick_table_words(a.rows, V);
     int tile_shift = 0;
     while ((1 << tile_shift) < tn) ++tile_shift;
     if ((1 << tile_shift) != tn) return hipErrorInvalidValue;      // tiles are 128 or 256 items
-    hipLaunchKernelGGL(slice_table_kernel, dim3(sb, (unsigned)a.rows), dim3(256), 0, stream, a.idx, k, tile_shift, tiles,
-                       table);
+    if (sorted) {
+        const unsigned sb = (unsigned)((k + 1023) / 1024);
+        hipLaunchKernelGGL(slice_table_kernel, dim3(sb, (unsigned)a.rows), dim3(256), 0, stream, a.idx, k, tile_shift,
+                           tiles, table);
+    } else {
+        if (tiles > kBucketMaxTiles) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(bucket_kernel, dim3((unsigned)a.rows), dim3(kBucketThreads), (size_t)2 * tiles * sizeof(uint32_t),
+                           stream, a.idx, k, tile_shift, (int)tiles, table, perm);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
     GemvArgs dense = a;
     dense.idx = nullptr;
     dense.idx_row_stride = 0;
@@ -219,6 +280,7 @@ hipError_t launch_sorted_pick_logits(const GemvArgs& a, int64_t V, void* ws, hip
     PickEpi pk{};
     pk.off = table;
     pk.off_stride = tiles + 1;
+    pk.perm = perm;
     pk.idx = a.idx;
     pk.k = k;
     pk.out = a.out_f32;

@@ -126,11 +126,15 @@ def test_dense_select_topk_reject_bad_arguments(lib):
     assert lib.specvocab_draft_step(A, 20, 256, 256, A, 5000, 256, 1, A, 1000, 4, 10, A, A, A, None, A, 80128,
                                     None) == 5
 
-    # many rows with lists declared sorted: the slice table instead of the union scratch
+    # many rows whose sets cover the vocabulary: the table of slices per (row, item tile) -- and, unless the lists
+    # are declared sorted, their positions grouped by tile -- instead of the union scratch
     tab = sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 512, 4096, 151936, 8192, idx_mode=sv.SV_IDX_PER_ROW | sv.SV_IDX_SORTED)
-    uni = sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 512, 4096, 151936, 8192, idx_mode=sv.SV_IDX_PER_ROW)
-    assert 512 * 594 * 4 <= tab <= 512 * 600 * 4 and uni > 512 * 151936 * 4
+    grp = sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 512, 4096, 151936, 8192, idx_mode=sv.SV_IDX_PER_ROW)
+    assert 512 * 594 * 4 <= tab <= 512 * 600 * 4 and grp == tab + 512 * 8192 * 4
     assert lib.specvocab_subset_logits(A, 512, 256, 256, A, 151936, 256, 1, A, 8192, 8, A, A, tab - 1, None) == 5
+    assert lib.specvocab_subset_logits(A, 512, 256, 256, A, 151936, 256, 1, A, 8192, 0, A, A, grp - 1, None) == 5
+    # sets that cannot cover the vocabulary keep the union of the sets
+    assert sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 100, 4096, 151936, 2048, idx_mode=sv.SV_IDX_PER_ROW) > 100 * 151936 * 4
     # the declaration changes nothing where the general path is the better one anyway
     assert sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 60, 4096, 128256, 4096, idx_mode=sv.SV_IDX_SORTED) == \
         sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 60, 4096, 128256, 4096)

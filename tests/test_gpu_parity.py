@@ -57,7 +57,7 @@ LOGIT_SHAPES = [
     ("bf16", 4, 8192, 30000, 13000, "per_row"),  # few rows, enough gathered bytes for the union-of-sets path
     ("bf16", 16, 1024, 6000, 1100, "per_row"),   # 16 rows: union-of-sets path
     ("bf16", 60, 520, 3000, 600, "per_row"),     # a tree's worth of rows, ragged reduction slice
-    ("bf16", 70, 256, 4000, 300, "per_row"),     # more than 64 hidden rows: two passes
+    ("bf16", 70, 256, 4000, 300, "per_row"),     # more than 64 hidden rows, sets that cover the vocabulary (128-item tiles)
     ("bf16", 33, 3840, 2500, 2500, "per_row"),   # every row asks for the whole vocabulary
     ("bf16", 64, 1024, 9000, 77, "per_step"),    # 64 rows, one shared set
     ("bf16", 17, 4096, 1500, 1500, "per_step"),
@@ -66,7 +66,9 @@ LOGIT_SHAPES = [
     ("bf16", 65, 1024, 3000, 700, "per_step"),   # more than 64 rows: LDS-tiled matrix-core kernel, ragged tiles
     ("bf16", 130, 200, 1111, 1111, "per_step"),  # three row tiles (last one 2 rows), 25 units: ragged last slice
     ("bf16", 200, 4096, 2000, 129, "per_step"),  # one item tile plus one item
-    ("bf16", 150, 512, 5000, 900, "per_row"),    # union of 150 sets on the tiled kernel
+    ("bf16", 150, 512, 5000, 900, "per_row"),    # 150 unsorted sets that cover the vocabulary: grouped by tile, pick epilogue
+    ("bf16", 150, 512, 50000, 300, "per_row"),   # 150 sets that do not: union of the sets on the tiled kernel
+    ("bf16", 300, 256, 70000, 900, "per_row"),   # 256 x 256 tiles with the pick epilogue, lists in any order, ragged last tile
     ("bf16", 70, 8, 300, 300, "per_step"),       # one 16-byte unit per row: a single, ragged reduction slice
     ("bf16", 300, 64, 100, 1, "per_step"),       # one item, three row tiles
     ("bf16", 256, 1024, 1500, 1500, "per_step"), # 256 x 256 tiles, hand-ordered main loop
@@ -550,6 +552,7 @@ PADDED_SHAPES = [
     ("bf16", 6, 1024, 5000, 700, "per_step"),     # matrix cores, one shared padded list
     ("bf16", 20, 512, 6000, 1100, "per_row"),     # union of sets
     ("bf16", 70, 256, 3000, 300, "per_step"),     # tiled matrix-core kernel
+    ("bf16", 80, 256, 2000, 300, "per_row"),      # many rows whose sets cover the vocabulary: grouped by tile, pick epilogue
 ]
 
 
