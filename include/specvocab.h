@@ -91,9 +91,10 @@ typedef enum { SV_IDX_PER_ROW = 0, SV_IDX_PER_STEP = 1 } sv_idx_mode;
  * not sorted then gives wrong logits (never an access out of bounds; the debug mode reports SV_ERR_INDEX).  It
  * matters for a large batch: with more than 64 bf16 hidden rows, one list per row and rows * k >= 2 V -- sets that
  * together cover the vocabulary -- the gathering calls read all of U once, tile by tile, and store only the
- * entries each row asks for.  Lists in any order take the same route after a pass that groups every list by
- * tile (one more small launch, rows * k more words of workspace, about 2 % to 7 % more time at 512 rows); the
- * declaration saves that pass.  Ignored together with SV_IDX_PADDED and wherever it makes no difference. */
+ * entries each row asks for.  Lists in any order take the same route between a pass that groups every list by
+ * tile and one that puts the logits back into the caller's order (two more small launches, 3 rows * k more words
+ * of workspace, about a tenth more time at 512 rows); the declaration saves both.  Ignored together with
+ * SV_IDX_PADDED and wherever it makes no difference. */
 #define SV_IDX_SORTED 8
 
 typedef enum {

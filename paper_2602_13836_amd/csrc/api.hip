@@ -51,6 +51,8 @@ hipError_t device_state(const DeviceState** out) {
             if (e != hipSuccess) return e;
             e = configure_select_lds();
             if (e != hipSuccess) return e;
+            e = configure_union_lds();
+            if (e != hipSuccess) return e;
             void* p = nullptr;
             e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
             if (e != hipSuccess) return e;

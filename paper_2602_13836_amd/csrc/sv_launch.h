@@ -19,6 +19,7 @@ hipError_t device_info(DeviceInfo* out);
 hipError_t configure_skinny_mfma_lds();
 hipError_t configure_tile_mfma_lds();
 hipError_t configure_select_lds();
+hipError_t configure_union_lds();
 
 // out[r, j] = < M[row(r, j), :], x[r, :] >  for j in [0, n_items)
 //   row(r, j) = j                       if idx == nullptr   (dense)
@@ -111,10 +112,9 @@ hipError_t launch_tile_mfma_bracket(const GemvArgs& a, const BracketEpi& ep, hip
 struct PickEpi {
     const uint32_t* off;     // [rows][off_stride]
     int64_t off_stride;      // item tiles + 1
-    const uint32_t* perm;    // [rows][k]: list positions grouped by item tile; null: the lists are ascending
-    const int32_t* idx;      // [rows][k]
+    const int32_t* idx;      // [rows][k]: lists in which the entries of an item tile are contiguous
     int64_t k;
-    float* out;              // [rows][k]
+    float* out;              // [rows][k], in the order of idx
 };
 int pick_tile_items(int rows);
 hipError_t launch_tile_mfma_pick(const GemvArgs& a, const PickEpi& pk, hipStream_t stream);

@@ -409,8 +409,9 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
     if constexpr (EPI == EPI_PICK) {
         // Band by band (the 32 GM rows that the wavefronts hold in the same accumulator group) the product goes
         // to LDS as a [32 GM x TN] tile; then 8 (4) threads per row walk the entries of the row's index list that
-        // fall into this item tile -- places pk.off[r, it] .. pk.off[r, it + 1] of the list itself if it is
-        // ascending, of pk.perm[r] (the list's positions grouped by tile) if not -- and store the asked entries.
+        // fall into this item tile -- places pk.off[r, it] .. pk.off[r, it + 1] of the list (ascending, or a copy
+        // grouped by tile: all that matters here is that a tile's entries are contiguous) -- and store the asked
+        // entries at the same places of the output.
         constexpr int kBandRows = 32 * GM;
         constexpr int kPerRow = kThreads / kBandRows;
         static_assert((size_t)kBandRows * TN * 4 <= (size_t)2 * kStage, "the band tile reuses the operand buffers");
@@ -437,9 +438,7 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
             __syncthreads();
             const int32_t* list = pk.idx + (int64_t)r * pk.k;
             float* o = pk.out + (int64_t)r * pk.k;
-            const uint32_t* grouped = pk.perm ? pk.perm + (int64_t)r * pk.k : nullptr;
-            for (uint32_t q = ja + sub; q < jb; q += kPerRow) {
-                const uint32_t j = grouped ? grouped[q] : q;              // (a position below k either way)
+            for (uint32_t j = ja + sub; j < jb; j += kPerRow) {
                 const uint32_t col = (uint32_t)(list[j] - (int32_t)(it * TN));
                 if (col < (uint32_t)TN) o[j] = s_band[br * TN + col];     // always true for a consistent table
             }

@@ -174,24 +174,33 @@ __global__ __launch_bounds__(256) void slice_table_kernel(const int32_t* idx, in
     }
 }
 
-// The same table for lists in ANY order, plus perm[r, :]: the positions j of row r's list grouped by item tile
-// (off[r, t] .. off[r, t + 1] are the places in perm of the entries that fall into tile t).  One workgroup per
+// The same table for lists in ANY order, plus grouped[r, :] and perm[r, :]: the ids of row r's list grouped by
+// item tile (off[r, t] .. off[r, t + 1] are the places of the entries that fall into tile t) and the positions in
+// the caller's list they came from.  One workgroup per
 // hidden row: count per tile in LDS, scan, scatter.  The order inside a tile's group depends on the run; every
 // position appears exactly once, which is all the epilogue needs.  Ids outside [0, V) (the caller's contract)
 // are counted into the first or last tile, where the epilogue finds no column for them and stores nothing.
 constexpr int kBucketThreads = 1024;
 constexpr int kBucketMaxTiles = 8192;                        // two LDS arrays of that many words
+constexpr size_t kStageLdsBytes = 156 * 1024;                // dynamic LDS these kernels may ask for (opted in at set-up)
+// STAGE: the two grouped arrays of the row are put together in LDS and stored as contiguous runs (scattered
+// 4-byte stores to memory are several times slower than the whole rest of the kernel); rows too long for that
+// scatter their stores.
+template <bool STAGE>
 __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t* idx, int64_t k, int tile_shift, int tiles,
-                                                               uint32_t* off, uint32_t* perm) {
-    extern __shared__ uint32_t s_tiles[];                    // [tiles] counts, [tiles] cursors
+                                                               uint32_t* off, uint32_t* perm, int32_t* grouped) {
+    extern __shared__ uint32_t s_tiles[];                    // [tiles] counts, [tiles] cursors, STAGE: [k] places, [k] ids
     __shared__ uint32_t s_w[kBucketThreads / 64];
     uint32_t* s_cnt = s_tiles;
     uint32_t* s_cur = s_tiles + tiles;
+    uint32_t* s_perm = s_tiles + 2 * tiles;
+    int32_t* s_gid = reinterpret_cast<int32_t*>(s_perm + (STAGE ? k : 0));
     const int tid = threadIdx.x;
     const int64_t r = blockIdx.x;
     const int32_t* list = idx + r * k;
     uint32_t* o = off + r * ((int64_t)tiles + 1);
     uint32_t* p = perm + r * k;
+    int32_t* gid = grouped + r * k;
     for (int t = tid; t < tiles; t += kBucketThreads) s_cnt[t] = 0u;
     __syncthreads();
     auto tile_of = [&](int32_t v) {
@@ -218,7 +227,37 @@ __global__ __launch_bounds__(kBucketThreads) void bucket_kernel(const int32_t* i
     }
     if (tid == 0) o[tiles] = (uint32_t)k;
     __syncthreads();
-    for (int64_t j = tid; j < k; j += kBucketThreads) p[atomicAdd(&s_cur[tile_of(list[j])], 1u)] = (uint32_t)j;
+    for (int64_t j = tid; j < k; j += kBucketThreads) {
+        const int32_t v = list[j];
+        const uint32_t q = atomicAdd(&s_cur[tile_of(v)], 1u);
+        (STAGE ? s_perm : p)[q] = (uint32_t)j;
+        (STAGE ? s_gid : gid)[q] = v;
+    }
+    if constexpr (STAGE) {
+        __syncthreads();
+        for (int64_t q = tid; q < k; q += kBucketThreads) {
+            p[q] = s_perm[q];
+            gid[q] = s_gid[q];
+        }
+    }
+}
+
+// out[r, perm[r, q]] = grouped_out[r, q]: the logits back into the order of the caller's list, one workgroup per
+// hidden row.  (Stored straight from the product's epilogue these scattered 4-byte stores come from all dies
+// over the whole launch and reach memory as partial lines: +50 to +100 us at 512 rows x 8192.)  STAGE: the row is
+// put together in LDS and stored as one contiguous run.
+template <bool STAGE>
+__global__ __launch_bounds__(1024) void unpermute_kernel(const float* grouped_out, const uint32_t* perm, int64_t k, float* out) {
+    extern __shared__ float s_row[];                         // STAGE: [k]
+    const int64_t r = blockIdx.x;
+    const float* z = grouped_out + r * k;
+    const uint32_t* p = perm + r * k;
+    float* o = out + r * k;
+    for (int64_t q = threadIdx.x; q < k; q += blockDim.x) (STAGE ? s_row : o)[p[q]] = z[q];
+    if constexpr (STAGE) {
+        __syncthreads();
+        for (int64_t j = threadIdx.x; j < k; j += blockDim.x) o[j] = s_row[j];
+    }
 }
 
 }  // namespace
@@ -236,6 +275,17 @@ bool union_path_wanted(int dt, const GemvArgs& a) {
     return pairs >= 16384 && (a.rows >= 16 || naive_bytes >= ((int64_t)512 << 20));
 }
 
+// more than 64 KiB of dynamic LDS needs an explicit opt-in per kernel and device (called once per device, outside
+// any stream capture, by the library's device set-up)
+hipError_t configure_union_lds() {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bucket_kernel<true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStageLdsBytes);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&unpermute_kernel<true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStageLdsBytes);
+    return e;
+}
+
 // Many rows whose sets are likely to cover most of the vocabulary (rows k >= 2 V), where reading all of U costs
 // no more than reading the union: the product over all of U whose epilogue stores only the asked entries.  Lists
 // declared ascending need only the table of slices; lists in any order are grouped by tile first, which needs
@@ -249,7 +299,7 @@ static size_t pick_table_words(int64_t rows, int64_t V) {
     return ((size_t)rows * (size_t)(pick_tiles((int)rows, V) + 1) + 3) & ~(size_t)3;
 }
 size_t pick_ws_bytes(int64_t rows, int64_t V, int64_t k, bool sorted) {
-    return (pick_table_words(rows, V) + (sorted ? 0 : (size_t)rows * (size_t)k)) * sizeof(uint32_t);
+    return (pick_table_words(rows, V) + (sorted ? 0 : 3 * (size_t)rows * (size_t)k)) * sizeof(uint32_t);
 }
 
 hipError_t launch_pick_logits(const GemvArgs& a, int64_t V, bool sorted, void* ws, hipStream_t stream) {
@@ -258,6 +308,8 @@ hipError_t launch_pick_logits(const GemvArgs& a, int64_t V, bool sorted, void* w
     const int64_t tiles = pick_tiles(a.rows, V);
     uint32_t* table = static_cast<uint32_t*>(ws);
     uint32_t* perm = sorted ? nullptr : table + pick_table_words(a.rows, V);
+    int32_t* grouped = sorted ? nullptr : reinterpret_cast<int32_t*>(perm + (size_t)a.rows * (size_t)k);
+    float* grouped_out = sorted ? nullptr : reinterpret_cast<float*>(grouped + (size_t)a.rows * (size_t)k);
     int tile_shift = 0;
     while ((1 << tile_shift) < tn) ++tile_shift;
     if ((1 << tile_shift) != tn) return hipErrorInvalidValue;      // tiles are 128 or 256 items
@@ -267,8 +319,13 @@ hipError_t launch_pick_logits(const GemvArgs& a, int64_t V, bool sorted, void* w
                            tiles, table);
     } else {
         if (tiles > kBucketMaxTiles) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(bucket_kernel, dim3((unsigned)a.rows), dim3(kBucketThreads), (size_t)2 * tiles * sizeof(uint32_t),
-                           stream, a.idx, k, tile_shift, (int)tiles, table, perm);
+        const size_t plain = (size_t)2 * tiles * sizeof(uint32_t), staged = plain + (size_t)2 * k * sizeof(uint32_t);
+        if (staged <= kStageLdsBytes)
+            hipLaunchKernelGGL(bucket_kernel<true>, dim3((unsigned)a.rows), dim3(kBucketThreads), staged, stream, a.idx, k,
+                               tile_shift, (int)tiles, table, perm, grouped);
+        else
+            hipLaunchKernelGGL(bucket_kernel<false>, dim3((unsigned)a.rows), dim3(kBucketThreads), plain, stream, a.idx, k,
+                               tile_shift, (int)tiles, table, perm, grouped);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -280,11 +337,18 @@ hipError_t launch_pick_logits(const GemvArgs& a, int64_t V, bool sorted, void* w
     PickEpi pk{};
     pk.off = table;
     pk.off_stride = tiles + 1;
-    pk.perm = perm;
-    pk.idx = a.idx;
+    pk.idx = sorted ? a.idx : grouped;
     pk.k = k;
-    pk.out = a.out_f32;
-    return launch_tile_mfma_pick(dense, pk, stream);
+    pk.out = sorted ? a.out_f32 : grouped_out;
+    e = launch_tile_mfma_pick(dense, pk, stream);
+    if (e != hipSuccess || sorted) return e;
+    if ((size_t)k * sizeof(float) <= kStageLdsBytes)
+        hipLaunchKernelGGL(unpermute_kernel<true>, dim3((unsigned)a.rows), dim3(1024), (size_t)k * sizeof(float), stream,
+                           grouped_out, perm, k, a.out_f32);
+    else
+        hipLaunchKernelGGL(unpermute_kernel<false>, dim3((unsigned)a.rows), dim3(1024), 0, stream, grouped_out, perm, k,
+                           a.out_f32);
+    return hipGetLastError();
 }
 
 size_t union_ws_bytes(int64_t rows, int64_t V, int64_t k) {

@@ -130,7 +130,7 @@ def test_dense_select_topk_reject_bad_arguments(lib):
     # are declared sorted, their positions grouped by tile -- instead of the union scratch
     tab = sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 512, 4096, 151936, 8192, idx_mode=sv.SV_IDX_PER_ROW | sv.SV_IDX_SORTED)
     grp = sv.workspace_bytes(sv.SV_OP_SUBSET_LOGITS, 512, 4096, 151936, 8192, idx_mode=sv.SV_IDX_PER_ROW)
-    assert 512 * 594 * 4 <= tab <= 512 * 600 * 4 and grp == tab + 512 * 8192 * 4
+    assert 512 * 594 * 4 <= tab <= 512 * 600 * 4 and grp == tab + 3 * 512 * 8192 * 4
     assert lib.specvocab_subset_logits(A, 512, 256, 256, A, 151936, 256, 1, A, 8192, 8, A, A, tab - 1, None) == 5
     assert lib.specvocab_subset_logits(A, 512, 256, 256, A, 151936, 256, 1, A, 8192, 0, A, A, grp - 1, None) == 5
     # sets that cannot cover the vocabulary keep the union of the sets
