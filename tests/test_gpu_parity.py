@@ -139,7 +139,8 @@ def test_strided_rows(rows, d, V, k):
 def test_subset_logits_many_rows_sorted_lists(rows, d, V, k, kind):
     """More than 64 hidden rows with their own lists, declared SORTED, that together cover the vocabulary: the
     product over all of U whose epilogue stores only the asked entries.  Element by element against the oracle
-    and bit for bit against the same call without the declaration (the general path; same matrix-core kernel)."""
+    and bit for bit against the same call without the declaration and against the same sets with every list
+    shuffled (lists in any order are grouped by item tile on the device and take the same product)."""
     say(f"many rows, own sorted lists ({kind}) rows={rows} d={d} V={V} k={k}")
     rng = np.random.default_rng(rows + V + k)
     U, h = rand(rng, (V, d), 0.02, "bf16"), rand(rng, (rows, d), 1.0, "bf16")
@@ -154,7 +155,14 @@ def test_subset_logits_many_rows_sorted_lists(rows, d, V, k, kind):
     z = sv.subset_logits(th, tU, tidx, sorted_lists=True)
     if rows * k >= 16384:                                   # both paths then multiply on the same matrix-core kernel
         assert torch.equal(z, sv.subset_logits(th, tU, tidx))
+    # the same sets with every list in an order of its own: grouped by item tile on the device, same product
+    order = np.stack([rng.permutation(k) for _ in range(rows)])
+    shuffled = np.take_along_axis(idx, order, axis=1)
+    z_shuffled = sv.subset_logits(th, tU, torch.from_numpy(shuffled).to(DEV)).cpu().numpy()
     z = z.cpu().numpy()
+    if rows * k >= 16384:
+        assert np.array_equal(z_shuffled, np.take_along_axis(z, order, axis=1))
+    assert_logits_close(z_shuffled, oracle.subset_logits(h, U, shuffled), "bf16")
     assert_logits_close(z, oracle.subset_logits(h, U, idx), "bf16")
     z2, tok, prob, _ = sv.draft_step(th, tU, tidx, min(10, k), sorted_lists=True)
     assert np.array_equal(z2.cpu().numpy(), z)
