@@ -393,7 +393,20 @@ hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream) {
     // But only a workgroup with at least 128 threads per 16 hidden rows stages the x slice behind the
     // multiplications (four 16-byte pieces per thread), and that matters more than the workgroup count.
     const bool wide = a.n_items >= (int64_t)di.cus * 2 * 128;
-    if (a.rows > 32) return launch_w<8>(a, 0, a.rows, stream);
+    if (a.rows > 32) {
+        // 33 to 64 hidden rows: this kernel (eight wavefronts of 16 rows of M each, two workgroups per CU) or the
+        // LDS-tiled one on 64 x 256 tiles (one workgroup per CU, whole 128-byte lines per request).  The tiled one
+        // streams faster when the chip is full (60 rows x 128256: 199 against 207 us, on some boxes 202 against
+        // 239), but its unit of work is a whole CU-round of 256 items where this kernel's is half of one: measured
+        // over list lengths, the tiled kernel wins when the last round is more than half full (or full), this one
+        // when it is at most half full (40960 items: 86 against 102 us; 81920: 166 against 156).  A count that
+        // lives on the device (the union of a tree step's sets) is not known here: the tiled kernel, whose bad
+        // cases cost less (8-11 % against 7-18 %).
+        const int64_t round_items = (int64_t)256 * di.cus;
+        const int64_t last = a.n_items % round_items;
+        if (a.n_items_dev != nullptr || last == 0 || 2 * last > round_items) return launch_tile_mfma(a, stream);
+        return launch_w<8>(a, 0, a.rows, stream);
+    }
     if (a.rows > 16 || wide) return launch_w<4>(a, 0, a.rows, stream);
     return launch_w<2>(a, 0, a.rows, stream);
 }

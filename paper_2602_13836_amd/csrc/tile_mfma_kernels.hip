@@ -1,4 +1,4 @@
-// Tiled matrix product on the matrix cores for MANY hidden-state rows (more than 64):
+// Tiled matrix product on the matrix cores for MANY hidden-state rows (more than 32):
 //     out[r, j] = < M[row(j), :], x[r, :] >      r < rows, j < n_items
 // with row(j) = j (the full-vocabulary projection of Section 3.1, or the selector's score matrix of
 // Section 3.3 Step 1 for a whole batch) or row(j) = idx[j] (Section 3.3 Step 3 over one set of rows
@@ -621,6 +621,7 @@ hipError_t configure_tile_mfma_lds() {
         if (e == hipSuccess) e = fn(std::integral_constant<int, EPI_BRACKET>{});
         if (e == hipSuccess) e = fn(std::integral_constant<int, EPI_PICK>{});
     };
+    if (e == hipSuccess) e = opt_in_lds<1, 8, 2, 1, 0, EPI_STORE>();
     all_epilogues([](auto ec) { return opt_in_lds<2, 2, 2, 2, 0, decltype(ec)::value>(); });
     all_epilogues([](auto ec) { return opt_in_lds<2, 2, 2, 2, 1, decltype(ec)::value>(); });
     all_epilogues([](auto ec) { return opt_in_lds<2, 4, 4, 2, 1, decltype(ec)::value>(); });
@@ -673,6 +674,9 @@ hipError_t launch_tile_mfma_pick(const GemvArgs& a, const PickEpi& pk, hipStream
 
 hipError_t launch_tile_mfma(const GemvArgs& a, hipStream_t stream, bool small_tiles) {
     if (a.n_items <= 0 || a.rows <= 0) return hipSuccess;
+    // up to 64 hidden rows (the caller decides when this beats the kernel without LDS tiles): 64 x 256 tiles, eight
+    // wavefronts of 64 x 32, one workgroup per CU
+    if (a.rows <= 64) return launch_tile<1, 8, 2, 1, 0>(a, stream);
     if (small_tiles) return a.rows <= 128 ? launch_tile<2, 2, 2, 2, 0>(a, stream) : launch_tile<2, 2, 2, 2, 1>(a, stream);
     // Up to 128 hidden rows the work is bound by streaming M once: small tiles, two workgroups per
     // CU.  Beyond that the 256 x 256 tile halves the operand traffic per multiply-add -- unless rounding
