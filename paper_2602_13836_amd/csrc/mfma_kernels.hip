@@ -1,5 +1,6 @@
 // Skinny matrix product on the matrix cores for several hidden-state rows at once:
 //     out[r, j] = < M[row(j), :], x[r, :] >      r < rows (<= 64 per pass), j < n_items
+// (from 33 rows on the launcher at the end of this file hands full CU-rounds of items to the LDS-tiled kernel)
 // with row(j) = j (the full-vocabulary projection of Section 3.1) or row(j) = idx[j] (Section 3.3
 // Step 3 with one index set shared by every row of the step).  bf16 storage only.
 //
