@@ -997,6 +997,13 @@ def test_config5_full_step_with_selection():
     sel, _ = sv.select(th, tWd, tWv, c.k)
     say("config 5 subset logits")
     z = sv.subset_logits(th, tU, sel, sorted_lists=True)       # the selection emits ascending ids
+    say("config 5 subset logits, the same sets with every list in an order of its own and nothing declared")
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(55)
+    order = torch.stack([torch.randperm(c.k, generator=gen, device=DEV) for _ in range(c.rows)])
+    z_any = sv.subset_logits(th, tU, torch.gather(sel, 1, order).contiguous())
+    assert torch.equal(z_any, torch.gather(z, 1, order))        # the same product, entry for entry
+    del z_any, order
     say("config 5 draft top-kd")
     tok, prob, _ = sv.draft_topk(z, sel, c.kd)
     torch.cuda.synchronize()
