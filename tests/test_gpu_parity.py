@@ -135,6 +135,7 @@ def test_strided_rows(rows, d, V, k):
     (200, 256, 4000, 1500, "repeats"),       # sorted with repeated ids
     (256, 128, 1000, 1000, "clustered"),     # every id of a row inside one item tile
     (100, 256, 30000, 100, "sorted"),        # too few pairs for the vocabulary: the declaration changes nothing
+    (70, 64, 50000, 45000, "sorted"),        # lists too long to be grouped and put back in order inside LDS
 ])
 def test_subset_logits_many_rows_sorted_lists(rows, d, V, k, kind):
     """More than 64 hidden rows with their own lists, declared SORTED, that together cover the vocabulary: the
