@@ -384,9 +384,13 @@ hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream) {
     DeviceInfo di;
     hipError_t e = device_info(&di);
     if (e != hipSuccess) return e;
-    // few items: split the reduction over the wavefronts of a workgroup, 32 hidden rows per workgroup row
-    // (every workgroup reads its hidden rows from L2 itself, so two row groups pay off for fewer items)
-    if (a.n_items <= (int64_t)di.cus * (a.rows > 32 ? 32 : 64) && a.chunks >= 8 * (kKC / 8)) {
+    // few items: split the reduction over the wavefronts of a workgroup, 32 hidden rows per workgroup row.
+    // Every workgroup reads its hidden rows from L2 itself and a CU is through with its workgroups one after the
+    // other (time grows in steps of 16 x CUs items), so the more hidden rows, the earlier the other kernel wins:
+    // measured crossovers (d = 3840) between 12288 and 16384 items at 2 and 8 rows, between 8192 and 10240 at
+    // 16 and 32 rows (16384 items: 29 against 33 us at 8 rows, 36 against 53 at 32 rows).
+    const int64_t split_items = (int64_t)di.cus * (a.rows <= 4 ? 64 : a.rows <= 8 ? 48 : 32);
+    if (a.n_items <= split_items && a.chunks >= 8 * (kKC / 8)) {
         if (a.rows <= 16) return launch_ksplit<1>(a, 0, 1, stream);
         return launch_ksplit<2>(a, 0, (a.rows + 31) / 32, stream);
     }
