@@ -622,6 +622,7 @@ hipError_t configure_tile_mfma_lds() {
         if (e == hipSuccess) e = fn(std::integral_constant<int, EPI_PICK>{});
     };
     if (e == hipSuccess) e = opt_in_lds<1, 8, 2, 1, 0, EPI_STORE>();
+    if (e == hipSuccess) e = opt_in_lds<2, 4, 2, 2, 0, EPI_STORE>();
     all_epilogues([](auto ec) { return opt_in_lds<2, 2, 2, 2, 0, decltype(ec)::value>(); });
     all_epilogues([](auto ec) { return opt_in_lds<2, 2, 2, 2, 1, decltype(ec)::value>(); });
     all_epilogues([](auto ec) { return opt_in_lds<2, 4, 4, 2, 1, decltype(ec)::value>(); });
@@ -682,7 +683,18 @@ hipError_t launch_tile_mfma(const GemvArgs& a, hipStream_t stream, bool small_ti
     // CU.  Beyond that the 256 x 256 tile halves the operand traffic per multiply-add -- unless rounding
     // the row count up to 256s would add a whole idle half-tile that 128-row tiles avoid.
     switch (tile_instance(a.rows)) {
-        case 0: return launch_tile<2, 2, 2, 2, 0>(a, stream);
+        case 0: {
+            // 65 to 128 hidden rows: 128 x 256 tiles with eight wavefronts and one workgroup per CU stream 3-8 %
+            // faster than two workgroups of 128 x 128 (128 rows x 128256: 244 against 261 us) -- when the list fills
+            // its last round of 256 x CUs items more than half, like the 64-row tiles; else they lose up to a third
+            // (100 rows x 16384 items: 82 against 61 us).  A count on the device: the smaller tiles.
+            DeviceInfo di;
+            const hipError_t e = device_info(&di);
+            if (e != hipSuccess) return e;
+            const int64_t round_items = (int64_t)256 * di.cus, last = a.n_items % round_items;
+            if (a.n_items_dev == nullptr && (last == 0 || 2 * last > round_items)) return launch_tile<2, 4, 2, 2, 0>(a, stream);
+            return launch_tile<2, 2, 2, 2, 0>(a, stream);
+        }
         case 1: return launch_tile<2, 2, 2, 2, 1>(a, stream);
         default: return turns_fit(a) ? launch_tile<2, 4, 4, 2, 2>(a, stream) : launch_tile<2, 4, 4, 2, 1>(a, stream);
     }
