@@ -251,8 +251,9 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
             asm volatile("" : "+v"(t));      // the 64-bit form of the offset is made here, not kept in registers
             g[o] = *reinterpret_cast<const u32x4*>(base + ((size_t)t << 4));
         };
-        // part P of slice ks: registers -> LDS buffer ks % 2, then the same registers <- slice ks + 1
-        auto copy_part = [&](auto pc, int ks) {
+        // part P of slice ks: registers -> LDS buffer ks % 2 (store_part), then the same registers <- slice ks + 1
+        // (refill_part)
+        auto store_part = [&](auto pc, int ks) {
             constexpr int P = decltype(pc)::value;
             constexpr int lo = P * PER, hi = (P + 1) * PER < NOPS ? (P + 1) * PER : NOPS;
             unsigned char* base = smem + (size_t)(ks & 1) * kStage + (size_t)r0 * kRowB + piece * 16;
@@ -261,18 +262,27 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
                 constexpr int row = o < QB ? TM + kRowsPerPass * o : kRowsPerPass * (o - QB);
                 *reinterpret_cast<u32x4*>(base + (size_t)row * kRowB) = g[o];
             });
+        };
+        auto refill_part = [&](auto pc, int ks) {
+            constexpr int P = decltype(pc)::value;
+            constexpr int lo = P * PER, hi = (P + 1) * PER < NOPS ? (P + 1) * PER : NOPS;
             static_for<lo, hi>([&](auto oc) { request(oc, ks + 1); });
         };
+        auto copy_part = [&](auto pc, int ks) { store_part(pc, ks); refill_part(pc, ks); };
         auto memory_turn = [&](auto mc, int ks) {
             constexpr int m = decltype(mc)::value;
             if constexpr (m < 3) read_frags(ks & 1, m + 1, fa[(m + 1) & 1], fb[(m + 1) & 1]);
             else read_frags((ks + 1) & 1, 0, fa[0], fb[0]);
-            if constexpr (m == 3) copy_part(std::integral_constant<int, 0>{}, ks + 2);
-            else if constexpr (m < 2) copy_part(std::integral_constant<int, m + 1>{}, ks + 1);
+            if constexpr (m == 3) store_part(std::integral_constant<int, 0>{}, ks + 2);
+            else if constexpr (m < 2) store_part(std::integral_constant<int, m + 1>{}, ks + 1);
             else __builtin_amdgcn_s_waitcnt(0xC07F);         // the slice's last reads: done before this turn ends
             turn_ends();
         };
-        auto multiply_turn = [&](auto mc) {
+        // The refill of the registers a memory turn has copied is requested in the multiply turn after it, behind
+        // the MFMAs: a wavefront issues in order, the address unit takes a 1 KB load per ~22 cycles and the LDS a
+        // request per ~30, and in one turn the loads queued behind the LDS work -- the two units then worked one
+        // after the other; now one group's loads run while the other group's LDS work does.
+        auto multiply_turn = [&](auto mc, int ks) {
             constexpr int m = decltype(mc)::value;
             __builtin_amdgcn_s_setprio(1);
 #pragma unroll
@@ -281,6 +291,9 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
                 for (int n = 0; n < WN; ++n)
                     acc[i][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m & 1][i], fb[m & 1][n], acc[i][n], 0, 0, 0);
             __builtin_amdgcn_s_setprio(0);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (m == 3) refill_part(std::integral_constant<int, 0>{}, ks + 2);
+            else if constexpr (m < 2) refill_part(std::integral_constant<int, m + 1>{}, ks + 1);
             __builtin_amdgcn_s_waitcnt(0xC07F);              // lgkmcnt(0): what the last memory turn issued is done
             turn_ends();
         };
@@ -297,7 +310,7 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
         for (int ks = 0; ks < nk; ++ks) {
             static_for<0, 4>([&](auto mc) {
                 memory_turn(mc, ks);
-                multiply_turn(mc);
+                multiply_turn(mc, ks);
             });
         }
         if (!second) turn_ends();              // ... and the first ends one turn earlier: the same count for all
