@@ -388,30 +388,27 @@ hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream) {
     // Every workgroup reads its hidden rows from L2 itself and a CU is through with its workgroups one after the
     // other (time grows in steps of 16 x CUs items), so the more hidden rows, the earlier the other kernel wins:
     // measured crossovers (d = 3840) between 12288 and 16384 items at 2 and 8 rows, between 8192 and 10240 at
-    // 16 and 32 rows (16384 items: 29 against 33 us at 8 rows, 36 against 53 at 32 rows).
-    const int64_t split_items = (int64_t)di.cus * (a.rows <= 4 ? 64 : a.rows <= 8 ? 48 : 32);
+    // 16 and 32 rows (16384 items: 29 against 33 us at 8 rows, 36 against 53 at 32 rows); from 33 rows on
+    // (d = 4096) between 4096 and 6144 items, where a single tile of the LDS-tiled kernel takes 35 us whatever
+    // the list's length (4096 items: 26 against 35 us; 6144: 39 against 35; 8192: 50 against 35).
+    const int64_t split_items = (int64_t)di.cus * (a.rows <= 4 ? 64 : a.rows <= 8 ? 48 : a.rows <= 32 ? 32 : 20);
     if (a.n_items <= split_items && a.chunks >= 8 * (kKC / 8)) {
         if (a.rows <= 16) return launch_ksplit<1>(a, 0, 1, stream);
         return launch_ksplit<2>(a, 0, (a.rows + 31) / 32, stream);
     }
+    // 33 to 64 hidden rows: the LDS-tiled kernel (whole 128-byte lines per request, several small workgroups per
+    // CU).  Measured over list lengths from 6144 to 128256 items at 36, 48 and 60 rows it is as fast as or faster
+    // than eight wavefronts of this kernel with 16 rows of M each (60 rows: 16384 items 37 against 56 us, 32768
+    // 60 against 66, 81920 144 against 155, 128256 202 against 204).
+    if (a.rows > 32) return launch_tile_mfma(a, stream);
+    // 17 to 32 hidden rows: the LDS-tiled kernel on 32 x 64 tiles wins in the middle -- 3 to 15 % between 12288 and
+    // 81920 items (32 rows: 24576 items 48 against 55 us, 40960 71 against 79, 81920 127 against 131), equal at
+    // 8192 -- and loses 3-5 % from 98304 items on (128256: 203 against 193).
+    if (a.rows > 16 && a.n_items <= (int64_t)di.cus * 352) return launch_tile_mfma(a, stream);
     // Wide workgroups share one x slice among more rows of M; small problems need more workgroups.
     // But only a workgroup with at least 128 threads per 16 hidden rows stages the x slice behind the
     // multiplications (four 16-byte pieces per thread), and that matters more than the workgroup count.
     const bool wide = a.n_items >= (int64_t)di.cus * 2 * 128;
-    if (a.rows > 32) {
-        // 33 to 64 hidden rows: this kernel (eight wavefronts of 16 rows of M each, two workgroups per CU) or the
-        // LDS-tiled one on 64 x 256 tiles (one workgroup per CU, whole 128-byte lines per request).  The tiled one
-        // streams faster when the chip is full (60 rows x 128256: 199 against 207 us, on some boxes 202 against
-        // 239), but its unit of work is a whole CU-round of 256 items where this kernel's is half of one: measured
-        // over list lengths, the tiled kernel wins when the last round is more than half full (or full), this one
-        // when it is at most half full (40960 items: 86 against 102 us; 81920: 166 against 156).  A count that
-        // lives on the device (the union of a tree step's sets) is not known here: the tiled kernel, whose bad
-        // cases cost less (8-11 % against 7-18 %).
-        const int64_t round_items = (int64_t)256 * di.cus;
-        const int64_t last = a.n_items % round_items;
-        if (a.n_items_dev != nullptr || last == 0 || 2 * last > round_items) return launch_tile_mfma(a, stream);
-        return launch_w<8>(a, 0, a.rows, stream);
-    }
     if (a.rows > 16 || wide) return launch_w<4>(a, 0, a.rows, stream);
     return launch_w<2>(a, 0, a.rows, stream);
 }

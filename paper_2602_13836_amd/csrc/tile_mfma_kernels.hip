@@ -634,7 +634,6 @@ hipError_t configure_tile_mfma_lds() {
         if (e == hipSuccess) e = fn(std::integral_constant<int, EPI_BRACKET>{});
         if (e == hipSuccess) e = fn(std::integral_constant<int, EPI_PICK>{});
     };
-    if (e == hipSuccess) e = opt_in_lds<1, 8, 2, 1, 0, EPI_STORE>();
     if (e == hipSuccess) e = opt_in_lds<2, 4, 2, 2, 0, EPI_STORE>();
     all_epilogues([](auto ec) { return opt_in_lds<2, 2, 2, 2, 0, decltype(ec)::value>(); });
     all_epilogues([](auto ec) { return opt_in_lds<2, 2, 2, 2, 1, decltype(ec)::value>(); });
@@ -688,9 +687,19 @@ hipError_t launch_tile_mfma_pick(const GemvArgs& a, const PickEpi& pk, hipStream
 
 hipError_t launch_tile_mfma(const GemvArgs& a, hipStream_t stream, bool small_tiles) {
     if (a.n_items <= 0 || a.rows <= 0) return hipSuccess;
-    // up to 64 hidden rows (the caller decides when this beats the kernel without LDS tiles): 64 x 256 tiles, eight
-    // wavefronts of 64 x 32, one workgroup per CU
-    if (a.rows <= 64) return launch_tile<1, 8, 2, 1, 0>(a, stream);
+    // Up to 64 hidden rows (the caller decides when this beats the kernel without LDS tiles) the product is one
+    // pass over M at the rate of the memory system, and what matters is how evenly the list's items spread over
+    // the chip: small tiles, several workgroups per CU.  32 x 64 tiles (two wavefronts, five workgroups per CU) up
+    // to 32 rows; 64 x 64 (four per CU) for lists of up to 64 x CUs items and 64 x 128 (four wavefronts, two per
+    // CU) beyond, measured at 60 rows against 64 x 256 tiles with one workgroup of eight wavefronts per CU: 16384
+    // items 37 / 44 / 61 us, 32768 59 / 60 / 76, 50200 103 / 93 / 95, 81920 150 / 144 / 161, 128256 213 / 201 / 206.
+    if (a.rows <= 32) return launch_tile<1, 2, 1, 1, 0>(a, stream);
+    if (a.rows <= 64) {
+        DeviceInfo di;
+        const hipError_t e = device_info(&di);
+        if (e != hipSuccess) return e;
+        return a.n_items <= (int64_t)64 * di.cus ? launch_tile<1, 2, 2, 1, 0>(a, stream) : launch_tile<1, 4, 2, 1, 0>(a, stream);
+    }
     if (small_tiles) return a.rows <= 128 ? launch_tile<2, 2, 2, 2, 0>(a, stream) : launch_tile<2, 2, 2, 2, 1>(a, stream);
     // Up to 128 hidden rows the work is bound by streaming M once: small tiles, two workgroups per
     // CU.  Beyond that the 256 x 256 tile halves the operand traffic per multiply-add -- unless rounding

@@ -79,6 +79,9 @@ LOGIT_SHAPES = [
     ("bf16", 1, 3840, 9000, 4000, "per_row"),    # one row, a few thousand items: eight-wavefront workgroups, clamped loads
     ("f32", 1, 1536, 6000, 3001, "per_row"),     # the same in float32, odd item count
     ("bf16", 16, 64, 600000, 300, "per_row"),    # a vocabulary beyond the ordered union: ranges reserved by atomics
+    ("bf16", 24, 520, 9000, 8500, "per_step"),   # 17 to 32 rows, mid-size list: 32 x 64 tiles, ragged last tile and slice
+    ("bf16", 50, 264, 6000, 5500, "per_step"),   # 33 to 64 rows, up to 64 x CUs items: 64 x 64 tiles
+    ("bf16", 20, 64, 100000, 95000, "per_step"), # 17 to 32 rows, a long list: back on the kernel without LDS tiles
 ]
 
 
