@@ -396,10 +396,10 @@ hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream) {
         if (a.rows <= 16) return launch_ksplit<1>(a, 0, 1, stream);
         return launch_ksplit<2>(a, 0, (a.rows + 31) / 32, stream);
     }
-    // 33 to 64 hidden rows: the LDS-tiled kernel (whole 128-byte lines per request, several small workgroups per
-    // CU).  Measured over list lengths from 6144 to 128256 items at 36, 48 and 60 rows it is as fast as or faster
-    // than eight wavefronts of this kernel with 16 rows of M each (60 rows: 16384 items 37 against 56 us, 32768
-    // 60 against 66, 81920 144 against 155, 128256 202 against 204).
+    // 33 to 64 hidden rows: the LDS-tiled kernel (whole 128-byte lines per request; it picks its tile by the
+    // list's length).  Measured over list lengths from 6144 to 128256 items at 36, 48 and 60 rows it is as fast
+    // as or faster than eight wavefronts of this kernel with 16 rows of M each (60 rows: 16384 items 37 against
+    // 56 us, 32768 60 against 66, 81920 144 against 155).
     if (a.rows > 32) return launch_tile_mfma(a, stream);
     // 17 to 32 hidden rows: the LDS-tiled kernel on 32 x 64 tiles wins in the middle -- 3 to 15 % between 12288 and
     // 81920 items (32 rows: 24576 items 48 against 55 us, 40960 71 against 79, 81920 127 against 131), equal at

@@ -634,6 +634,7 @@ hipError_t configure_tile_mfma_lds() {
         if (e == hipSuccess) e = fn(std::integral_constant<int, EPI_BRACKET>{});
         if (e == hipSuccess) e = fn(std::integral_constant<int, EPI_PICK>{});
     };
+    if (e == hipSuccess) e = opt_in_lds<1, 8, 2, 1, 0, EPI_STORE>();
     if (e == hipSuccess) e = opt_in_lds<2, 4, 2, 2, 0, EPI_STORE>();
     all_epilogues([](auto ec) { return opt_in_lds<2, 2, 2, 2, 0, decltype(ec)::value>(); });
     all_epilogues([](auto ec) { return opt_in_lds<2, 2, 2, 2, 1, decltype(ec)::value>(); });
@@ -689,15 +690,20 @@ hipError_t launch_tile_mfma(const GemvArgs& a, hipStream_t stream, bool small_ti
     if (a.n_items <= 0 || a.rows <= 0) return hipSuccess;
     // Up to 64 hidden rows (the caller decides when this beats the kernel without LDS tiles) the product is one
     // pass over M at the rate of the memory system, and what matters is how evenly the list's items spread over
-    // the chip: small tiles, several workgroups per CU.  32 x 64 tiles (two wavefronts, five workgroups per CU) up
-    // to 32 rows; 64 x 64 (four per CU) for lists of up to 64 x CUs items and 64 x 128 (four wavefronts, two per
-    // CU) beyond, measured at 60 rows against 64 x 256 tiles with one workgroup of eight wavefronts per CU: 16384
-    // items 37 / 44 / 61 us, 32768 59 / 60 / 76, 50200 103 / 93 / 95, 81920 150 / 144 / 161, 128256 213 / 201 / 206.
+    // the chip.  17 to 32 rows: 32 x 64 tiles (two wavefronts, five workgroups per CU).  33 to 64 rows: 64 x 256
+    // tiles (eight wavefronts, one workgroup per CU) stream best when the list fills its last round of 256 x CUs
+    // items, or more than half of it (a tree step of 60 rows over 50223 rows of U: 110 against 113 us with the
+    // tiles below; all 128256 rows: 197 against 200) -- and for a count on the device, which such a tree step has;
+    // otherwise small tiles with several workgroups per CU: 64 x 64 (four per CU) up to 64 x CUs items, 64 x 128
+    // (four wavefronts, two per CU) beyond.  60 rows, 64 x 64 / 64 x 128 / 64 x 256: 16384 items 37 / 44 / 61 us,
+    // 32768 59 / 60 / 76, 81920 150 / 144 / 161, 98304 186 / 160 / 170.
     if (a.rows <= 32) return launch_tile<1, 2, 1, 1, 0>(a, stream);
     if (a.rows <= 64) {
         DeviceInfo di;
         const hipError_t e = device_info(&di);
         if (e != hipSuccess) return e;
+        const int64_t round_items = (int64_t)256 * di.cus, last = a.n_items % round_items;
+        if (a.n_items_dev != nullptr || last == 0 || 2 * last > round_items) return launch_tile<1, 8, 2, 1, 0>(a, stream);
         return a.n_items <= (int64_t)64 * di.cus ? launch_tile<1, 2, 2, 1, 0>(a, stream) : launch_tile<1, 4, 2, 1, 0>(a, stream);
     }
     if (small_tiles) return a.rows <= 128 ? launch_tile<2, 2, 2, 2, 0>(a, stream) : launch_tile<2, 2, 2, 2, 1>(a, stream);
