@@ -148,6 +148,17 @@ def other_configs(sv, torch, np, dev, capture, timed_replays):
                              "speedup_vs_dense": round(dense_us / step_us, 2),
                              "unique_rows_per_step": round(uniq), "unique_row_MB": round(uniq * c.d * 2 / 1e6, 1),
                              "dense_frac_hbm_peak": round(c.V * c.d * 2 / (dense_us * 1e-6) / 8e12, 3)}
+    # the same tree with sets that overlap more (slices of the lists above: their shared part comes first), so that
+    # the union is a few thousand rows -- its size is known on the device only, which picks the kernel there
+    over = []
+    for lo, kk in ((0, 1024), (1500, 1024), (1500, 2048)):
+        idx_o = idx[:, :, lo:lo + kk].contiguous()
+        z_o = torch.empty((c.rows, kk), dtype=torch.float32, device=dev)
+        us = med_us(lambda t: sv.draft_step(h[t % nst], U, idx_o[t % nst], c.kd, logits_out=z_o, tok_out=tok,
+                                            prob_out=prob), 20)
+        uq = float(np.mean([np.unique(idx_o[t].cpu().numpy()).size for t in range(nst)]))
+        over.append({"k": kk, "unique_rows_per_step": round(uq), "step_us": round(us, 1)})
+    out["config3_tree60"]["sets_that_overlap_more"] = over
     # the same shape with selection, at the width of one level of a small draft tree (8 rows) and at 60:
     # the selector has random weights, so its sets are timed, and the draft step runs on config 3's recipe
     from workloads import tree_subsets

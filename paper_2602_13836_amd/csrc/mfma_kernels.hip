@@ -66,7 +66,7 @@ __global__ __launch_bounds__(WPB * 64) void skinny_mfma_kernel(SV_HOT_PARAMS, co
     const int nslices = (C * 8 + kKC - 1) / kKC;
     const int rows_here = min(a.rows - row0, N);
     const int64_t n_items = a.n_items_dev ? (int64_t)*a.n_items_dev : a.n_items;
-    if ((int64_t)blockIdx.x * WPB * 16 >= n_items) return;        // whole workgroup past the end
+    if ((int64_t)blockIdx.x * WPB * 16 >= n_items || !gate_open(a, n_items)) return;   // past the end / not this launch's list
 
     const int64_t tile0 = ((int64_t)blockIdx.x * WPB + wave) * 16;
     int64_t item = tile0 + i;
@@ -204,7 +204,7 @@ __global__ __launch_bounds__(512) void skinny_mfma_ksplit_kernel(SV_HOT_PARAMS, 
     const int rows_here = min(a.rows - row0, N);
     const int64_t n_items = a.n_items_dev ? (int64_t)*a.n_items_dev : a.n_items;
     const int64_t tile0 = (int64_t)blockIdx.x * 16;
-    if (tile0 >= n_items || rows_here <= 0) return;
+    if (tile0 >= n_items || rows_here <= 0 || !gate_open(a, n_items)) return;
 
     int64_t item = tile0 + i;
     if (item > n_items - 1) item = n_items - 1;
@@ -392,6 +392,33 @@ hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream) {
     // (d = 4096) between 4096 and 6144 items, where a single tile of the LDS-tiled kernel takes 35 us whatever
     // the list's length (4096 items: 26 against 35 us; 6144: 39 against 35; 8192: 50 against 35).
     const int64_t split_items = (int64_t)di.cus * (a.rows <= 4 ? 64 : a.rows <= 8 ? 48 : a.rows <= 32 ? 32 : 20);
+    // A count on the device (the union of the rows' sets; a.n_items is its upper bound, often several times the
+    // count when the sets overlap) that may fall on either side of such a crossover: launches with complementary
+    // gates, of which those that do not serve the list leave at once (about 2 us each).  The crossovers that matter:
+    // the one above, and from 33 rows the one between 64 x 64 tiles and larger ones at 64 x CUs items (the tiled
+    // kernel picks its tile by n_items, here the upper end of the gate).  60 rows whose 512 / 1024-item sets unite to
+    // 553 / 1401 rows: whole step 31 / 33 us, against 64 / 66 with the kernel picked by the bound.
+    if (a.n_items_dev != nullptr && a.gate_hi == 0 && a.n_items > split_items && a.chunks >= 8 * (kKC / 8)) {
+        int64_t cuts[2];
+        int ncuts = 0;
+        // (a union of duplicate-free sets of k items has at least k: from three quarters of the crossover on, the
+        // split form has nothing left to win -- 4096 items 26 us against 35 on one tile, 5120 items 33)
+        if (4 * a.n_items_min < 3 * split_items) cuts[ncuts++] = split_items;
+        if (a.rows > 32 && a.n_items > (int64_t)di.cus * 64) cuts[ncuts++] = (int64_t)di.cus * 64;
+        if (ncuts > 0) {
+            GemvArgs part = a;
+            for (int c = 0; c < ncuts; ++c) {
+                part.n_items = cuts[c];               // sizes the grid: enough for every list this launch serves
+                part.gate_hi = cuts[c];
+                e = launch_skinny_mfma(part, stream);
+                if (e != hipSuccess) return e;
+                part.gate_lo = cuts[c];
+            }
+            part.n_items = a.n_items;
+            part.gate_hi = INT64_MAX;
+            return launch_skinny_mfma(part, stream);
+        }
+    }
     if (a.n_items <= split_items && a.chunks >= 8 * (kKC / 8)) {
         if (a.rows <= 16) return launch_ksplit<1>(a, 0, 1, stream);
         return launch_ksplit<2>(a, 0, (a.rows + 31) / 32, stream);

@@ -50,7 +50,16 @@ struct GemvArgs {
                                    // the place of an item in the list may differ from run to run)
     int64_t m_rows;                // number of rows of M that idx may name, 0 if the caller does not say (a kernel that
                                    // keeps row offsets in 32 bits is then not used with an index list)
+    int64_t n_items_min;           // with a count on the device: what the count is expected to reach at least (a hint that
+                                   // saves launches, 0 if the caller has none; a smaller count is still served correctly)
+    int64_t gate_lo, gate_hi;      // matrix-core kernels with a count on the device, if gate_hi != 0: the launch does its
+                                   // work only if gate_lo < count <= gate_hi and leaves at once otherwise (two launches
+                                   // with complementary gates let the device pick the kernel that fits the count)
 };
+// true if this launch is the one that serves a list of n_items items
+__device__ __forceinline__ bool gate_open(const GemvArgs& a, int64_t n_items) {
+    return a.gate_hi == 0 || (n_items > a.gate_lo && n_items <= a.gate_hi);
+}
 // what a launch does for later kernels besides its product: every thread of the grid calls this once
 __device__ __forceinline__ void prepare_scratch(const GemvArgs& a) {
     if (a.zero_words == 0 && a.spread_n == 0) return;

@@ -123,7 +123,7 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
     const int64_t slot = blockIdx.x / kXcds;
     const int rt = (int)(slot % RT);
     const int64_t it = (slot / RT) * kXcds + (blockIdx.x % kXcds);
-    if (it >= IT) return;
+    if (it >= IT || !gate_open(a, n_items)) return;
 
     // loader role: 8 threads cover the 128-byte slice of one row, 32 rows per pass
     const int piece = tid & 7, r0 = tid >> 3;
@@ -703,7 +703,9 @@ hipError_t launch_tile_mfma(const GemvArgs& a, hipStream_t stream, bool small_ti
         const hipError_t e = device_info(&di);
         if (e != hipSuccess) return e;
         const int64_t round_items = (int64_t)256 * di.cus, last = a.n_items % round_items;
-        if (a.n_items_dev != nullptr || last == 0 || 2 * last > round_items) return launch_tile<1, 8, 2, 1, 0>(a, stream);
+        // (with a count on the device a.n_items is its upper bound: at most half a round, and the list is short for sure)
+        const bool unknown = a.n_items_dev != nullptr && 2 * a.n_items > round_items;
+        if (unknown || last == 0 || 2 * last > round_items) return launch_tile<1, 8, 2, 1, 0>(a, stream);
         return a.n_items <= (int64_t)64 * di.cus ? launch_tile<1, 2, 2, 1, 0>(a, stream) : launch_tile<1, 4, 2, 1, 0>(a, stream);
     }
     if (small_tiles) return a.rows <= 128 ? launch_tile<2, 2, 2, 2, 0>(a, stream) : launch_tile<2, 2, 2, 2, 1>(a, stream);

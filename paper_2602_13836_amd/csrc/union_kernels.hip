@@ -385,6 +385,7 @@ hipError_t launch_union_logits(const GemvArgs& a, int64_t V, void* ws, hipStream
     u.idx_row_stride = 0;
     u.n_items = w.zu_stride;                              // upper bound: sizes the grid
     u.n_items_dev = w.counter;
+    u.n_items_min = k;                                    // every row's k items are in the union
     u.plain_order = ordered ? 0 : 1;                      // a list in run-dependent order: no rotated reduction
     u.out_f32 = w.zu;
     u.out_row_stride = w.zu_stride;
