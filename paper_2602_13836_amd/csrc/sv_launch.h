@@ -52,6 +52,8 @@ struct GemvArgs {
                                    // keeps row offsets in 32 bits is then not used with an index list)
     int64_t n_items_min;           // with a count on the device: what the count is expected to reach at least (a hint that
                                    // saves launches, 0 if the caller has none; a smaller count is still served correctly)
+    int balance_cus;               // LDS-tiled kernel, product stored: if > 0, the width of an item tile shrinks (in steps
+                                   // of 32 items) so that the list's tiles fill whole rounds of this many workgroups
     int64_t gate_lo, gate_hi;      // matrix-core kernels with a count on the device, if gate_hi != 0: the launch does its
                                    // work only if gate_lo < count <= gate_hi and leaves at once otherwise (two launches
                                    // with complementary gates let the device pick the kernel that fits the count)

@@ -118,12 +118,25 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
     const int nk = (C + 7) / 8;
     const int64_t n_items = a.n_items_dev ? (int64_t)*a.n_items_dev : a.n_items;
     const int RT = (a.rows + TM - 1) / TM;
-    const int64_t IT = (n_items + TN - 1) / TN;
+    // Width of an item tile: TN, or (a.balance_cus workgroups at a time, product stored) the smallest multiple of
+    // 32 with which the list still takes as many rounds of workgroups as with TN -- 50223 items on 256 CUs: 225
+    // tiles of 224 items instead of 197 of 256.  The wavefronts past that width multiply copies of the tile's last
+    // row and store nothing.
+    int64_t tn = TN;
+    if (EPI == EPI_STORE && a.balance_cus > 0 && n_items > 0) {
+        const int64_t per_round = (int64_t)TN * a.balance_cus;
+        const int64_t rounds = (n_items + per_round - 1) / per_round;
+        const int64_t lanes32 = (int64_t)32 * a.balance_cus * rounds;
+        tn = 32 * ((n_items + lanes32 - 1) / lanes32);
+    }
+    const int64_t IT = (n_items + tn - 1) / tn;
     // block id -> (XCD, slot on that XCD); consecutive slots of one XCD: the RT hidden-row tiles of one item tile
     const int64_t slot = blockIdx.x / kXcds;
     const int rt = (int)(slot % RT);
     const int64_t it = (slot / RT) * kXcds + (blockIdx.x % kXcds);
     if (it >= IT || !gate_open(a, n_items)) return;
+    const int64_t tile0 = it * tn;
+    const int64_t tile_end = tile0 + tn < n_items ? tile0 + tn : n_items;
 
     // loader role: 8 threads cover the 128-byte slice of one row, 32 rows per pass
     const int piece = tid & 7, r0 = tid >> 3;
@@ -137,8 +150,8 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
     }
 #pragma unroll
     for (int q = 0; q < QB; ++q) {
-        int64_t item = it * TN + r0 + kRowsPerPass * q;
-        if (item > n_items - 1) item = n_items - 1;
+        int64_t item = tile0 + r0 + kRowsPerPass * q;
+        if (item > tile_end - 1) item = tile_end - 1;
         const int64_t mrow = a.idx ? (int64_t)a.idx[item] : item;
         pb[q] = reinterpret_cast<const u32x4*>(a.M + mrow * a.m_row_bytes);
     }
@@ -417,7 +430,7 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
     }
 
     // D[i][j]: j = lane % 32 (item), i = 8 (e / 4) + 4 (lane / 32) + e % 4 (hidden row) for element e
-    const int64_t item0 = it * TN + wc * 32 * WN + (lane & 31);
+    const int64_t item0 = tile0 + wc * 32 * WN + (lane & 31);
     const int row0 = rt * TM + wr * 32 * WM + 4 * (lane >> 5);
     if constexpr (EPI == EPI_PICK) {
         // Band by band (the 32 GM rows that the wavefronts hold in the same accumulator group) the product goes
@@ -588,7 +601,7 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
 #pragma unroll
         for (int n = 0; n < WN; ++n) {
             const int64_t item = item0 + 32 * n;
-            if (item >= n_items) continue;
+            if (item >= tile_end) continue;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int r = row0 + 32 * m + 8 * (e >> 2) + (e & 3);
@@ -613,7 +626,9 @@ hipError_t launch_tile(const GemvArgs& a, hipStream_t stream, const BracketEpi& 
                        const PickEpi& pk = PickEpi{}) {
     constexpr int TM = 32 * GM * WM, TN = 32 * GN * WN;
     const int64_t RT = (a.rows + TM - 1) / TM;
-    const int64_t IT = (a.n_items + TN - 1) / TN;
+    int64_t IT = (a.n_items + TN - 1) / TN;
+    if (EPI == EPI_STORE && a.balance_cus > 0)                  // narrower tiles: whole rounds of balance_cus workgroups
+        IT = (IT + a.balance_cus - 1) / a.balance_cus * a.balance_cus;
     const int64_t groups = (IT + kXcds - 1) / kXcds;            // item tiles per XCD, rounded up
     const int64_t bx = groups * RT * kXcds;
     if (bx > 0x7fffffffLL) return hipErrorInvalidValue;         // more tiles than a grid dimension holds
@@ -705,7 +720,13 @@ hipError_t launch_tile_mfma(const GemvArgs& a, hipStream_t stream, bool small_ti
         const int64_t round_items = (int64_t)256 * di.cus, last = a.n_items % round_items;
         // (with a count on the device a.n_items is its upper bound: at most half a round, and the list is short for sure)
         const bool unknown = a.n_items_dev != nullptr && 2 * a.n_items > round_items;
-        if (unknown || last == 0 || 2 * last > round_items) return launch_tile<1, 8, 2, 1, 0>(a, stream);
+        if (unknown || last == 0 || 2 * last > round_items) {
+            // ... of a width that fills whole rounds of workgroups (40960 items: 80 against 87 us; unions of 30940 and
+            // 44831 rows: a tree step in 82 and 104 us against 88 and 109)
+            GemvArgs b = a;
+            b.balance_cus = di.cus;
+            return launch_tile<1, 8, 2, 1, 0>(b, stream);
+        }
         return a.n_items <= (int64_t)64 * di.cus ? launch_tile<1, 2, 2, 1, 0>(a, stream) : launch_tile<1, 4, 2, 1, 0>(a, stream);
     }
     if (small_tiles) return a.rows <= 128 ? launch_tile<2, 2, 2, 2, 0>(a, stream) : launch_tile<2, 2, 2, 2, 1>(a, stream);
