@@ -109,6 +109,28 @@ def test_subset_and_dense_logits(dtype, rows, d, V, k, mode):
     assert_logits_close(z, oracle.subset_logits(h, U, idx, acc="f64"), dtype, "subset logits vs f64")
 
 
+@pytest.mark.parametrize("rows,d,V,k,pool", [
+    (40, 264, 50000, 900, 3000),     # bound 36000, union <= 3000: the launch gated for the reduction-split form serves it
+    (40, 264, 50000, 900, 9000),     # union ~8900: the launch gated for 64 x 64 tiles
+    (40, 264, 50000, 900, 50000),    # union ~26000: the launch picked by the bound, both others leave
+    (60, 136, 90000, 4096, 4600),    # sets longer than three quarters of the first crossover: that gate is not launched
+    (24, 264, 50000, 900, 2500),     # up to 32 rows: one gate
+    (24, 264, 50000, 900, 50000),
+    (8, 4096, 40000, 8192, 9000),    # few rows, 512 MB of pairs: union path with the gates of 8 rows
+])
+def test_union_size_known_on_device_only(rows, d, V, k, pool):
+    """One set per row whose union is much smaller than rows x k (or not): whichever gated launch serves it,
+    the logits are those of the oracle."""
+    say(f"union on device rows={rows} d={d} V={V} k={k} pool={pool}")
+    rng = np.random.default_rng(rows * 1000 + pool)
+    U = rand(rng, (V, d), 0.02, "bf16")
+    h = rand(rng, (rows, d), 1.0, "bf16")
+    members = rng.permutation(V)[:pool]
+    idx = np.stack([rng.permutation(members)[:k] for _ in range(rows)]).astype(np.int32)
+    z = sv.subset_logits(to_dev(h), to_dev(U), torch.from_numpy(idx).to(DEV)).cpu().numpy()
+    assert_logits_close(z, oracle.subset_logits(h, U, idx), "bf16", "subset logits")
+
+
 @pytest.mark.parametrize("rows,d,V,k", [
     (3, 512, 700, 200),          # row kernel
     (1, 4096, 600, 200),         # one row per wavefront, whole 8 KiB rows inside a wider matrix
