@@ -139,12 +139,14 @@ int validate_indices(const int32_t* idx, int64_t n, int64_t V, hipStream_t s, bo
 //   several hidden rows sharing one set of rows of M  -> matrix cores, M read once
 //   several hidden rows with their own sets           -> union of the sets, then matrix cores
 //   otherwise (one hidden row, float32, small cases)  -> row-gather kernel
-int launch_rows_product(int dt, const sv::GemvArgs& g, int64_t V, void* ws, size_t ws_bytes, hipStream_t s) {
+// defer != nullptr: the caller can do the union path's pick itself (see sv::DeferredPick; untouched on other paths)
+int launch_rows_product(int dt, const sv::GemvArgs& g, int64_t V, void* ws, size_t ws_bytes, hipStream_t s,
+                        sv::DeferredPick* defer = nullptr) {
     if (sv::skinny_mfma_supported(dt, g)) return sv::launch_skinny_mfma(g, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
     if (sv::union_path_wanted(dt, g)) {
         if (!ws || ws_bytes < sv::union_ws_bytes(g.rows, V, g.n_items)) return SV_ERR_WORKSPACE;
         if (!aligned16(ws)) return SV_ERR_ALIGN;
-        return sv::launch_union_logits(g, V, ws, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
+        return sv::launch_union_logits(g, V, ws, s, defer) == hipSuccess ? SV_OK : SV_ERR_HIP;
     }
     return sv::launch_gemv(dt, g, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
 }
@@ -199,7 +201,7 @@ size_t gather_ws_bytes(int64_t rows, int64_t d, int64_t V, int64_t k, int dt, in
 // paths stay exactly as they are for plain lists.
 int launch_gather(int dt, const void* h, int64_t rows, int64_t d, int64_t ldh, const void* U, int64_t V,
                   int64_t ldu, const int32_t* idx, int64_t k, int idx_mode, float* logits_out, void* ws,
-                  size_t ws_bytes, hipStream_t s) {
+                  size_t ws_bytes, hipStream_t s, sv::DeferredPick* defer = nullptr) {
     const bool padded = is_padded(idx_mode);
     const int64_t sets = base_mode(idx_mode) == SV_IDX_PER_ROW ? rows : 1;
     const sv::GemvArgs g0 = gather_args(h, rows, d, ldh, U, V, ldu, dt, idx, k, idx_mode, logits_out);
@@ -230,7 +232,7 @@ int launch_gather(int dt, const void* h, int64_t rows, int64_t d, int64_t ldh, c
     if (sv::pick_path_wanted(dt, g, V, is_sorted(idx_mode)))
         st = sv::launch_pick_logits(g, V, is_sorted(idx_mode), rest, s) == hipSuccess ? SV_OK : SV_ERR_HIP;
     else
-        st = launch_rows_product(dt, g, V, rest_bytes ? rest : nullptr, rest_bytes, s);
+        st = launch_rows_product(dt, g, V, rest_bytes ? rest : nullptr, rest_bytes, s, copy ? nullptr : defer);
     if (st != SV_OK) return st;
     if (copy && sv::launch_pad_mask(idx, g.idx_row_stride, (int)rows, k, logits_out, s) != hipSuccess)
         return SV_ERR_HIP;
@@ -664,8 +666,19 @@ int specvocab_draft_step(const void* h, int64_t rows, int64_t d, int64_t ldh, co
     t.prob_out = prob_out;
     t.probs_full_out = probs_full_out;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    st = launch_gather(dt, h, rows, d, ldh, U, V, ldu, idx, k, idx_mode, logits_out, ws, ws_bytes, s);
+    // on the union path (one set per row) the top-k kernel picks each row's logits from the union's product
+    // itself and writes logits_out on the way: one launch and one pass over the logits less
+    sv::DeferredPick pick{};
+    const bool can_pick = !is_padded(idx_mode) && sv::softmax_topk_can_pick(t);
+    st = launch_gather(dt, h, rows, d, ldh, U, V, ldu, idx, k, idx_mode, logits_out, ws, ws_bytes, s,
+                       can_pick ? &pick : nullptr);
     if (st != SV_OK) return st;
+    if (pick.pos) {
+        t.pick_pos = pick.pos;
+        t.pick_zu = pick.zu;
+        t.pick_zu_stride = pick.zu_stride;
+        t.pick_logits_out = logits_out;
+    }
     if (sv::launch_softmax_topk(t, s) != hipSuccess) return SV_ERR_HIP;
     return SV_OK;
 }

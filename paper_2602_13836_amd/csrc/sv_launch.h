@@ -150,7 +150,15 @@ size_t pick_ws_bytes(int64_t rows, int64_t V, int64_t k, bool sorted);
 hipError_t launch_pick_logits(const GemvArgs& a, int64_t V, bool sorted, void* ws, hipStream_t stream);
 bool union_path_wanted(int dt, const GemvArgs& a);
 size_t union_ws_bytes(int64_t rows, int64_t V, int64_t k);
-hipError_t launch_union_logits(const GemvArgs& a, int64_t V, void* ws, hipStream_t stream);
+// the last step of the union path when the caller leaves it to a later kernel (the top-k kernel of a draft step):
+// logit[r, j] = zu[r * zu_stride + pos[idx[r, j]]]
+struct DeferredPick {
+    const uint32_t* pos;
+    const float* zu;
+    int64_t zu_stride;
+};
+// defer != nullptr: everything but the pick is launched, *defer says what is left to do (a.out_f32 stays unwritten)
+hipError_t launch_union_logits(const GemvArgs& a, int64_t V, void* ws, hipStream_t stream, DeferredPick* defer = nullptr);
 
 // s[r, v] = < W_vocab[v, :], hp[r, :] > for short rows (d_prime * esize <= 1024 bytes), fused with the
 // first histogram pass of the top-k selection
@@ -220,7 +228,16 @@ struct TopkArgs {
     int32_t* tok_out;
     float* prob_out;
     float* probs_full_out;
+    // optional: the logits are not there yet but picked by this launch from the product over the union of the rows'
+    // sets, logit[r, j] = pick_zu[r * pick_zu_stride + pick_pos[idx[r, j]]], and written to pick_logits_out (the
+    // same [rows x k] array that `logits` names)
+    const uint32_t* pick_pos;
+    const float* pick_zu;
+    int64_t pick_zu_stride;
+    float* pick_logits_out;
 };
 hipError_t launch_softmax_topk(const TopkArgs& a, hipStream_t stream);
+// true if launch_softmax_topk can do the pick itself for these arguments (pick_* not looked at)
+bool softmax_topk_can_pick(const TopkArgs& a);
 
 }  // namespace sv

@@ -32,8 +32,11 @@ constexpr int kCap = 512;                    // candidate list capacity
 // bytes -- are not read up front: candidates carry their position and only the few of them fetch
 // their token (one more round trip, a quarter of a megabyte less at k = 32768).
 constexpr int kDeferFrom = 16;
-template <int M, bool VEC>
+// PICK (registers, tokens read up front): the row's logits are picked from the product over the union of the rows' sets -- entry j is
+// a.pick_zu[r, a.pick_pos[idx[j]]] -- and written out as the logits row on the way.
+template <int M, bool VEC, bool PICK = false>
 __device__ __forceinline__ void softmax_topk_block(const TopkArgs& a, const int64_t r) {
+    static_assert(!PICK || (M > 0 && M < kDeferFrom), "the picking form keeps logits and tokens in registers");
     __shared__ __attribute__((aligned(16))) uint32_t s_rowmax[kRows16];   // exact row maxima
     __shared__ __attribute__((aligned(16))) uint32_t s_rowtag[kRows16];   // made unique: low 6 bits = 63 - row
     __shared__ uint64_t s_cand[kCap];
@@ -67,8 +70,19 @@ __device__ __forceinline__ void softmax_topk_block(const TopkArgs& a, const int6
             const int64_t j0 = (int64_t)q * (4 * kThreads) + 4 * tid;
             u32x4 zz = zero16(), tt = zero16();
             if (j0 < k) {
-                zz = *reinterpret_cast<const u32x4*>(z + j0);
-                if constexpr (!DEFER) tt = *reinterpret_cast<const u32x4*>(idx + j0);
+                if constexpr (PICK) {
+                    tt = *reinterpret_cast<const u32x4*>(idx + j0);
+                    const float* zu = a.pick_zu + r * a.pick_zu_stride;
+                    uint32_t at[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) at[e] = a.pick_pos[tt[e]];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) zz[e] = __float_as_uint(zu[at[e]]);
+                    *reinterpret_cast<u32x4*>(a.pick_logits_out + r * k + j0) = zz;
+                } else {
+                    zz = *reinterpret_cast<const u32x4*>(z + j0);
+                    if constexpr (!DEFER) tt = *reinterpret_cast<const u32x4*>(idx + j0);
+                }
             }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -81,8 +95,19 @@ __device__ __forceinline__ void softmax_topk_block(const TopkArgs& a, const int6
 #pragma unroll
         for (int i = 0; i < M; ++i) {
             const int64_t j = (int64_t)i * kThreads + tid;
-            key[i] = j < k ? f32_to_ord(z[j]) : 0u;          // 0 = no element (finite keys are larger)
-            if constexpr (!DEFER) tk[i] = j < k ? idx[j] : 0;
+            if constexpr (PICK) {
+                tk[i] = j < k ? idx[j] : 0;
+                if (j < k) {
+                    const float f = a.pick_zu[r * a.pick_zu_stride + a.pick_pos[tk[i]]];
+                    a.pick_logits_out[r * k + j] = f;
+                    key[i] = f32_to_ord(f);
+                } else {
+                    key[i] = 0u;
+                }
+            } else {
+                key[i] = j < k ? f32_to_ord(z[j]) : 0u;      // 0 = no element (finite keys are larger)
+                if constexpr (!DEFER) tk[i] = j < k ? idx[j] : 0;
+            }
             lmax = key[i] > lmax ? key[i] : lmax;
         }
     } else {

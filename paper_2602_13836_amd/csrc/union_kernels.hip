@@ -356,7 +356,7 @@ size_t union_ws_bytes(int64_t rows, int64_t V, int64_t k) {
     return (4 + flag_words(V) + 2 * vpad + (size_t)rows * (size_t)union_cap(rows, V, k)) * sizeof(uint32_t);
 }
 
-hipError_t launch_union_logits(const GemvArgs& a, int64_t V, void* ws, hipStream_t stream) {
+hipError_t launch_union_logits(const GemvArgs& a, int64_t V, void* ws, hipStream_t stream, DeferredPick* defer) {
     DeviceInfo di;
     hipError_t e = device_info(&di);
     if (e != hipSuccess) return e;
@@ -391,6 +391,12 @@ hipError_t launch_union_logits(const GemvArgs& a, int64_t V, void* ws, hipStream
     u.out_row_stride = w.zu_stride;
     e = launch_skinny_mfma(u, stream);
     if (e != hipSuccess) return e;
+    if (defer) {
+        defer->pos = w.pos;
+        defer->zu = w.zu;
+        defer->zu_stride = w.zu_stride;
+        return hipSuccess;
+    }
 
     unsigned pb = (unsigned)((k + 1023) / 1024);              // four entries per thread
     if ((int64_t)pb * a.rows > (int64_t)di.cus * 16) pb = (unsigned)(((int64_t)di.cus * 16 + a.rows - 1) / a.rows);

@@ -371,6 +371,13 @@ STEP_SHAPES = [
     ("bf16", 1, 4096, 20000, 8192, 64, "per_row"),
     ("bf16", 2, 512, 3000, 1001, 5, "per_row"),
     ("bf16", 65, 256, 2000, 64, 3, "per_step"),
+    # one set per row, union path: the top-k kernel picks the logits from the union's product itself
+    ("bf16", 20, 520, 30000, 4096, 10, "per_row"),    # four entries per thread
+    ("bf16", 16, 264, 9000, 2052, 7, "per_row"),      # groups of four, half of the threads without entries
+    ("bf16", 16, 264, 9000, 1201, 7, "per_row"),      # two entries per thread, odd length
+    ("bf16", 24, 264, 9000, 700, 64, "per_row"),      # one entry per thread, kd = 64
+    ("bf16", 18, 136, 40000, 8192, 64, "per_row"),    # eight entries per thread
+    ("bf16", 16, 264, 9000, 4098, 7, "per_row"),      # k no multiple of four: the pick stays a launch of its own
 ]
 
 
