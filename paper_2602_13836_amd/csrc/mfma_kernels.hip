@@ -1,6 +1,7 @@
 // Skinny matrix product on the matrix cores for several hidden-state rows at once:
-//     out[r, j] = < M[row(j), :], x[r, :] >      r < rows (<= 64 per pass), j < n_items
-// (from 33 rows on the launcher at the end of this file hands full CU-rounds of items to the LDS-tiled kernel)
+//     out[r, j] = < M[row(j), :], x[r, :] >      r < rows (<= 32), j < n_items
+// (the launcher at the end of this file hands more rows, and mid-size lists from 17 rows on, to the LDS-tiled kernel;
+// the form that splits the reduction serves short lists at up to 64 rows)
 // with row(j) = j (the full-vocabulary projection of Section 3.1) or row(j) = idx[j] (Section 3.3
 // Step 3 with one index set shared by every row of the step).  bf16 storage only.
 //
@@ -312,8 +313,6 @@ template <int WPB>
 hipError_t opt_in_lds_all_nb() {
     hipError_t e = opt_in_lds<WPB, 1>();
     if (e == hipSuccess) e = opt_in_lds<WPB, 2>();
-    if (e == hipSuccess) e = opt_in_lds<WPB, 3>();
-    if (e == hipSuccess) e = opt_in_lds<WPB, 4>();
     return e;
 }
 
@@ -338,9 +337,7 @@ hipError_t launch_wn(const GemvArgs& a, int row0, hipStream_t stream) {
 template <int WPB>
 hipError_t launch_w(const GemvArgs& a, int row0, int nrows, hipStream_t stream) {
     if (nrows <= 16) return launch_wn<WPB, 1>(a, row0, stream);
-    if (nrows <= 32) return launch_wn<WPB, 2>(a, row0, stream);
-    if (nrows <= 48) return launch_wn<WPB, 3>(a, row0, stream);
-    return launch_wn<WPB, 4>(a, row0, stream);
+    return launch_wn<WPB, 2>(a, row0, stream);               // (launch_skinny_mfma keeps up to 32 hidden rows here)
 }
 
 }  // namespace
@@ -350,7 +347,6 @@ hipError_t launch_w(const GemvArgs& a, int row0, int nrows, hipStream_t stream) 
 hipError_t configure_skinny_mfma_lds() {
     hipError_t e = opt_in_lds_all_nb<2>();
     if (e == hipSuccess) e = opt_in_lds_all_nb<4>();
-    if (e == hipSuccess) e = opt_in_lds_all_nb<8>();
     return e;
 }
 
