@@ -62,9 +62,10 @@ def parse_args():
     p.add_argument("--counter-run", nargs="?", const="warm", choices=("warm", "cold"), default=None,
                    help="for rocprofv3 --pmc: 1 GiB reference copies, then a few eager (ungraphed) steps on one U "
                         "(warm) or on 8 rotating copies of U (cold); no timing, no JSON line")
-    p.add_argument("--trace-config", type=int, choices=(3, 4, 5), default=None,
+    p.add_argument("--trace-config", type=int, choices=(3, 4, 5, 30), default=None,
                    help="for rocprofv3 --kernel-trace: a few eager passes of that configuration (its draft step and "
-                        "the dense projection; config 5 also the selection), no timing, no JSON line")
+                        "the dense projection; config 5 also the selection; 30 = the tree of config 3 with sets that "
+                        "overlap more, draft steps only), no timing, no JSON line")
     return p.parse_args()
 
 
@@ -263,6 +264,19 @@ def trace_config(number, sv, torch, np, dev):
             run_dense()
         torch.cuda.synchronize()
         print("config 5 trace run done: 3 x (select, draft step, dense)", flush=True)
+        return
+    if number == 30:
+        c = CONFIGS[3]
+        U = dev_bf16(CONFIGS[2].weights())
+        h = dev_bf16(c.hidden(1)[0])
+        idx = torch.from_numpy(c.indices(1)[0]).to(dev)
+        for lo, kk in ((0, 1024), (1500, 1024), (1500, 2048)):        # the slices `sets_that_overlap_more` times
+            idx_o = idx[:, lo:lo + kk].contiguous()
+            for _ in range(5):
+                sv.draft_step(h, U, idx_o, c.kd)
+            torch.cuda.synchronize()
+            print(f"k={kk}: union of {int(torch.unique(idx_o).numel())} rows", flush=True)
+        print("config 3 with sets that overlap more, trace run done: per slice 5 x draft step", flush=True)
         return
     if number == 3:
         c = CONFIGS[3]
