@@ -160,12 +160,21 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
     // data has arrived anyway): without branches between them the compiler can count the loads in
     // flight and wait for exactly the oldest slice.
     // Workgroups walk the reduction in rotated order (slice ks of the walk is slice eff(ks) of the rows): rows a
-    // power of two apart put the same offset of every row on the same L2 channels, and workgroups that all
-    // start at offset 0 keep hitting the same channels together.  Consecutive workgroups of one XCD start one
-    // slice apart.
+    // power of two apart put the same offset of every row on the same memory channels, and workgroups that all
+    // start at offset 0 keep hitting the same channels together.  With up to 64 hidden rows (one row of
+    // wavefronts) consecutive workgroups of one XCD start 37 slices apart (modulo the number of slices): the
+    // starts of even a few dozen workgroups -- a launch of one
+    // workgroup per CU has 32 slots per XCD -- then spread over the whole row.  With starts one slice apart such a
+    // launch kept all its workgroups within the same 4 KB of their rows at any time: 60 rows x 50200 gathered
+    // rows of 8 KB 97 us against 88, x 65536 117 against 105, all 128256 rows 201 against 192-194 (rows padded
+    // to 8320 bytes had shown the same gain, which is how the channels were found out).
     // (Short reductions have nothing to spread.  a.plain_order: the place of an item in the list may vary from
     // run to run, and the order of a token's float32 additions must not.)
-    const int rot = nk >= 16 && !a.plain_order ? (int)(slot % nk) : 0;
+    // (Tiles of 128 and 256 hidden rows keep starts one slice apart: measured equal or better there, 512 rows 663
+    // against 693 us -- the hidden-row tiles of one item tile share the rows of M through their XCD's L2, and
+    // neighbouring item tiles that walk almost in step seem to help that.)
+    const int64_t rot_step = GM == 1 ? (nk % 37 ? 37 : 41) : 1;
+    const int rot = nk >= 16 && !a.plain_order ? (int)((slot * rot_step) % nk) : 0;
     auto eff = [&](int ks) { const int e = min(ks, nk - 1) + rot; return e >= nk ? e - nk : e; };
     auto load = [&](int ks, u32x4 (&ga)[QA], u32x4 (&gb)[QB]) {
         const int u = min(eff(ks) * 8 + piece, C - 1);
