@@ -161,8 +161,8 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
     // flight and wait for exactly the oldest slice.
     // Workgroups walk the reduction in rotated order (slice ks of the walk is slice eff(ks) of the rows): rows a
     // power of two apart put the same offset of every row on the same memory channels, and workgroups that all
-    // start at offset 0 keep hitting the same channels together.  With up to 64 hidden rows (one row of
-    // wavefronts) consecutive workgroups of one XCD start 37 slices apart (modulo the number of slices): the
+    // start at offset 0 keep hitting the same channels together.  With one tile of hidden rows (up to 128)
+    // consecutive workgroups of one XCD start 37 slices apart (modulo the number of slices): the
     // starts of even a few dozen workgroups -- a launch of one
     // workgroup per CU has 32 slots per XCD -- then spread over the whole row.  With starts one slice apart such a
     // launch kept all its workgroups within the same 4 KB of their rows at any time: 60 rows x 50200 gathered
@@ -170,10 +170,11 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
     // to 8320 bytes had shown the same gain, which is how the channels were found out).
     // (Short reductions have nothing to spread.  a.plain_order: the place of an item in the list may vary from
     // run to run, and the order of a token's float32 additions must not.)
-    // (Tiles of 128 and 256 hidden rows keep starts one slice apart: measured equal or better there, 512 rows 663
+    // (Several tiles of hidden rows keep starts one slice apart: measured equal or better there, 512 rows 663
     // against 693 us -- the hidden-row tiles of one item tile share the rows of M through their XCD's L2, and
-    // neighbouring item tiles that walk almost in step seem to help that.)
-    const int64_t rot_step = GM == 1 ? (nk % 37 ? 37 : 41) : 1;
+    // neighbouring item tiles that walk almost in step seem to help that.  One tile of 65 to 128 rows gains like
+    // the smaller ones: 100 rows x 50200 items 120 -> 112 us, 128 rows x 65536 135 -> 128.)
+    const int64_t rot_step = RT == 1 ? (nk % 37 ? 37 : 41) : 1;
     const int rot = nk >= 16 && !a.plain_order ? (int)((slot * rot_step) % nk) : 0;
     auto eff = [&](int ks) { const int e = min(ks, nk - 1) + rot; return e >= nk ? e - nk : e; };
     auto load = [&](int ks, u32x4 (&ga)[QA], u32x4 (&gb)[QB]) {
