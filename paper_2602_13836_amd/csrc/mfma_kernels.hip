@@ -391,8 +391,10 @@ hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream) {
     // A count on the device (the union of the rows' sets; a.n_items is its upper bound, often several times the
     // count when the sets overlap) that may fall on either side of such a crossover: launches with complementary
     // gates, of which those that do not serve the list leave at once (about 2 us each).  The crossovers that matter:
-    // the one above, and from 33 rows the one between 64 x 64 tiles and larger ones at 64 x CUs items (the tiled
-    // kernel picks its tile by n_items, here the upper end of the gate).  60 rows whose 512 / 1024-item sets unite to
+    // the one above, and from 33 rows the one between small tiles with several workgroups per CU and 64 x 256 tiles
+    // at half a round of those, 128 x CUs items (the tiled kernel picks its tile by n_items, here the upper end of
+    // the gate: 64 x 128; unions of 16 K to 32 K rows gain ~10 us over 64 x 256 tiles, up to 16 K they pay ~3 us
+    // against 64 x 64 tiles -- a gate of their own would cost every other list 2 us).  60 rows whose 512 / 1024-item sets unite to
     // 553 / 1401 rows: whole step 31 / 33 us, against 64 / 66 with the kernel picked by the bound.
     if (a.n_items_dev != nullptr && a.gate_hi == 0 && a.n_items > split_items && a.chunks >= 8 * (kKC / 8)) {
         int64_t cuts[2];
@@ -400,7 +402,7 @@ hipError_t launch_skinny_mfma(const GemvArgs& a, hipStream_t stream) {
         // (a union of duplicate-free sets of k items has at least k: from three quarters of the crossover on, the
         // split form has nothing left to win -- 4096 items 26 us against 35 on one tile, 5120 items 33)
         if (4 * a.n_items_min < 3 * split_items) cuts[ncuts++] = split_items;
-        if (a.rows > 32 && a.n_items > (int64_t)di.cus * 64) cuts[ncuts++] = (int64_t)di.cus * 64;
+        if (a.rows > 32 && a.n_items > (int64_t)di.cus * 128) cuts[ncuts++] = (int64_t)di.cus * 128;
         if (ncuts > 0) {
             GemvArgs part = a;
             for (int c = 0; c < ncuts; ++c) {

@@ -111,8 +111,9 @@ def test_subset_and_dense_logits(dtype, rows, d, V, k, mode):
 
 @pytest.mark.parametrize("rows,d,V,k,pool", [
     (40, 264, 50000, 900, 3000),     # bound 36000, union <= 3000: the launch gated for the reduction-split form serves it
-    (40, 264, 50000, 900, 9000),     # union ~8900: the launch gated for 64 x 64 tiles
-    (40, 264, 50000, 900, 50000),    # union ~26000: the launch picked by the bound, both others leave
+    (40, 264, 50000, 900, 9000),     # union ~8900: the launch gated for small tiles
+    (40, 264, 50000, 900, 50000),    # union ~26000: the same launch, near the upper end of its gate
+    (40, 136, 100000, 2000, 100000), # union ~55000: the launch picked by the bound, both others leave
     (60, 136, 90000, 4096, 4600),    # sets longer than three quarters of the first crossover: that gate is not launched
     (24, 264, 50000, 900, 2500),     # up to 32 rows: one gate
     (24, 264, 50000, 900, 50000),
