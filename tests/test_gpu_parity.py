@@ -110,14 +110,16 @@ def test_subset_and_dense_logits(dtype, rows, d, V, k, mode):
 
 
 @pytest.mark.parametrize("rows,d,V,k,pool", [
-    (40, 264, 50000, 900, 3000),     # bound 36000, union <= 3000: the launch gated for the reduction-split form serves it
-    (40, 264, 50000, 900, 9000),     # union ~8900: the launch gated for small tiles
-    (40, 264, 50000, 900, 50000),    # union ~26000: the same launch, near the upper end of its gate
-    (40, 136, 100000, 2000, 100000), # union ~55000: the launch picked by the bound, both others leave
-    (60, 136, 90000, 4096, 4600),    # sets longer than three quarters of the first crossover: that gate is not launched
-    (24, 264, 50000, 900, 2500),     # up to 32 rows: one gate
-    (24, 264, 50000, 900, 50000),
-    (8, 4096, 40000, 8192, 9000),    # few rows, 512 MB of pairs: union path with the gates of 8 rows
+    # (the gates are for reductions of 2048 elements and more, which the reduction-split form takes)
+    (40, 2048, 50000, 900, 3000),     # bound 36000, union <= 3000: the launch gated for the reduction-split form serves it
+    (40, 2048, 50000, 900, 9000),     # union ~8900: the launch gated for small tiles
+    (40, 2048, 50000, 900, 50000),    # union ~26000: the same launch, near the upper end of its gate
+    (40, 2048, 100000, 2000, 100000), # union ~55000: the launch picked by the bound, both others leave
+    (60, 2048, 90000, 4096, 4600),    # sets longer than three quarters of the first crossover: that gate is not launched
+    (24, 2048, 50000, 900, 2500),     # up to 32 rows: one gate
+    (24, 2048, 50000, 900, 50000),
+    (8, 4096, 40000, 8192, 9000),     # few rows, 512 MB of pairs: union path with the gates of 8 rows
+    (40, 264, 50000, 900, 3000),      # a short reduction: no gates, the kernel that the bound picks
 ])
 def test_union_size_known_on_device_only(rows, d, V, k, pool):
     """One set per row whose union is much smaller than rows x k (or not): whichever gated launch serves it,
