@@ -83,6 +83,7 @@ LOGIT_SHAPES = [
     ("bf16", 50, 264, 6000, 5500, "per_step"),   # 33 to 64 rows, up to 64 x CUs items: 64 x 64 tiles
     ("bf16", 20, 64, 100000, 95000, "per_step"), # 17 to 32 rows, a long list: back on the kernel without LDS tiles
     ("bf16", 60, 136, 45001, 44000, "per_step"), # 64-row tiles whose width follows the list's length (192 of 256 items), ragged last tile
+    ("bf16", 40, 2368, 9000, 6000, "per_step"),  # 37 slices: the other stride between the workgroups' starts in the rotated walk
     ("bf16", 40, 264, 12000, 900, "per_row"),    # union of 40 sets, at most 12000 rows: 64 x 64 tiles with the count on the device
     ("bf16", 48, 136, 30000, 1500, "per_row"),   # ... at most 30000 rows: 64 x 128 tiles
 ]
