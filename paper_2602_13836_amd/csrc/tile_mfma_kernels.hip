@@ -162,9 +162,9 @@ __global__ __launch_bounds__(64 * GM * GN) void tile_mfma_kernel(const GemvArgs 
     // Workgroups walk the reduction in rotated order (slice ks of the walk is slice eff(ks) of the rows): rows a
     // power of two apart put the same offset of every row on the same memory channels, and workgroups that all
     // start at offset 0 keep hitting the same channels together.  With one tile of hidden rows (up to 128)
-    // consecutive workgroups of one XCD start 37 slices apart (modulo the number of slices): the
-    // starts of even a few dozen workgroups -- a launch of one
-    // workgroup per CU has 32 slots per XCD -- then spread over the whole row.  With starts one slice apart such a
+    // consecutive workgroups of one XCD start 37 slices apart (modulo the number of slices): the starts of even a
+    // few dozen workgroups -- a launch of one workgroup per CU has 32 slots per XCD -- then spread over the whole
+    // row.  With starts one slice apart such a
     // launch kept all its workgroups within the same 4 KB of their rows at any time: 60 rows x 50200 gathered
     // rows of 8 KB 97 us against 88, x 65536 117 against 105, all 128256 rows 201 against 192-194 (rows padded
     // to 8320 bytes had shown the same gain, which is how the channels were found out).
